@@ -1,0 +1,312 @@
+/*
+ * CPU oracle for the LLM.int8() mixed-precision decomposition matmul
+ * (arXiv 2208.07339, Section 3: vector-wise quantization, Eq. 7, and
+ * mixed-precision decomposition, Eq. 8; absmax quantization, Section 2.1).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a slow, plain restatement of the method
+ * used only to check the GPU library and to be timed as a CPU baseline.  It
+ * shares no code with the GPU path and the GPU path never calls it.
+ *
+ * Conventions
+ *   - fp16 values travel as their IEEE binary16 bit patterns (uint16_t) and
+ *     are decoded/encoded by the two helpers below, written from the format
+ *     definition (1 sign, 5 exponent, 10 fraction bits, bias 15).
+ *   - X is [s x h] row-major, W is [h x o] row-major, as in the problem
+ *     statement above Eq. 6 (s tokens, h features, o outputs).
+ *   - A "constant" c_x / c_w is stored as the absolute maximum itself (an
+ *     exact fp16 value); the paper's multiplier is 127 / absmax, so the
+ *     denormalisation term S of Eq. 7 is c_x * c_w / 127^2 elementwise.
+ *   - All floating point arithmetic is double precision with one rounding to
+ *     fp16 at the very end.
+ *
+ * Pins (tests/test_oracle_*.py): fp16 helpers against every bit pattern,
+ * Q() against pure-integer rational arithmetic, the integer GEMM against a
+ * triple loop and closed forms, alpha = 0 against a float64 library matmul,
+ * alpha = inf against Eq. 7 alone, the half-step error bound of rounding to
+ * nearest.  Numbers printed by the paper: none exist for this path, so
+ * end-to-end agreement with the authors' own runs is unpinned.
+ */
+#include <fenv.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- IEEE binary16 <-> double ------------------------------------------ */
+
+/* value = (-1)^sign * 2^(e-15) * (1 + f/1024) for 0 < e < 31,
+ *         (-1)^sign * 2^-14 * (f/1024)         for e == 0,
+ *         inf / nan                             for e == 31.              */
+double oracle_f16_to_double(uint16_t bits)
+{
+    int sign = (bits >> 15) & 1;
+    int e = (bits >> 10) & 0x1f;
+    int f = bits & 0x3ff;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -24);
+    else if (e == 31)
+        v = f ? NAN : INFINITY;
+    else
+        v = ldexp((double)(1024 + f), e - 25);
+    return sign ? -v : v;
+}
+
+/* round-to-nearest, ties-to-even; magnitudes that round past 65504 become
+ * infinity, as IEEE 754 prescribes.                                          */
+uint16_t oracle_double_to_f16(double v)
+{
+    uint16_t sign = signbit(v) ? 0x8000u : 0u;
+    double a = fabs(v);
+    if (isnan(v))
+        return (uint16_t)(sign | 0x7e00u);
+    if (isinf(v))
+        return (uint16_t)(sign | 0x7c00u);
+    if (a == 0.0)
+        return sign;
+    int ex;
+    (void)frexp(a, &ex); /* a = m * 2^ex, 0.5 <= m < 1  =>  2^(ex-1) <= a   */
+    int e = ex - 1;       /* unbiased exponent of a                          */
+    if (e < -14)
+        e = -14;          /* subnormal range: fixed quantum 2^-24            */
+    /* quantum (spacing of fp16 values at this exponent) is 2^(e-10)         */
+    double scaled = ldexp(a, 10 - e); /* exact: power-of-two scaling         */
+    double r = nearbyint(scaled);     /* current mode is round-to-nearest-even */
+    /* r is in [0, 2048]; r == 2048 means the mantissa carried               */
+    long n = (long)r;
+    if (n == 2048) {
+        n = 1024;
+        e += 1;
+    }
+    if (n >= 1024) { /* normal */
+        if (e > 15)
+            return (uint16_t)(sign | 0x7c00u);
+        return (uint16_t)(sign | ((uint16_t)(e + 15) << 10) | (uint16_t)(n - 1024));
+    }
+    /* subnormal (e == -14, n < 1024)                                         */
+    return (uint16_t)(sign | (uint16_t)n);
+}
+
+/* ---- absmax quantizer, Section 2.1 ------------------------------------- */
+
+/* Q(x, c) = nearest integer to 127 * x / c, ties to even; 0 when c == 0.
+ * 127 * x is exact in double (x has 11 significant bits); the division is
+ * correctly rounded, a half-integer quotient is representable and therefore
+ * produced exactly, and nearbyint() then applies ties-to-even.               */
+int oracle_q(double x, double c)
+{
+    if (c == 0.0)
+        return 0;
+    return (int)nearbyint(127.0 * x / c);
+}
+
+/* ---- step 1: outlier feature dimensions, Section 3.2 -------------------- */
+
+/* O = ascending list of feature columns j with |X[i][j]| >= alpha for at
+ * least one row i.  Returns |O|; writes at most cap indices.                 */
+int oracle_find_outliers(const uint16_t *X, int s, int h, double alpha, int32_t *idx, int cap)
+{
+    int count = 0;
+    for (int j = 0; j < h; j++) {
+        int hit = 0;
+        for (int i = 0; i < s && !hit; i++)
+            if (fabs(oracle_f16_to_double(X[(size_t)i * h + j])) >= alpha)
+                hit = 1;
+        if (hit) {
+            if (count < cap)
+                idx[count] = j;
+            count++;
+        }
+    }
+    return count;
+}
+
+/* ---- step 2: weights, one constant per output column (Section 3.1) ------ */
+
+void oracle_quantize_weight(const uint16_t *W, int h, int o, int8_t *Wq, uint16_t *cw)
+{
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < o; j++) {
+        double m = 0.0;
+        uint16_t mb = 0;
+        for (int k = 0; k < h; k++) {
+            double a = fabs(oracle_f16_to_double(W[(size_t)k * o + j]));
+            if (a > m) {
+                m = a;
+                mb = (uint16_t)(W[(size_t)k * o + j] & 0x7fffu);
+            }
+        }
+        cw[j] = mb;
+        for (int k = 0; k < h; k++)
+            Wq[(size_t)k * o + j] = (int8_t)oracle_q(oracle_f16_to_double(W[(size_t)k * o + j]), m);
+    }
+}
+
+/* ---- step 3: hidden states, one constant per row over non-outlier columns */
+
+void oracle_quantize_rows(const uint16_t *X, int s, int h, const int32_t *idx, int count,
+                          int8_t *Xq, uint16_t *cx)
+{
+    uint8_t *is_out = (uint8_t *)calloc((size_t)h, 1);
+    for (int t = 0; t < count; t++)
+        is_out[idx[t]] = 1;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < s; i++) {
+        double m = 0.0;
+        uint16_t mb = 0;
+        for (int j = 0; j < h; j++) {
+            if (is_out[j])
+                continue;
+            double a = fabs(oracle_f16_to_double(X[(size_t)i * h + j]));
+            if (a > m) {
+                m = a;
+                mb = (uint16_t)(X[(size_t)i * h + j] & 0x7fffu);
+            }
+        }
+        cx[i] = mb;
+        for (int j = 0; j < h; j++)
+            Xq[(size_t)i * h + j] =
+                is_out[j] ? (int8_t)0 : (int8_t)oracle_q(oracle_f16_to_double(X[(size_t)i * h + j]), m);
+    }
+    free(is_out);
+}
+
+/* ---- step 4: integer product with 32-bit accumulation (Eq. 7) ----------- */
+
+/* C[i][j] = sum_k Xq[i][k] * Wq[k][j].  The k loop sits outside the j loop so
+ * that memory is walked along rows; integer addition is exact in any order.
+ * Accumulates in 64 bits and reports whether every sum fits in int32.
+ * Returns 0 on success, 1 if some accumulator left the int32 range.          */
+int oracle_igemm(const int8_t *Xq, const int8_t *Wq, int s, int h, int o, int32_t *C)
+{
+    int overflow = 0;
+#pragma omp parallel for schedule(static) reduction(| : overflow)
+    for (int i = 0; i < s; i++) {
+        int64_t *acc = (int64_t *)calloc((size_t)o, sizeof(int64_t));
+        for (int k = 0; k < h; k++) {
+            int64_t a = Xq[(size_t)i * h + k];
+            for (int j = 0; j < o; j++)
+                acc[j] += a * (int64_t)Wq[(size_t)k * o + j];
+        }
+        for (int j = 0; j < o; j++) {
+            if (acc[j] > INT32_MAX || acc[j] < INT32_MIN)
+                overflow = 1;
+            C[(size_t)i * o + j] = (int32_t)acc[j];
+        }
+        free(acc);
+    }
+    return overflow;
+}
+
+/* ---- steps 5 + 6: dequantize and add the 16-bit outlier product (Eq. 8) - */
+
+void oracle_output(const int32_t *C, const uint16_t *cx, const uint16_t *cw, const uint16_t *X,
+                   const uint16_t *W, const int32_t *idx, int count, int s, int h, int o,
+                   uint16_t *Out)
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < s; i++) {
+        double *acc = (double *)calloc((size_t)o, sizeof(double));
+        for (int t = 0; t < count; t++) {
+            int k = idx[t];
+            double x = oracle_f16_to_double(X[(size_t)i * h + k]);
+            for (int j = 0; j < o; j++)
+                acc[j] += x * oracle_f16_to_double(W[(size_t)k * o + j]);
+        }
+        double ci = oracle_f16_to_double(cx[i]);
+        for (int j = 0; j < o; j++) {
+            double d = (double)C[(size_t)i * o + j] * ci * oracle_f16_to_double(cw[j]) / 16129.0;
+            Out[(size_t)i * o + j] = oracle_double_to_f16(d + acc[j]);
+        }
+        free(acc);
+    }
+}
+
+/* ---- the whole forward call ---------------------------------------------- */
+
+/* Runs steps 1-6 on rows [0, s) of X.  Every output buffer is caller-owned.
+ * idx must hold h entries (|O| can be as large as h).  Returns |O|, or -1 if
+ * an int32 accumulator overflowed, or -2 if an input is not finite.          */
+int oracle_linear(const uint16_t *X, const uint16_t *W, int s, int h, int o, double alpha,
+                  int32_t *idx, int8_t *Xq, uint16_t *cx, int8_t *Wq, uint16_t *cw, int32_t *C,
+                  uint16_t *Out)
+{
+    for (size_t n = 0; n < (size_t)s * h; n++)
+        if ((X[n] & 0x7c00u) == 0x7c00u)
+            return -2;
+    for (size_t n = 0; n < (size_t)h * o; n++)
+        if ((W[n] & 0x7c00u) == 0x7c00u)
+            return -2;
+    int count = oracle_find_outliers(X, s, h, alpha, idx, h);
+    oracle_quantize_weight(W, h, o, Wq, cw);
+    oracle_quantize_rows(X, s, h, idx, count, Xq, cx);
+    if (oracle_igemm(Xq, Wq, s, h, o, C))
+        return -1;
+    oracle_output(C, cx, cw, X, W, idx, count, s, h, o, Out);
+    return count;
+}
+
+/* ---- single outputs of a large problem ------------------------------------ */
+
+/* Computes Out[i][j] and C[i][j] for n listed (i, j) pairs from the definition,
+ * given the outlier set of the full X.  Each pair costs O(h): the row constant
+ * of row i, the column constant of column j, then the two sums of Eq. 8.      */
+void oracle_sampled(const uint16_t *X, const uint16_t *W, int s, int h, int o, const int32_t *idx,
+                    int count, const int32_t *rows, const int32_t *cols, int n, int32_t *C_out,
+                    uint16_t *Out_out)
+{
+    (void)s;
+    uint8_t *is_out = (uint8_t *)calloc((size_t)h, 1);
+    for (int t = 0; t < count; t++)
+        is_out[idx[t]] = 1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int p = 0; p < n; p++) {
+        int i = rows[p], j = cols[p];
+        double mx = 0.0, mw = 0.0;
+        for (int k = 0; k < h; k++) {
+            double w = fabs(oracle_f16_to_double(W[(size_t)k * o + j]));
+            if (w > mw)
+                mw = w;
+            if (is_out[k])
+                continue;
+            double x = fabs(oracle_f16_to_double(X[(size_t)i * h + k]));
+            if (x > mx)
+                mx = x;
+        }
+        int64_t acc = 0;
+        double hi = 0.0;
+        for (int k = 0; k < h; k++) {
+            double x = oracle_f16_to_double(X[(size_t)i * h + k]);
+            double w = oracle_f16_to_double(W[(size_t)k * o + j]);
+            if (is_out[k])
+                hi += x * w;
+            else
+                acc += (int64_t)oracle_q(x, mx) * (int64_t)oracle_q(w, mw);
+        }
+        C_out[p] = (int32_t)acc;
+        Out_out[p] = oracle_double_to_f16((double)acc * mx * mw / 16129.0 + hi);
+    }
+    free(is_out);
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
