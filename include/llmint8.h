@@ -1,0 +1,126 @@
+/*
+ * llmint8 -- LLM.int8() mixed-precision decomposition matmul for one MI355X
+ * (gfx950), arXiv 2208.07339.
+ *
+ * Problem statement (Section 2.1, above Eq. 6; Section 3): hidden states
+ * X_f16 [s x h] (s tokens, h features), weights W_f16 [h x o], threshold alpha;
+ * result C_f16 [s x o] approximating X W by Eq. 8:
+ *
+ *     C = sum_{k in O} X_f16[:,k] W_f16[k,:]  +  S * sum_{k not in O} X_i8[:,k] W_i8[k,:]
+ *
+ * with O the feature columns of X holding any |x| >= alpha (Section 3.2),
+ * X_i8 / W_i8 the absmax codes (Section 2.1) with one constant per row of X
+ * and one per column of W (vector-wise quantization, Section 3.1, Eq. 7), and
+ * S the outer product of those constants over 127^2.
+ *
+ * Conventions
+ *   - Every matrix/vector pointer is a DEVICE pointer owned by the caller.
+ *     fp16 data is IEEE binary16, passed as (const) void*.  X, W, Out are
+ *     dense row-major.  Inputs must be finite; with NaN/Inf the results are
+ *     unspecified (no fault).
+ *   - "Constants" c_x, c_w are stored as the absolute maximum itself (an fp16
+ *     value); the paper's multiplier is 127 / absmax.
+ *   - Xq and Wq are PRIVATE tiled layouts (see llmint8_xq_bytes /
+ *     llmint8_wq_bytes); llmint8_export_rows / llmint8_export_weight turn
+ *     them into plain row-major int8 matrices.
+ *   - stream is a hipStream_t (NULL = the default stream).  Every call only
+ *     enqueues kernels on it: no host synchronisation, no allocation, no
+ *     global state.  Calls that share a workspace must be ordered by stream.
+ *   - Return value: LLMINT8_OK or an error code below; nothing is enqueued
+ *     when an argument error is returned.  Conditions only visible on the
+ *     device (|O| > cap) set bit 0 of the device status word and clamp.
+ */
+#ifndef LLMINT8_H
+#define LLMINT8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    LLMINT8_OK = 0,
+    LLMINT8_INVALID_ARG = 1, /* null pointer, non-positive dimension, cap < 1 */
+    LLMINT8_SHAPE = 2,       /* h > LLMINT8_MAX_H, or a size beyond 2^31 elements per row block */
+    LLMINT8_WORKSPACE = 3,   /* workspace smaller than llmint8_workspace_bytes() */
+    LLMINT8_HIP = 4          /* a kernel launch failed (hipGetLastError) */
+};
+
+/* Largest feature dimension whose int32 accumulator cannot overflow:
+ * h * 127^2 <= 2^31 - 1 (Section 2.1: outputs are accumulated as int32). */
+#define LLMINT8_MAX_H 133144
+
+typedef void *llmint8_stream_t;
+
+const char *llmint8_status_string(int status);
+
+/* Leading dimension (in fp16 elements) of the gathered-outlier matrix Xo for a
+ * given capacity: cap rounded up to a multiple of 16. */
+int llmint8_opad(int cap);
+
+/* Bytes of the private int8 buffers.  Wq: ceil(o/32) x ceil(h/128)*4 tiles of
+ * 1 KiB; Xq: ceil(s/32) x ceil(h/128)*4 tiles.  A tile holds 32 rows (output
+ * columns of W, or tokens of X) by 32 consecutive features; padding is zero. */
+size_t llmint8_wq_bytes(int h, int o);
+size_t llmint8_xq_bytes(int s, int h);
+
+/* Bytes of scratch any of the calls below may need for these sizes. */
+size_t llmint8_workspace_bytes(int s, int h, int o, int cap);
+
+/* Section 3.1 / Section 2.1, done once per weight ("converted to Int8 and
+ * used immediately"): c_w[j] = max_k |W[k][j]| over all h rows,
+ * W_i8[k][j] = round-half-even(127 W[k][j] / c_w[j]) (0 where c_w[j] = 0).
+ *   W_f16  in   [h x o] fp16
+ *   Wq     out  llmint8_wq_bytes(h, o) bytes, private layout
+ *   cw_f16 out  [o] fp16                                                     */
+int llmint8_quantize_weight(const void *W_f16, int h, int o, int8_t *Wq, void *cw_f16, void *ws,
+                            size_t ws_bytes, llmint8_stream_t stream);
+
+/* Section 3.2: O = { j : max_i |X[i][j]| >= alpha }, ascending.
+ *   idx    out  [cap] int32, first min(|O|, cap) entries valid
+ *   count  out  int32 = min(|O|, cap)
+ *   status out  int32, bit 0 set iff |O| > cap (may be NULL)                 */
+int llmint8_find_outliers(const void *X_f16, int s, int h, float alpha, int32_t *idx, int cap,
+                          int32_t *count, int32_t *status, void *ws, size_t ws_bytes,
+                          llmint8_stream_t stream);
+
+/* Section 3.1 applied to the non-outlier part of X (Eq. 8 sums the int8 product
+ * over k not in O): c_x[i] = max_{j not in O} |X[i][j]|,
+ * X_i8[i][j] = round-half-even(127 X[i][j] / c_x[i]) for j not in O and 0 for
+ * j in O; Xo[i][t] = X[i][O_t] for t < |O| and 0 for |O| <= t < opad.
+ *   idx, count  in   as written by llmint8_find_outliers (device)
+ *   Xq     out  llmint8_xq_bytes(s, h) bytes, private layout
+ *   cx_f16 out  [s] fp16
+ *   Xo_f16 out  [s x llmint8_opad(cap)] fp16                                 */
+int llmint8_quantize_rows(const void *X_f16, int s, int h, const int32_t *idx, const int32_t *count,
+                          int cap, int8_t *Xq, void *cx_f16, void *Xo_f16, llmint8_stream_t stream);
+
+/* Eq. 7 + Eq. 8: C_i32 = X_i8 W_i8 (int32 accumulation),
+ * Out = fp16( C_i32 * c_x (x) c_w / 127^2 + Xo W_f16[O,:] ), the outlier product
+ * accumulated in fp32.  Token counts s <= 32 take a weight-streaming path.
+ *   W_f16       in   the original weights; only rows O are read
+ *   Out_f16     out  [s x o] fp16
+ *   C_i32_debug out  NULL, or [s x o] int32 receiving the raw accumulators   */
+int llmint8_matmul(const int8_t *Xq, const void *cx_f16, const void *Xo_f16, const int32_t *idx,
+                   const int32_t *count, int cap, const int8_t *Wq, const void *cw_f16,
+                   const void *W_f16, int s, int h, int o, void *Out_f16, int32_t *C_i32_debug,
+                   void *ws, size_t ws_bytes, llmint8_stream_t stream);
+
+/* The per-call sequence find_outliers -> quantize_rows -> matmul on one stream.
+ * Xq, cx_f16, Xo_f16, idx, count, status are caller-provided scratch/outputs
+ * of the sizes given above.                                                   */
+int llmint8_linear(const void *X_f16, int s, int h, float alpha, const int8_t *Wq, const void *cw_f16,
+                   const void *W_f16, int o, int32_t *idx, int cap, int32_t *count, int32_t *status,
+                   int8_t *Xq, void *cx_f16, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
+                   llmint8_stream_t stream);
+
+/* Test/support: private layouts -> plain row-major int8 ([h x o], [s x h]). */
+int llmint8_export_weight(const int8_t *Wq, int h, int o, int8_t *W_i8_rowmajor, llmint8_stream_t stream);
+int llmint8_export_rows(const int8_t *Xq, int s, int h, int8_t *X_i8_rowmajor, llmint8_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LLMINT8_H */

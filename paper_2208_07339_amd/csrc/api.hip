@@ -1,0 +1,161 @@
+// C-ABI entry points of libllmint8: argument checks, workspace carving and the
+// kernel sequences.  Declarations and argument contracts: include/llmint8.h.
+#include "../../include/llmint8.h"
+#include "common.h"
+
+using namespace llmint8;
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+inline void* ws_base(void* ws) { return (void*)align_up((uintptr_t)ws, 256); }
+
+inline size_t outlier_ws(int s, int h) { return align_up((size_t)colmax_slabs(s, h) * h * 2, 256); }
+inline size_t weight_ws(int h, int o) { return align_up((size_t)colmax_slabs(h, o) * o * 2, 256); }
+inline size_t matmul_ws(int o, int cap) { return align_up((size_t)row_tiles(o) * 32 * opad_of(cap) * 2, 256); }
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? LLMINT8_OK : LLMINT8_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char* llmint8_status_string(int status)
+{
+    switch (status) {
+        case LLMINT8_OK: return "ok";
+        case LLMINT8_INVALID_ARG: return "invalid argument (null or misaligned pointer, non-positive size)";
+        case LLMINT8_SHAPE: return "unsupported shape (feature dimension above the int32 accumulation bound)";
+        case LLMINT8_WORKSPACE: return "workspace too small";
+        case LLMINT8_HIP: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+int llmint8_opad(int cap) { return cap < 1 ? 0 : opad_of(cap); }
+
+size_t llmint8_wq_bytes(int h, int o)
+{
+    if (h < 1 || o < 1) return 0;
+    return (size_t)row_tiles(o) * k_tiles(h) * TILE_BYTES;
+}
+
+size_t llmint8_xq_bytes(int s, int h)
+{
+    if (s < 1 || h < 1) return 0;
+    return (size_t)row_tiles(s) * k_tiles(h) * TILE_BYTES;
+}
+
+size_t llmint8_workspace_bytes(int s, int h, int o, int cap)
+{
+    if (s < 1 || h < 1 || o < 1 || cap < 1) return 0;
+    size_t a = outlier_ws(s, h), b = weight_ws(h, o), c = matmul_ws(o, cap);
+    size_t m = a > b ? a : b;
+    m = m > c ? m : c;
+    return m + 256;  // slack to align the caller's pointer
+}
+
+int llmint8_quantize_weight(const void* W_f16, int h, int o, int8_t* Wq, void* cw_f16, void* ws, size_t ws_bytes,
+                            llmint8_stream_t stream)
+{
+    if (!W_f16 || !Wq || !cw_f16 || !ws || h < 1 || o < 1) return LLMINT8_INVALID_ARG;
+    if (misaligned(W_f16, 2) || misaligned(Wq, 16) || misaligned(cw_f16, 8)) return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
+    if (ws_bytes < weight_ws(h, o) + 256) return LLMINT8_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned short* part = (unsigned short*)ws_base(ws);
+    const int nslab = colmax_slabs(h, o);
+    hipError_t e = launch_colmax_partial(W_f16, h, o, part, nslab, st);
+    if (e == hipSuccess) e = launch_colmax_final(part, nslab, o, (unsigned short*)cw_f16, st);
+    if (e == hipSuccess) e = launch_quantize_weight(W_f16, h, o, (const unsigned short*)cw_f16, Wq, st);
+    return hip_status(e);
+}
+
+int llmint8_find_outliers(const void* X_f16, int s, int h, float alpha, int32_t* idx, int cap, int32_t* count,
+                          int32_t* status, void* ws, size_t ws_bytes, llmint8_stream_t stream)
+{
+    if (!X_f16 || !idx || !count || !ws || s < 1 || h < 1 || cap < 1) return LLMINT8_INVALID_ARG;
+    if (misaligned(X_f16, 2) || misaligned(idx, 4) || misaligned(count, 4) || misaligned(status, 4))
+        return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
+    if (ws_bytes < outlier_ws(s, h) + 256) return LLMINT8_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned short* part = (unsigned short*)ws_base(ws);
+    const int nslab = colmax_slabs(s, h);
+    hipError_t e = launch_colmax_partial(X_f16, s, h, part, nslab, st);
+    if (e == hipSuccess)
+        e = launch_outlier_compact(part, nslab, h, threshold_bits(alpha), idx, cap, count, status, st);
+    return hip_status(e);
+}
+
+int llmint8_quantize_rows(const void* X_f16, int s, int h, const int32_t* idx, const int32_t* count, int cap,
+                          int8_t* Xq, void* cx_f16, void* Xo_f16, llmint8_stream_t stream)
+{
+    if (!X_f16 || !idx || !count || !Xq || !cx_f16 || !Xo_f16 || s < 1 || h < 1 || cap < 1)
+        return LLMINT8_INVALID_ARG;
+    if (misaligned(X_f16, 2) || misaligned(idx, 4) || misaligned(count, 4) || misaligned(Xq, 16) ||
+        misaligned(cx_f16, 2) || misaligned(Xo_f16, 16))
+        return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
+    return hip_status(launch_quantize_rows(X_f16, s, h, idx, count, cap, Xq, (unsigned short*)cx_f16,
+                                           (unsigned short*)Xo_f16, (hipStream_t)stream));
+}
+
+int llmint8_matmul(const int8_t* Xq, const void* cx_f16, const void* Xo_f16, const int32_t* idx,
+                   const int32_t* count, int cap, const int8_t* Wq, const void* cw_f16, const void* W_f16, int s,
+                   int h, int o, void* Out_f16, int32_t* C_i32_debug, void* ws, size_t ws_bytes,
+                   llmint8_stream_t stream)
+{
+    if (!Xq || !cx_f16 || !Xo_f16 || !idx || !count || !Wq || !cw_f16 || !W_f16 || !Out_f16 || !ws || s < 1 ||
+        h < 1 || o < 1 || cap < 1)
+        return LLMINT8_INVALID_ARG;
+    if (misaligned(Xq, 16) || misaligned(Wq, 16) || misaligned(Xo_f16, 16) || misaligned(cw_f16, 8) ||
+        misaligned(cx_f16, 2) || misaligned(W_f16, 2) || misaligned(Out_f16, 8) || misaligned(idx, 4) ||
+        misaligned(count, 4) || misaligned(C_i32_debug, 4))
+        return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
+    if (ws_bytes < matmul_ws(o, cap) + 256) return LLMINT8_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned short* Wo = (unsigned short*)ws_base(ws);
+    hipError_t e = launch_gather_w(W_f16, o, idx, count, cap, Wo, st);
+    if (e != hipSuccess) return LLMINT8_HIP;
+    if (s <= 32)
+        e = launch_gemm_decode(Xq, (const unsigned short*)cx_f16, (const unsigned short*)Xo_f16, count, cap, Wq,
+                               (const unsigned short*)cw_f16, Wo, s, h, o, (unsigned short*)Out_f16, C_i32_debug,
+                               st);
+    else
+        e = launch_gemm_prefill(Xq, (const unsigned short*)cx_f16, (const unsigned short*)Xo_f16, count, cap, Wq,
+                                (const unsigned short*)cw_f16, Wo, s, h, o, (unsigned short*)Out_f16, C_i32_debug,
+                                st);
+    return hip_status(e);
+}
+
+int llmint8_linear(const void* X_f16, int s, int h, float alpha, const int8_t* Wq, const void* cw_f16,
+                   const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status, int8_t* Xq,
+                   void* cx_f16, void* Xo_f16, void* Out_f16, void* ws, size_t ws_bytes, llmint8_stream_t stream)
+{
+    int r = llmint8_find_outliers(X_f16, s, h, alpha, idx, cap, count, status, ws, ws_bytes, stream);
+    if (r != LLMINT8_OK) return r;
+    // validate the remaining arguments before anything else is enqueued
+    if (!Wq || !cw_f16 || !W_f16 || !Out_f16 || o < 1) return LLMINT8_INVALID_ARG;
+    if (ws_bytes < llmint8_workspace_bytes(s, h, o, cap)) return LLMINT8_WORKSPACE;
+    r = llmint8_quantize_rows(X_f16, s, h, idx, count, cap, Xq, cx_f16, Xo_f16, stream);
+    if (r != LLMINT8_OK) return r;
+    return llmint8_matmul(Xq, cx_f16, Xo_f16, idx, count, cap, Wq, cw_f16, W_f16, s, h, o, Out_f16, nullptr, ws,
+                          ws_bytes, stream);
+}
+
+int llmint8_export_weight(const int8_t* Wq, int h, int o, int8_t* W_i8_rowmajor, llmint8_stream_t stream)
+{
+    if (!Wq || !W_i8_rowmajor || h < 1 || o < 1 || misaligned(Wq, 16)) return LLMINT8_INVALID_ARG;
+    return hip_status(launch_export_tiled(Wq, o, h, W_i8_rowmajor, 0, (hipStream_t)stream));
+}
+
+int llmint8_export_rows(const int8_t* Xq, int s, int h, int8_t* X_i8_rowmajor, llmint8_stream_t stream)
+{
+    if (!Xq || !X_i8_rowmajor || s < 1 || h < 1 || misaligned(Xq, 16)) return LLMINT8_INVALID_ARG;
+    return hip_status(launch_export_tiled(Xq, s, h, X_i8_rowmajor, 1, (hipStream_t)stream));
+}
+
+}  // extern "C"

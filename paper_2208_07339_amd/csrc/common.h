@@ -1,0 +1,79 @@
+// Shared declarations of the gfx950 kernels: tile layout of the private int8
+// buffers, fp16 bit helpers, launcher prototypes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace llmint8 {
+
+// ---- private int8 layout ---------------------------------------------------
+// A matrix M[rows][K] of int8 (rows = tokens of X, or output columns of W;
+// K = features) is cut into tiles of 32 rows x 32 features.  A tile is 1 KiB
+// stored in the operand order of v_mfma_i32_32x32x32_i8: lane l of a wave
+// holds row (l % 32), features 16*(l / 32) .. +15, so byte (r, kk) of a tile
+// sits at ((kk >> 4) * 32 + r) * 16 + (kk & 15).  Tiles of one row block are
+// consecutive along K: tile (rt, kt) starts at (rt * KT + kt) * 1024 with
+// KT = 4 * ceil(h / 128).  Rows and features beyond the matrix are zero.
+constexpr int TILE = 32;
+constexpr int TILE_BYTES = 1024;
+
+__host__ __device__ inline int k_tiles(int h) { return 4 * ((h + 127) / 128); }
+__host__ __device__ inline int row_tiles(int n) { return (n + 31) / 32; }
+__host__ __device__ inline int tile_byte(int r, int kk) { return (((kk >> 4) << 5) + r) * 16 + (kk & 15); }
+__host__ __device__ inline int opad_of(int cap) { return (cap + 15) & ~15; }
+
+// ---- fp16 as bit patterns ----------------------------------------------------
+// For finite values the magnitude order of binary16 equals the integer order
+// of (bits & 0x7fff), so absolute maxima and the threshold test are done on
+// integers and are exact.
+__device__ inline float f16_bits_to_float(unsigned short b)
+{
+    return (float)__builtin_bit_cast(_Float16, b);  // exact widening
+}
+
+// Smallest magnitude bit pattern whose value is >= alpha (0 if alpha <= 0,
+// 0x7c00 if no finite fp16 reaches alpha).
+__host__ inline unsigned threshold_bits(float alpha)
+{
+    if (!(alpha > 0.0f)) return 0u;            // alpha <= 0 (or NaN): every column qualifies
+    if (alpha > 65504.0f) return 0x7c00u;      // above the largest finite fp16
+    // binary search over the 0x7c00 non-negative finite patterns
+    unsigned lo = 0, hi = 0x7bff;              // invariant: value(hi) >= alpha
+    while (lo < hi) {
+        unsigned mid = (lo + hi) / 2;
+        unsigned e = mid >> 10, f = mid & 0x3ff;
+        float v = e ? __builtin_ldexpf((float)(1024 + f), (int)e - 25) : __builtin_ldexpf((float)f, -24);
+        if (v >= alpha) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
+// ---- launchers (host side, defined next to their kernels) -------------------
+// All return a hipError_t from hipGetLastError() after the launches.
+
+// partial column maxima of an fp16 matrix M[rows][cols]: part[slab][cols] (u16 magnitude bits)
+int colmax_slabs(int rows, int cols);
+hipError_t launch_colmax_partial(const void* M, int rows, int cols, unsigned short* part, int nslab,
+                                 hipStream_t st);
+hipError_t launch_outlier_compact(const unsigned short* part, int nslab, int h, unsigned thr, int32_t* idx,
+                                  int cap, int32_t* count, int32_t* status, hipStream_t st);
+hipError_t launch_colmax_final(const unsigned short* part, int nslab, int cols, unsigned short* out,
+                               hipStream_t st);
+hipError_t launch_quantize_weight(const void* W, int h, int o, const unsigned short* cw, int8_t* Wq,
+                                  hipStream_t st);
+hipError_t launch_quantize_rows(const void* X, int s, int h, const int32_t* idx, const int32_t* count, int cap,
+                                int8_t* Xq, unsigned short* cx, unsigned short* Xo, hipStream_t st);
+hipError_t launch_export_tiled(const int8_t* T, int rows, int h, int8_t* out, int ld_rows_major,
+                               hipStream_t st);
+hipError_t launch_gather_w(const void* W, int o, const int32_t* idx, const int32_t* count, int cap,
+                           unsigned short* Wo, hipStream_t st);
+hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
+                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
+                               const unsigned short* Wo, int s, int h, int o, unsigned short* Out,
+                               int32_t* Cdbg, hipStream_t st);
+hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
+                              const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
+                              const unsigned short* Wo, int s, int h, int o, unsigned short* Out,
+                              int32_t* Cdbg, hipStream_t st);
+
+}  // namespace llmint8

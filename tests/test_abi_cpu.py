@@ -1,0 +1,56 @@
+"""No-GPU checks of the boundary: the library loads, exports every symbol the
+header declares, and the host-side size functions / argument checks behave."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2208_07339_amd as L
+    if not os.path.exists(L.LIB_PATH):
+        from paper_2208_07339_amd.build import build
+        build()
+    return L.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "llmint8.h")).read()
+    names = set(re.findall(r"\b(llmint8_[a-z0-9_]+)\s*\(", hdr))
+    assert {"llmint8_quantize_weight", "llmint8_find_outliers", "llmint8_quantize_rows", "llmint8_matmul"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2208_07339_amd.binding import SYMBOLS
+    assert set(SYMBOLS) == names
+
+
+def test_size_functions(lib):
+    import paper_2208_07339_amd as L
+    assert L.opad(1) == 16 and L.opad(16) == 16 and L.opad(17) == 32 and L.opad(0) == 0
+    # tiles of 1 KiB: 32 rows x 32 features, features padded to 128
+    assert L.xq_bytes(8, 256) == 1 * 8 * 1024
+    assert L.xq_bytes(33, 200) == 2 * 8 * 1024
+    assert L.wq_bytes(12288, 49152) == 12288 * 49152
+    assert L.wq_bytes(0, 5) == 0
+    assert L.workspace_bytes(16, 12288, 49152, 32) >= 49152 * 32 * 2
+    assert L.workspace_bytes(0, 1, 1, 1) == 0
+
+
+def test_argument_checks_need_no_gpu(lib):
+    assert lib.llmint8_matmul(*([None] * 5), 4, *([None] * 3), 1, 1, 1, None, None, None, 0, None) == 1
+    assert lib.llmint8_quantize_weight(None, 4, 4, None, None, None, 0, None) == 1
+    assert lib.llmint8_status_string(0) == b"ok"
+    assert b"workspace" in lib.llmint8_status_string(3)
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2208_07339_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                txt = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in txt and "from oracle" not in txt and "liboracle" not in txt, f

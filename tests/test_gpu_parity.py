@@ -1,0 +1,181 @@
+"""HIP path vs CPU oracle through the C-ABI, element by element, at sizes the
+oracle finishes in seconds: several tiles, ragged tails, both GEMM paths, and
+the degenerate cases of the method.  Integer stages bit-exact; fp16 output
+within 1e-3 * max|Out|."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2208_07339_amd import workloads as wl
+from gpu_util import assert_out_close, bits, hip_weight_i8, run_hip
+
+pytestmark = pytest.mark.gpu
+
+
+def full_compare(d, alpha=None, cap=32):
+    alpha = d["alpha"] if alpha is None else alpha
+    X, W = d["X"], d["W"]
+    r = oracle.linear(X, W, alpha)
+    g = run_hip(X, W, alpha, cap)
+    assert g["status"] == 0
+    assert g["idx"].tolist() == r["idx"].tolist()
+    assert np.array_equal(bits(g["cw"]), bits(r["cw"]))
+    assert np.array_equal(hip_weight_i8(g["qw"]), r["Wq"])
+    assert np.array_equal(bits(g["cx"]), bits(r["cx"]))
+    assert np.array_equal(g["Xq"], r["Xq"])
+    n = len(r["idx"])
+    assert np.array_equal(bits(g["Xo"][:, :n]), bits(X[:, r["idx"]]))
+    assert not bits(g["Xo"][:, n:]).any()
+    assert np.array_equal(g["C"], r["C"])
+    assert_out_close(g["Out"], r["Out"])
+    return g, r
+
+
+def test_tiny_config():
+    g, r = full_compare(wl.make("tiny"))
+    assert g["idx"].tolist() == [17, 200]
+
+
+@pytest.mark.parametrize("s,h,o,ncol", [
+    (1, 64, 32, 1),          # single token, single tile
+    (16, 1024, 2048, 5),     # decode path, aligned
+    (13, 200, 61, 2),        # decode path, nothing aligned (scalar load/store paths)
+    (32, 384, 96, 3),        # largest decode token count
+    (33, 384, 96, 3),        # smallest prefill token count
+    (300, 1000, 520, 4),     # prefill, two token blocks, three column blocks, ragged everywhere
+    (257, 4160, 264, 6),     # one row into the second block, K not a multiple of 128
+    (512, 2048, 1024, 7),    # aligned multi-block
+])
+def test_shapes_against_full_oracle(s, h, o, ncol):
+    full_compare(wl.make_custom(s, h, o, ncol, seed=s * 7 + o))
+
+
+def test_alpha_zero_is_pure_fp16_matmul_on_both_paths():
+    d = wl.make("tiny")
+    g, r = full_compare(d, alpha=0.0, cap=256)
+    assert g["count"] == 256 and not g["C"].any()
+    d = wl.make_custom(40, 96, 64, 2, seed=5)
+    g, r = full_compare(d, alpha=0.0, cap=96)
+    assert g["count"] == 96
+
+
+def test_alpha_infinity_is_vector_wise_only():
+    d = wl.make("tiny")
+    g, r = full_compare(d, alpha=float("inf"))
+    assert g["count"] == 0
+    full_compare(wl.make_custom(70, 256, 128, 3, seed=9), alpha=1e9)
+
+
+def test_capacity_overflow_sets_status_and_clamps():
+    d = wl.make_custom(48, 512, 96, 9, seed=21)
+    X, W = d["X"], d["W"]
+    full = oracle.find_outliers(X, 6.0)
+    assert len(full) >= 9
+    g = run_hip(X, W, 6.0, cap=4)
+    assert g["status"] == 1 and g["count"] == 4
+    assert g["idx"].tolist() == full[:4].tolist()
+    # the rest of the pipeline treats exactly the reported columns as outliers
+    Xq, cx = oracle.quantize_rows(X, full[:4])
+    assert np.array_equal(g["Xq"], Xq) and np.array_equal(bits(g["cx"]), bits(cx))
+    Wq, cw = oracle.quantize_weight(W)
+    Cm = oracle.igemm(Xq, Wq)
+    assert np.array_equal(g["C"], Cm)
+    assert_out_close(g["Out"], oracle.output(Cm, cx, cw, X, W, full[:4]))
+
+
+def test_zero_rows_and_zero_weight_columns():
+    d = wl.make_custom(40, 256, 96, 2, seed=3)
+    d["X"][5] = 0
+    d["X"][39] = 0
+    d["W"][:, 7] = 0
+    d["W"][:, 95] = 0
+    g, r = full_compare(d)
+    assert g["cx"][5] == 0 and g["cw"][7] == 0
+    assert not g["Out"][5].any() and not g["Out"][:, 7].any()
+
+
+def test_row_made_only_of_outlier_columns():
+    X = np.zeros((34, 64), np.float16)
+    X[:, 3] = 9.0
+    X[1, 10] = 1.0
+    W = wl.make_w(64, 64, seed=8)
+    d = dict(X=X, W=W, alpha=6.0)
+    g, r = full_compare(d)
+    assert g["idx"].tolist() == [3] and g["cx"][0] == 0
+
+
+def test_threshold_boundary_values():
+    X = wl.normal_f16(40, 128, 0.5, 17)
+    X[3, 5] = 6.0
+    X[7, 9] = -6.0
+    X[9, 11] = np.nextafter(np.float16(6.0), np.float16(0))
+    W = wl.make_w(128, 64, seed=18)
+    g, r = full_compare(dict(X=X, W=W, alpha=6.0))
+    assert g["idx"].tolist() == [5, 9]
+
+
+def test_quantizer_sweep_matches_oracle_bit_for_bit():
+    # every mantissa of the row constant in one binade against every smaller magnitude, and
+    # constants in the range real rows have; includes hundreds of exact ties
+    for lo, hi, xmax, neg in [(0x3C00, 0x4000, 0x3FFF, False), (0x4400, 0x4800, 0x47FF, True),
+                              (0x0001, 0x0400, 0x03FF, False), (0x7800, 0x7C00, 0x7BFF, True)]:
+        c = np.arange(lo, hi, dtype=np.int64)
+        cols = np.arange(xmax + 1, dtype=np.int64)
+        X = np.zeros((len(c), xmax + 2), np.uint16)
+        X[:, 0] = c
+        X[:, 1:] = np.where(cols[None, :] <= c[:, None], cols[None, :], 0).astype(np.uint16)
+        if neg:
+            X[:, 1:] |= 0x8000
+        Xf = X.view(np.float16)
+        want, cx = oracle.quantize_rows(Xf, np.zeros(0, np.int32))
+        import torch
+
+        import paper_2208_07339_amd as L
+        Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
+        ws = L.Workspace.allocate(Xd.shape[0], Xd.shape[1], 32, 16)
+        outl = L.find_outliers(Xd, float("inf"), 16, ws)
+        rows = L.quantize_rows(Xd, outl)
+        got = L.export_rows(rows).cpu().numpy()
+        assert np.array_equal(bits(rows.cx.cpu().numpy()), bits(cx))
+        assert np.array_equal(got, want)
+
+
+def test_two_runs_are_bit_identical():
+    d = wl.make_custom(300, 1000, 520, 4, seed=99)
+    a = run_hip(d["X"], d["W"], 6.0, 32)
+    b = run_hip(d["X"], d["W"], 6.0, 32)
+    for k in ("idx", "Xq", "C"):
+        assert np.array_equal(a[k], b[k])
+    assert np.array_equal(bits(a["Out"]), bits(b["Out"]))
+    assert np.array_equal(bits(a["cx"]), bits(b["cx"]))
+
+
+def test_linear_entry_point_matches_step_by_step():
+    import torch
+
+    import paper_2208_07339_amd as L
+    d = wl.make_custom(100, 512, 256, 3, seed=41)
+    g = run_hip(d["X"], d["W"], 6.0, 32, want_c=False)
+    out = L.linear(g["Xd"], g["qw"], 6.0, g["outl"], g["rows"], g["ws"])
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(out.cpu().numpy()), bits(g["Out"]))
+
+
+def test_argument_errors_are_reported_not_executed():
+    import ctypes as C
+
+    import paper_2208_07339_amd as L
+    lib = L.lib()
+    assert lib.llmint8_find_outliers(None, 4, 4, 6.0, None, 4, None, None, None, 0, None) == 1
+    import torch
+    X = torch.zeros((4, 8), dtype=torch.float16, device="cuda")
+    idx = torch.zeros(8, dtype=torch.int32, device="cuda")
+    p = lambda t: C.c_void_p(t.data_ptr())
+    # workspace too small
+    assert lib.llmint8_find_outliers(p(X), 4, 8, 6.0, p(idx), 8, p(idx), None, p(idx), 16, None) == 3
+    # feature dimension above the int32 accumulation bound
+    assert lib.llmint8_find_outliers(p(X), 1, 133145, 6.0, p(idx), 8, p(idx), None, p(idx), 1 << 30, None) == 2
+    # cap < 1
+    assert lib.llmint8_find_outliers(p(X), 4, 8, 6.0, p(idx), 0, p(idx), None, p(idx), 1 << 20, None) == 1
+    with pytest.raises(L.Llmint8Error):
+        L.binding._check(3)
