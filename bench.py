@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Throughput of the LLM.int8() matmul hot path on one MI355X.
+
+A step is one pass of the whole per-call path -- outlier scan, row quantize +
+outlier gather, int8 GEMM with fused dequantization and fp16 outlier product
+-- over one batch of synthetic hidden states already resident in HBM; the
+weights were converted to int8 once, before the timed region (as the method
+prescribes).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Workloads (paper_2208_07339_amd/workloads.py): ffn13b (default headline,
+effective int8 TOPS), decode (HBM GB/s, reported in the same line under
+"decode"), attn6p7b, ffn175b_down.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5033.0   # 256 CU x 8192 int8 op/clk/CU x 2.4 GHz, dense
+HBM_PEAK_GBS = 8000.0
+CAP = 32                       # capacity of the outlier index list
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/*pmc*.txt), or None while not measured.
+MEASURED_TRAFFIC = {}
+
+
+def algorithmic_bytes_decode(s, h, o, n_out):
+    """W_i8 + c_w + Out + outlier rows of W_f16 + X_i8 tile + Xo, per launch of the decode kernel."""
+    return h * o + 2 * o + 2 * s * o + n_out * o * 2 + 32 * h + s * 32 * 2
+
+
+def to_dev(a):
+    import torch
+    return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
+
+
+def run_workload(name, steps, warmup, copies=1):
+    import torch
+
+    import paper_2208_07339_amd as L
+    from paper_2208_07339_amd import workloads as wl
+
+    d = wl.make(name)
+    s, h, o = d["s"], d["h"], d["o"]
+    Xd = to_dev(d["X"])
+    Wd = to_dev(d["W"])
+    ws = L.Workspace.allocate(s, h, o, CAP)
+    t0 = time.perf_counter()
+    qws = [L.quantize_weight(Wd, ws)]
+    torch.cuda.synchronize()
+    t_wq = time.perf_counter() - t0
+    for _ in range(copies - 1):  # rotate weight copies so that no last-level cache flatters a streaming read
+        q = qws[0]
+        qws.append(L.QuantizedWeight(q.Wq.clone(), q.cw.clone(), q.W, q.h, q.o))
+    outl = L.find_outliers(Xd, d["alpha"], CAP, ws)
+    rows = L.quantize_rows(Xd, outl)
+    out = torch.empty((s, o), dtype=torch.float16, device="cuda")
+    torch.cuda.synchronize()
+    n_out = int(outl.count.item())
+
+    def step(i):
+        L.linear(Xd, qws[i % len(qws)], d["alpha"], outl, rows, ws, out)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+
+    # same steps again with HIP events around the dominant kernel (llmint8_matmul is one launch)
+    # and around the two pre-passes, on the stream the library launches on
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    for i in range(steps):
+        evs[i][0].record()
+        L.find_outliers(Xd, d["alpha"], CAP, ws, outl)
+        L.quantize_rows(Xd, outl, rows)
+        evs[i][1].record()
+        L.matmul(rows, outl, qws[i % len(qws)], ws, out)
+        evs[i][2].record()
+    torch.cuda.synchronize()
+    ms_pre = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    ms_mm = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    return dict(name=name, s=s, h=h, o=o, n_out=n_out, planted=len(d["planted"]), ms_step=ms_step,
+                ms_prepass=ms_pre, ms_matmul=ms_mm, weight_quantize_ms=t_wq * 1e3, inputs=d)
+
+
+def cpu_baseline(res, target_seconds=12.0):
+    """The CPU oracle, as it stands, on a bounded sample: the per-call steps (outlier scan, row
+    quantization, integer product, dequantization + outlier product) on the first r rows of X
+    against the full weight matrix, which is quantized beforehand and not timed."""
+    import oracle
+    d = res["inputs"]
+    X, W = d["X"], d["W"]
+    s, h, o = res["s"], res["h"], res["o"]
+    Wq, cw = oracle.quantize_weight(W)
+    # calibrate the sample size on a couple of rows
+    r = min(s, 2)
+    t0 = time.perf_counter()
+    _cpu_rows(oracle, X[:r], W, Wq, cw, d["alpha"])
+    per_row = (time.perf_counter() - t0) / r
+    r = int(max(1, min(s, target_seconds / max(per_row, 1e-9))))
+    cores = oracle.num_threads()
+    r = max(min(s, cores), r - r % cores) if r >= cores else r
+    t0 = time.perf_counter()
+    _cpu_rows(oracle, X[:r], W, Wq, cw, d["alpha"])
+    t = time.perf_counter() - t0
+    return r, t, cores
+
+
+def _cpu_rows(oracle, Xs, W, Wq, cw, alpha):
+    Xs = np.ascontiguousarray(Xs)
+    idx = oracle.find_outliers(Xs, alpha)
+    Xq, cx = oracle.quantize_rows(Xs, idx)
+    Cm = oracle.igemm(Xq, Wq)
+    return oracle.output(Cm, cx, cw, Xs, W, idx)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="ffn13b", choices=["ffn13b", "decode", "attn6p7b", "ffn175b_down"])
+    ap.add_argument("--no-decode", action="store_true", help="skip the secondary decode measurement")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1. "
+                 "value is one MI355X's throughput.")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback.")
+
+    res = run_workload(a.workload, a.steps, a.warmup, copies=2 if a.workload == "decode" else 1)
+    s, h, o = res["s"], res["h"], res["o"]
+    ops = 2.0 * s * h * o
+    line = {
+        "metric": "effective int8 TOPS of the LLM.int8() matmul per call (outlier scan + row quantize + "
+                  "int8 GEMM with fused dequant/outlier epilogue), 1 MI355X",
+        "value": ops / (res["ms_step"] * 1e-3) / 1e12,
+        "unit": "TOPS",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": res["ms_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": a.workload, "s": s, "h": h, "o": o, "alpha": 6.0,
+                   "outlier_columns_planted": res["planted"], "outlier_columns_found": res["n_out"],
+                   "outlier_capacity": CAP},
+        "ms_prepass": res["ms_prepass"], "ms_matmul_kernel": res["ms_matmul"],
+        "weight_quantize_ms_once": res["weight_quantize_ms"],
+    }
+    if a.workload == "decode":
+        nbytes = algorithmic_bytes_decode(s, h, o, res["n_out"])
+        line["metric"] = ("achieved HBM GB/s of the LLM.int8() matmul per call at decode size "
+                          "(algorithmic bytes / step time), 1 MI355X")
+        line["value"] = nbytes / (res["ms_step"] * 1e-3) / 1e9
+        line["unit"] = "GB/s"
+        ach = nbytes / (res["ms_matmul"] * 1e-3) / 1e9
+        line["roofline"] = {"bound": "hbm", "kernel": "gemm_decode_kernel", "achieved": ach,
+                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                            "traffic": MEASURED_TRAFFIC.get("decode")}
+    else:
+        ach = ops / (res["ms_matmul"] * 1e-3) / 1e12
+        line["roofline"] = {"bound": "mfma", "kernel": "gemm_prefill_kernel", "achieved": ach,
+                            "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": ach / INT8_MFMA_PEAK_TOPS,
+                            "traffic": MEASURED_TRAFFIC.get(a.workload)}
+
+    if not a.no_cpu_baseline:
+        r, t, cores = cpu_baseline(res)
+        if a.workload == "decode":
+            # the oracle reads fp16 weights; quote it in the metric's unit on the same algorithmic bytes
+            v = algorithmic_bytes_decode(r, h, o, res["n_out"]) / t / 1e9
+            unit = "GB/s"
+        else:
+            v = 2.0 * r * h * o / t / 1e12
+            unit = "TOPS"
+        line["cpu_baseline"] = {"value": v, "unit": unit, "cores": cores, "kind": "oracle",
+                                "sample": f"per-call steps on the first {r} of {s} rows of X against the full "
+                                          f"{h}x{o} weights (quantized beforehand, untimed); {t:.1f} s"}
+    del res["inputs"]
+
+    if a.workload != "decode" and not a.no_decode:
+        dres = run_workload("decode", a.steps, a.warmup, copies=2)
+        nbytes = algorithmic_bytes_decode(dres["s"], dres["h"], dres["o"], dres["n_out"])
+        line["decode"] = {
+            "workload": "decode", "s": dres["s"], "h": dres["h"], "o": dres["o"],
+            "ms_per_step": dres["ms_step"], "ms_prepass": dres["ms_prepass"], "ms_matmul_kernel": dres["ms_matmul"],
+            "value": nbytes / (dres["ms_step"] * 1e-3) / 1e9, "unit": "GB/s",
+            "roofline": {"bound": "hbm", "kernel": "gemm_decode_kernel",
+                         "achieved": nbytes / (dres["ms_matmul"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": nbytes / (dres["ms_matmul"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": MEASURED_TRAFFIC.get("decode")},
+        }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

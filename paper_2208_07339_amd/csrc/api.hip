@@ -13,7 +13,6 @@ inline void* ws_base(void* ws) { return (void*)align_up((uintptr_t)ws, 256); }
 
 inline size_t outlier_ws(int s, int h) { return align_up((size_t)colmax_slabs(s, h) * h * 2, 256); }
 inline size_t weight_ws(int h, int o) { return align_up((size_t)colmax_slabs(h, o) * o * 2, 256); }
-inline size_t matmul_ws(int o, int cap) { return align_up((size_t)row_tiles(o) * 32 * opad_of(cap) * 2, 256); }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? LLMINT8_OK : LLMINT8_HIP; }
 
@@ -50,9 +49,8 @@ size_t llmint8_xq_bytes(int s, int h)
 size_t llmint8_workspace_bytes(int s, int h, int o, int cap)
 {
     if (s < 1 || h < 1 || o < 1 || cap < 1) return 0;
-    size_t a = outlier_ws(s, h), b = weight_ws(h, o), c = matmul_ws(o, cap);
+    size_t a = outlier_ws(s, h), b = weight_ws(h, o);
     size_t m = a > b ? a : b;
-    m = m > c ? m : c;
     return m + 256;  // slack to align the caller's pointer
 }
 
@@ -107,27 +105,26 @@ int llmint8_matmul(const int8_t* Xq, const void* cx_f16, const void* Xo_f16, con
                    int h, int o, void* Out_f16, int32_t* C_i32_debug, void* ws, size_t ws_bytes,
                    llmint8_stream_t stream)
 {
-    if (!Xq || !cx_f16 || !Xo_f16 || !idx || !count || !Wq || !cw_f16 || !W_f16 || !Out_f16 || !ws || s < 1 ||
-        h < 1 || o < 1 || cap < 1)
+    if (!Xq || !cx_f16 || !Xo_f16 || !idx || !count || !Wq || !cw_f16 || !W_f16 || !Out_f16 || s < 1 || h < 1 ||
+        o < 1 || cap < 1)
         return LLMINT8_INVALID_ARG;
     if (misaligned(Xq, 16) || misaligned(Wq, 16) || misaligned(Xo_f16, 16) || misaligned(cw_f16, 8) ||
         misaligned(cx_f16, 2) || misaligned(W_f16, 2) || misaligned(Out_f16, 8) || misaligned(idx, 4) ||
         misaligned(count, 4) || misaligned(C_i32_debug, 4))
         return LLMINT8_INVALID_ARG;
     if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
-    if (ws_bytes < matmul_ws(o, cap) + 256) return LLMINT8_WORKSPACE;
+    (void)ws;
+    (void)ws_bytes;
     hipStream_t st = (hipStream_t)stream;
-    unsigned short* Wo = (unsigned short*)ws_base(ws);
-    hipError_t e = launch_gather_w(W_f16, o, idx, count, cap, Wo, st);
-    if (e != hipSuccess) return LLMINT8_HIP;
+    hipError_t e;
     if (s <= 32)
         e = launch_gemm_decode(Xq, (const unsigned short*)cx_f16, (const unsigned short*)Xo_f16, count, cap, Wq,
-                               (const unsigned short*)cw_f16, Wo, s, h, o, (unsigned short*)Out_f16, C_i32_debug,
-                               st);
+                               (const unsigned short*)cw_f16, (const unsigned short*)W_f16, idx, s, h, o,
+                               (unsigned short*)Out_f16, C_i32_debug, st);
     else
         e = launch_gemm_prefill(Xq, (const unsigned short*)cx_f16, (const unsigned short*)Xo_f16, count, cap, Wq,
-                                (const unsigned short*)cw_f16, Wo, s, h, o, (unsigned short*)Out_f16, C_i32_debug,
-                                st);
+                                (const unsigned short*)cw_f16, (const unsigned short*)W_f16, idx, s, h, o,
+                                (unsigned short*)Out_f16, C_i32_debug, st);
     return hip_status(e);
 }
 

@@ -65,15 +65,13 @@ hipError_t launch_quantize_rows(const void* X, int s, int h, const int32_t* idx,
                                 int8_t* Xq, unsigned short* cx, unsigned short* Xo, hipStream_t st);
 hipError_t launch_export_tiled(const int8_t* T, int rows, int h, int8_t* out, int ld_rows_major,
                                hipStream_t st);
-hipError_t launch_gather_w(const void* W, int o, const int32_t* idx, const int32_t* count, int cap,
-                           unsigned short* Wo, hipStream_t st);
 hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                                const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
-                               const unsigned short* Wo, int s, int h, int o, unsigned short* Out,
-                               int32_t* Cdbg, hipStream_t st);
+                               const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
+                               unsigned short* Out, int32_t* Cdbg, hipStream_t st);
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
-                              const unsigned short* Wo, int s, int h, int o, unsigned short* Out,
-                              int32_t* Cdbg, hipStream_t st);
+                              const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
+                              unsigned short* Out, int32_t* Cdbg, hipStream_t st);
 
 }  // namespace llmint8

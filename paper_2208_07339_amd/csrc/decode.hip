@@ -17,9 +17,9 @@ template <int NJ, int U>
 __global__ void __launch_bounds__(256)
 gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq, int KT, int JT,
                    const unsigned short* __restrict__ cw, const unsigned short* __restrict__ cx,
-                   const unsigned short* __restrict__ Wo, const unsigned short* __restrict__ Xo,
-                   const int32_t* __restrict__ count, int cap, int opad, _Float16* __restrict__ Out,
-                   int32_t* __restrict__ Cdbg, int s, int o)
+                   const unsigned short* __restrict__ Wf, const int32_t* __restrict__ idx,
+                   const unsigned short* __restrict__ Xo, const int32_t* __restrict__ count, int cap, int opad, _Float16* __restrict__ Out,
+                   int32_t* __restrict__ Cdbg, int s, int h, int o)
 {
     __shared__ int red[4][NJ][16][64];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -89,9 +89,12 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
             if (Cdbg) Cdbg[(size_t)i * o + j] = c;
             // Eq. 7 dequantization, then the outlier product of Eq. 8 accumulated in fp32
             float d = (float)c * (f16_bits_to_float(cx[i]) * (1.0f / 16129.0f)) * cwj;
-            for (int t = 0; t < cnt; t++)
-                d = __builtin_fmaf(f16_bits_to_float(Xo[(size_t)i * opad + t]),
-                                   f16_bits_to_float(Wo[(size_t)j * opad + t]), d);
+            for (int t = 0; t < cnt; t++) {
+                const unsigned k = (unsigned)idx[t];  // row of the original fp16 weights
+                if (k < (unsigned)h)
+                    d = __builtin_fmaf(f16_bits_to_float(Xo[(size_t)i * opad + t]),
+                                       f16_bits_to_float(Wf[(size_t)k * o + j]), d);
+            }
             Out[(size_t)i * o + j] = (_Float16)d;
         }
     }
@@ -99,13 +102,13 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
 
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
-                              const unsigned short* Wo, int s, int h, int o, unsigned short* Out,
-                              int32_t* Cdbg, hipStream_t st)
+                              const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
+                              unsigned short* Out, int32_t* Cdbg, hipStream_t st)
 {
     const int KT = k_tiles(h), JT = row_tiles(o);
     constexpr int NJ = 1, U = 8;
-    gemm_decode_kernel<NJ, U><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wo, Xo, count, cap,
-                                                                 opad_of(cap), (_Float16*)Out, Cdbg, s, o);
+    gemm_decode_kernel<NJ, U><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, idx, Xo, count, cap,
+                                                                 opad_of(cap), (_Float16*)Out, Cdbg, s, h, o);
     return hipGetLastError();
 }
 

@@ -19,46 +19,6 @@ typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 #define WAIT_VMCNT_LGKM0(n) __builtin_amdgcn_s_waitcnt(0x0070 | ((n) & 0xf) | ((((n) >> 4) & 3) << 14))
 
 // ---------------------------------------------------------------------------
-// Wo[j][t] = W_f16[O_t][j] for t < |O|, 0 for |O| <= t < opad, j < jpad
-// (jpad = o rounded up to 32; rows j >= o are zero).  K-contiguous so that the
-// epilogue's fp16 MFMA reads 16 bytes per lane.
-// ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) gather_w_kernel(const unsigned short* __restrict__ W, int o, int jpad,
-                                                       const int32_t* __restrict__ idx,
-                                                       const int32_t* __restrict__ count, int cap, int opad,
-                                                       unsigned short* __restrict__ Wo)
-{
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= jpad) return;
-    int cnt = *count;
-    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
-    for (int t0 = 0; t0 < opad; t0 += 8) {
-        unsigned short v[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const int t = t0 + e;
-            v[e] = 0;
-            if (t < cnt && j < o) v[e] = W[(size_t)idx[t] * o + j];
-        }
-        uint4 pk;
-        pk.x = v[0] | ((unsigned)v[1] << 16);
-        pk.y = v[2] | ((unsigned)v[3] << 16);
-        pk.z = v[4] | ((unsigned)v[5] << 16);
-        pk.w = v[6] | ((unsigned)v[7] << 16);
-        *(uint4*)(Wo + (size_t)j * opad + t0) = pk;
-    }
-}
-
-hipError_t launch_gather_w(const void* W, int o, const int32_t* idx, const int32_t* count, int cap,
-                           unsigned short* Wo, hipStream_t st)
-{
-    const int jpad = row_tiles(o) * 32;
-    gather_w_kernel<<<(jpad + 255) / 256, 256, 0, st>>>((const unsigned short*)W, o, jpad, idx, count, cap,
-                                                        opad_of(cap), Wo);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------
 // int8 GEMM, 256 output columns x 256 tokens per workgroup, 4 waves, each
 // wave a 128 x 128 sub-tile = 4 x 4 MFMA tiles of 32 x 32 (256 accumulator
 // registers per lane).  The MFMA "A" operand is a W tile (its 32 rows are
@@ -81,9 +41,9 @@ constexpr int LOADS_PER_STAGE = 8;                // per wave: 32 tiles / 4 wave
 __global__ void __launch_bounds__(256, 1)
 gemm_prefill_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq, int KT, int JT, int RT,
                     int nP, int nQ, const unsigned short* __restrict__ cw, const unsigned short* __restrict__ cx,
-                    const _Float16* __restrict__ Wo, const _Float16* __restrict__ Xo,
-                    const int32_t* __restrict__ count, int cap, int opad, _Float16* __restrict__ Out,
-                    int32_t* __restrict__ Cdbg, int s, int o)
+                    const unsigned short* __restrict__ Wf, const int32_t* __restrict__ idx,
+                    const _Float16* __restrict__ Xo, const int32_t* __restrict__ count, int cap, int opad, _Float16* __restrict__ Out,
+                    int32_t* __restrict__ Cdbg, int s, int h, int o)
 {
     extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -234,7 +194,30 @@ gemm_prefill_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq
         // c_x / 127^2 for this lane's token (Eq. 7: S = c_x (x) c_w / 127^2)
         sx[b] = (i < s) ? f16_bits_to_float(cx[i]) * (1.0f / 16129.0f) : 0.0f;
     }
-    const int jpad = JT * 32;
+    // Eq. 8, outlier term: the rows O of the original fp16 weights are read straight from W_f16
+    // (|O| * o * 2 bytes in all).  Lane l supplies outlier slots 8*(l>>5) .. +7 of a 16-slot k-step
+    // for column J0 + a*32 + (l & 31) (MFMA "A" operand) and for its token (MFMA "B" operand).
+    auto load_w = [&](int jcol, int t0) {
+        v8h wa;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const int t = t0 + 8 * g + e;
+            unsigned short v = 0;
+            if (t < cnt && jcol < o) {
+                const unsigned k = (unsigned)idx[t];
+                if (k < (unsigned)h) v = Wf[(size_t)k * o + jcol];
+            }
+            wa[e] = __builtin_bit_cast(_Float16, v);
+        }
+        return wa;
+    };
+    v8h xb0[4];
+#pragma unroll
+    for (int b = 0; b < 4; b++) {
+        const int i = I0 + b * 32 + (lane & 31);
+        xb0[b] = (v8h)(0);
+        if (i < s && cnt > 0) xb0[b] = *(const v8h*)(Xo + (size_t)i * opad + 8 * g);
+    }
 #pragma unroll
     for (int a = 0; a < 4; a++) {
         const int jb = J0 + a * 32 + 4 * g;
@@ -253,9 +236,9 @@ gemm_prefill_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq
                 for (int e = 0; e < 4; e++) cwv[4 * rr + e] = (j + e < o) ? f16_bits_to_float(cw[j + e]) : 0.0f;
             }
         }
-        // rows of Wo feeding the fp16 MFMA "A" operand: columns J0 + a*32 + (l & 31), clamped into the buffer
-        int ja = J0 + a * 32 + (lane & 31);
-        ja = ja < jpad ? ja : jpad - 1;
+        const int ja = J0 + a * 32 + (lane & 31);
+        v8h wa0 = (v8h)(0);
+        if (cnt > 0) wa0 = load_w(ja, 0);
 #pragma unroll
         for (int b = 0; b < 4; b++) {
             const int i = I0 + b * 32 + (lane & 31);
@@ -263,10 +246,9 @@ gemm_prefill_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq
             v16f d;
 #pragma unroll
             for (int r = 0; r < 16; r++) d[r] = (float)acc[a][b][r] * sx[b] * cwv[r];
-            // outlier product of Eq. 8 on the fp16 matrix cores, fp32 accumulate on top of d;
-            // each lane supplies 8 of the 16 outlier slots of a k-step for its column / token
-            for (int t0 = 0; t0 < cnt; t0 += 16) {
-                v8h wa = *(const v8h*)(Wo + (size_t)ja * opad + t0 + 8 * g);
+            if (cnt > 0) d = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa0, xb0[b], d, 0, 0, 0);
+            for (int t0 = 16; t0 < cnt; t0 += 16) {  // more than 16 outlier columns: rare
+                v8h wa = load_w(ja, t0);
                 v8h xb = (v8h)(0);
                 if (iok) xb = *(const v8h*)(Xo + (size_t)i * opad + t0 + 8 * g);
                 d = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa, xb, d, 0, 0, 0);
@@ -292,8 +274,8 @@ gemm_prefill_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq
 
 hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                                const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
-                               const unsigned short* Wo, int s, int h, int o, unsigned short* Out,
-                               int32_t* Cdbg, hipStream_t st)
+                               const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
+                               unsigned short* Out, int32_t* Cdbg, hipStream_t st)
 {
     const int KT = k_tiles(h), JT = row_tiles(o), RT = row_tiles(s);
     const int nP = (JT + 7) / 8, nQ = (RT + 7) / 8;
@@ -305,9 +287,9 @@ hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_prefill_kernel<<<nP * nQ, 256, shm, st>>>(Wq, Xq, KT, JT, RT, nP, nQ, cw, cx, (const _Float16*)Wo,
+    gemm_prefill_kernel<<<nP * nQ, 256, shm, st>>>(Wq, Xq, KT, JT, RT, nP, nQ, cw, cx, Wf, idx,
                                                    (const _Float16*)Xo, count, cap, opad_of(cap),
-                                                   (_Float16*)Out, Cdbg, s, o);
+                                                   (_Float16*)Out, Cdbg, s, h, o);
     return hipGetLastError();
 }
 
