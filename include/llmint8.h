@@ -25,7 +25,7 @@
  *     them into plain row-major int8 matrices.
  *   - stream is a hipStream_t (NULL = the default stream).  Every call only
  *     enqueues kernels on it: no host synchronisation, no allocation, no
- *     global state.  Calls that share a workspace must be ordered by stream.
+ *     global state (llmint8_debug_prefill_tile aside).  Calls that share a workspace must be ordered by stream.
  *   - Return value: LLMINT8_OK or an error code below; nothing is enqueued
  *     when an argument error is returned.  Conditions only visible on the
  *     device (|O| > cap) set bit 0 of the device status word and clamp.
@@ -55,6 +55,8 @@ enum {
 typedef void *llmint8_stream_t;
 
 const char *llmint8_status_string(int status);
+/* Text of the HIP error behind the calling thread's most recent LLMINT8_HIP return. */
+const char *llmint8_last_hip_error(void);
 
 /* Leading dimension (in fp16 elements) of the gathered-outlier matrix Xo for a
  * given capacity: cap rounded up to a multiple of 16. */
@@ -115,6 +117,12 @@ int llmint8_linear(const void *X_f16, int s, int h, float alpha, const int8_t *W
                    const void *W_f16, int o, int32_t *idx, int cap, int32_t *count, int32_t *status,
                    int8_t *Xq, void *cx_f16, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
                    llmint8_stream_t stream);
+
+/* Test/support: force the workgroup tile of the prefill GEMM (output columns x tokens):
+ * 0 = 256 x 256, 1 = 192 x 256, 2 = 128 x 256, 3 = 128 x 128; -1 = choose from the shape (default).
+ * Process-wide; results do not depend on it.                                  */
+#define LLMINT8_PREFILL_TILES 4
+int llmint8_debug_prefill_tile(int cfg);
 
 /* Test/support: private layouts -> plain row-major int8 ([h x o], [s x h]). */
 int llmint8_export_weight(const int8_t *Wq, int h, int o, int8_t *W_i8_rowmajor, llmint8_stream_t stream);

@@ -7,10 +7,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libllmint8.so")
 
 SYMBOLS = [
-    "llmint8_status_string", "llmint8_opad", "llmint8_wq_bytes", "llmint8_xq_bytes",
+    "llmint8_status_string", "llmint8_last_hip_error", "llmint8_opad", "llmint8_wq_bytes", "llmint8_xq_bytes",
     "llmint8_workspace_bytes", "llmint8_quantize_weight", "llmint8_find_outliers",
     "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_export_weight",
-    "llmint8_export_rows",
+    "llmint8_export_rows", "llmint8_debug_prefill_tile",
 ]
 
 _lib = None
@@ -28,10 +28,15 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise Llmint8Error(f"{LIB_PATH} is missing: run `python -m paper_2208_07339_amd.build` "
                            "(hipcc, gfx950). There is no fallback path.")
+    # torch first: it ships its own HIP runtime, and the library must bind to the one the tensors and
+    # streams it is handed come from (a second runtime loaded earlier sees no device)
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, sz, f32 = C.c_void_p, C.c_int, C.c_size_t, C.c_float
     L.llmint8_status_string.restype = C.c_char_p
     L.llmint8_status_string.argtypes = [i32]
+    L.llmint8_last_hip_error.restype = C.c_char_p
+    L.llmint8_last_hip_error.argtypes = []
     L.llmint8_opad.restype = i32
     L.llmint8_opad.argtypes = [i32]
     L.llmint8_wq_bytes.restype = sz
@@ -54,13 +59,16 @@ def lib():
     L.llmint8_export_weight.argtypes = [vp, i32, i32, vp, vp]
     L.llmint8_export_rows.restype = i32
     L.llmint8_export_rows.argtypes = [vp, i32, i32, vp, vp]
+    L.llmint8_debug_prefill_tile.restype = i32
+    L.llmint8_debug_prefill_tile.argtypes = [i32]
     _lib = L
     return L
 
 
 def _check(code):
     if code != 0:
-        raise Llmint8Error(f"llmint8 status {code}: {lib().llmint8_status_string(code).decode()}")
+        detail = f" ({lib().llmint8_last_hip_error().decode()})" if code == 4 else ""
+        raise Llmint8Error(f"llmint8 status {code}: {lib().llmint8_status_string(code).decode()}{detail}")
 
 
 def _torch():
@@ -197,6 +205,11 @@ def linear(X, qw, alpha, outl, rows, ws, out=None):
                                 _ptr(outl.idx), outl.cap, _ptr(outl.count), _ptr(outl.status), _ptr(rows.Xq),
                                 _ptr(rows.cx), _ptr(rows.Xo), _ptr(out), _ptr(ws.buf), ws.nbytes, _stream()))
     return out
+
+
+def debug_prefill_tile(cfg):
+    """llmint8_debug_prefill_tile: force the prefill GEMM's workgroup tile (-1 = automatic)."""
+    _check(lib().llmint8_debug_prefill_tile(int(cfg)))
 
 
 def export_weight(qw):

@@ -14,7 +14,14 @@ inline void* ws_base(void* ws) { return (void*)align_up((uintptr_t)ws, 256); }
 inline size_t outlier_ws(int s, int h) { return align_up((size_t)colmax_slabs(s, h) * h * 2, 256); }
 inline size_t weight_ws(int h, int o) { return align_up((size_t)colmax_slabs(h, o) * o * 2, 256); }
 
-inline int hip_status(hipError_t e) { return e == hipSuccess ? LLMINT8_OK : LLMINT8_HIP; }
+thread_local hipError_t g_last_hip = hipSuccess;  // reported by llmint8_last_hip_error()
+
+inline int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return LLMINT8_OK;
+    g_last_hip = e;
+    return LLMINT8_HIP;
+}
 
 }  // namespace
 
@@ -31,6 +38,8 @@ const char* llmint8_status_string(int status)
         default: return "unknown status";
     }
 }
+
+const char* llmint8_last_hip_error(void) { return hipGetErrorString(g_last_hip); }
 
 int llmint8_opad(int cap) { return cap < 1 ? 0 : opad_of(cap); }
 
@@ -141,6 +150,13 @@ int llmint8_linear(const void* X_f16, int s, int h, float alpha, const int8_t* W
     if (r != LLMINT8_OK) return r;
     return llmint8_matmul(Xq, cx_f16, Xo_f16, idx, count, cap, Wq, cw_f16, W_f16, s, h, o, Out_f16, nullptr, ws,
                           ws_bytes, stream);
+}
+
+int llmint8_debug_prefill_tile(int cfg)
+{
+    if (cfg < -1 || cfg >= LLMINT8_PREFILL_TILES) return LLMINT8_INVALID_ARG;
+    g_force_cfg = cfg;
+    return LLMINT8_OK;
 }
 
 int llmint8_export_weight(const int8_t* Wq, int h, int o, int8_t* W_i8_rowmajor, llmint8_stream_t stream)

@@ -74,4 +74,7 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
                               const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
                               unsigned short* Out, int32_t* Cdbg, hipStream_t st);
 
+// tile shape of the prefill GEMM forced by llmint8_debug_prefill_tile (-1: chosen from the shape)
+extern int g_force_cfg;
+
 }  // namespace llmint8

@@ -1,5 +1,7 @@
 // Prefill path of Eq. 7 + Eq. 8: int8 MFMA GEMM over the tiled operands with
 // the dequantization and the fp16 outlier product fused into the epilogue.
+#include <type_traits>
+
 #include "common.h"
 
 namespace llmint8 {
@@ -9,45 +11,87 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 
 #define GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define LPTR(p) ((__attribute__((address_space(3))) void*)(p))
-#define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+#define FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// s_waitcnt immediate for gfx9: vmcnt = n, lgkmcnt and expcnt left open.
-// WAIT_VMCNT_LGKM0 additionally waits for every LDS / scalar-memory operation of the wave.
+// s_waitcnt immediate for gfx9: vmcnt = n (6 bits, split 4 + 2), lgkmcnt = 0, expcnt left open.
 #define WAIT_VMCNT_LGKM0(n) __builtin_amdgcn_s_waitcnt(0x0070 | ((n) & 0xf) | ((((n) >> 4) & 3) << 14))
+// Workgroup barrier of the K pipeline: wait until at most n of this wave's direct loads are in flight and
+// all its LDS reads are done, then s_barrier.  __syncthreads() is not used here: its release fence waits
+// for every direct-to-LDS load in flight (vmcnt(0)), which would drain the pipeline at every stage.
+#define STAGE_SYNC(n)                        \
+    do {                                     \
+        asm volatile("" ::: "memory");       \
+        WAIT_VMCNT_LGKM0(n);                 \
+        __builtin_amdgcn_s_barrier();        \
+        asm volatile("" ::: "memory");       \
+    } while (0)
+
+struct GemmArgs {
+    const int8_t* Wq;            // tiled W_i8 (tile rows = output columns)
+    const int8_t* Xq;            // tiled X_i8 (tile rows = tokens)
+    int KT, JT, RT;              // k tiles, column tiles of W, token tiles of X
+    int nP, nQ;                  // workgroup grid: column blocks, token blocks
+    const unsigned short* cw;    // [o] fp16 bits
+    const unsigned short* cx;    // [s]
+    const unsigned short* Wf;    // [h x o] original fp16 weights
+    const int32_t* idx;          // [cap] outlier columns
+    const _Float16* Xo;          // [s x opad] gathered outlier columns of X
+    const int32_t* count;
+    int cap, opad;
+    _Float16* Out;               // [s x o]
+    int32_t* Cdbg;               // NULL or [s x o]
+    int s, h, o;
+    int fast_ok;                 // o % 8 == 0 and every epilogue operand 16-byte aligned
+};
 
 // ---------------------------------------------------------------------------
-// int8 GEMM, 256 output columns x 256 tokens per workgroup, 4 waves, each
-// wave a 128 x 128 sub-tile = 4 x 4 MFMA tiles of 32 x 32 (256 accumulator
-// registers per lane).  The MFMA "A" operand is a W tile (its 32 rows are
-// output columns j), the "B" operand an X tile (32 tokens i), so a lane ends
-// up with 4 consecutive output columns of one token per register quad.
+// One workgroup = 4 waves (2 x 2) computes 64*WA output columns x 64*WB tokens;
+// a wave owns WA x WB MFMA tiles of 32 x 32 (16*WA*WB accumulator registers per
+// lane).  The MFMA "A" operand is a W tile (its 32 rows are output columns j),
+// the "B" operand an X tile (32 tokens i): a lane ends up with 4 consecutive
+// output columns of one token per register quad.
 //
-// K pipeline: a stage is 64 features (2 MFMA k-steps) of all 16 row tiles =
-// 32 KiB; NB stages form a ring in LDS (128 KiB).  Tiles go global -> LDS
-// with 16-byte direct loads, one 1 KiB tile per wave instruction, and are
-// read back with one ds_read_b128 per operand (linear, conflict free).
-// One barrier per stage, placed before the stage's last k-step: it publishes
-// stage st+1 (every wave waited for its own loads of it) and retires the ring
-// slot of stage st (all its operands are in registers by then), which is
-// refilled right away with stage st+NB: NB-1 stages of lookahead.
+// K pipeline.  A stage is 64 features (2 MFMA k-steps) of all 2*(WA+WB) row
+// tiles; NB = 4 stages form a ring in LDS.  Tiles go global -> LDS with
+// 16-byte direct loads (one 1 KiB tile piece per wave instruction, WA+WB per
+// wave and stage) and come back with one ds_read_b128 per operand (linear,
+// conflict free).  The operands of a whole stage sit in registers, double
+// buffered: while the MFMAs of stage st run from one register set, stage st+1
+// is read from LDS into the other and stage st+4 is requested from memory.
+// One barrier per stage, at its top: it publishes stage st+1 (every wave
+// waited for its own pieces) and retires the ring slot of stage st (every wave
+// has it in registers), which is refilled right away.
+//
+// The stage sequence of a tile continues past K with two "epilogue stages"
+// that bring c_w, c_x, the gathered outlier columns Xo and rows O of the
+// original fp16 weights into the ring slots that fall free first, so that the
+// epilogue finds them in LDS without having waited for them.
 // ---------------------------------------------------------------------------
 constexpr int NB = 4;
-constexpr int STAGE_BYTES = 16 * 2 * TILE_BYTES;  // 32 KiB
-constexpr int LOADS_PER_STAGE = 8;                // per wave: 32 tiles / 4 waves
+constexpr int OSLOTS = 32;  // outlier slots staged through LDS; more are read from memory directly
 
-__global__ void __launch_bounds__(256, 1)
-gemm_prefill_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq, int KT, int JT, int RT,
-                    int nP, int nQ, const unsigned short* __restrict__ cw, const unsigned short* __restrict__ cx,
-                    const unsigned short* __restrict__ Wf, const int32_t* __restrict__ idx,
-                    const _Float16* __restrict__ Xo, const int32_t* __restrict__ count, int cap, int opad, _Float16* __restrict__ Out,
-                    int32_t* __restrict__ Cdbg, int s, int h, int o)
+template <int WA, int WB>
+__global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
 {
+    constexpr int TW = 2 * WA, TX = 2 * WB;
+    constexpr int PIECES = WA + WB;              // direct loads per wave per stage
+    constexpr int STAGE = (TW + TX) * 2 * TILE_BYTES;
+    constexpr int NMFMA = 2 * WA * WB;
+    constexpr int NRD = 2 * (WA + WB);
+    constexpr int NOPS = PIECES + NRD;
+    constexpr int NEW = 4 * WA;                  // epilogue-stage pieces holding W rows: [32 slots][64*WA columns] fp16
+    constexpr int NEX = 4 * WB;                  // pieces holding Xo: [64*WB tokens][32 slots] fp16
+    static_assert(NEW + NEX + 1 <= 8 * PIECES, "epilogue operands must fit two stages");
+    static_assert(2 * STAGE >= 32768, "output staging needs 8 KiB per wave");
+
     extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int s = g.s, h = g.h, o = g.o, KT = g.KT, opad = g.opad;
 
     // ---- workgroup -> output tile.  Hardware deals consecutive workgroup ids
     // round-robin to the 8 XCDs; give each XCD a contiguous run of the tile
@@ -55,6 +99,7 @@ gemm_prefill_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq
     // order, bands of 4 token blocks are walked column block by column block.
     int pj, qi;
     {
+        const int nP = g.nP, nQ = g.nQ;
         const int total = nP * nQ;
         const int wg = blockIdx.x;
         const int xcd = wg & 7, within = wg >> 3;
@@ -68,229 +113,387 @@ gemm_prefill_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq
         pj = inband / bh;
         qi = q0 + inband - pj * bh;
     }
+    const int wp = w >> 1, wq = w & 1;              // wave position: column half, token half
+    const int J0w = pj * 64 * WA, I0w = qi * 64 * WB;  // first column / token of the workgroup
+    const bool interior = g.fast_ok && !g.Cdbg && (J0w + 64 * WA <= o) && (I0w + 64 * WB <= s);
 
-    // ---- loader role: waves 0,1 bring W row tiles 0-3 / 4-7 of the block, waves 2,3 X row tiles
-    const bool isQ = w >= 2;
-    const int8_t* gsrc = isQ ? Xq : Wq;
-    const int ntile = isQ ? RT : JT;
-    const int tbase = (isQ ? qi : pj) * 8 + (w & 1) * 4;
-    const int8_t* gp[4];
-    const unsigned voff = lane * 16;
-#pragma unroll
-    for (int a = 0; a < 4; a++) {
-        int t = tbase + a;
-        t = t < ntile ? t : ntile - 1;  // clamp: rows past the matrix re-read the last tile, results unused
-        gp[a] = gsrc + (size_t)t * KT * TILE_BYTES;
+    int cnt = *g.count;
+    cnt = cnt < 0 ? 0 : (cnt > g.cap ? g.cap : cnt);
+    // lane t < 32 keeps the weight row of outlier slot t (row 0 for unused slots: finite values that
+    // meet the zeros of Xo)
+    int myk = 0;
+    if ((lane & 31) < cnt) {
+        const unsigned k = (unsigned)g.idx[lane & 31];
+        myk = k < (unsigned)h ? (int)k : 0;
     }
-    const int lslot = ((isQ ? 8 : 0) + (w & 1) * 4) * 2;  // first 1 KiB slot this wave fills in a stage
-    const int wp = w >> 1, wq = w & 1;                    // compute role: column half, token half
 
-    v16i acc[4][4];
+    // ---- loader role: piece p = w*PIECES + k of a stage is k-half (p & 1) of row tile p >> 1
+    // (W tiles first, then X tiles); it lands at byte p * 1024 of the stage's ring slot.
+    const unsigned voff = lane * 16;
+    const int8_t* gpp[PIECES];
 #pragma unroll
-    for (int a = 0; a < 4; a++)
+    for (int k = 0; k < PIECES; k++) {
+        const int p = w * PIECES + k;
+        const int r = p >> 1;
+        const int8_t* base;
+        if (r < TW) {
+            int t = pj * TW + r;
+            t = t < g.JT ? t : g.JT - 1;  // rows past the matrix re-read the last tile, results unused
+            base = g.Wq + (size_t)t * KT * TILE_BYTES;
+        } else {
+            int t = qi * TX + (r - TW);
+            t = t < g.RT ? t : g.RT - 1;
+            base = g.Xq + (size_t)t * KT * TILE_BYTES;
+        }
+        gpp[k] = base + (p & 1) * TILE_BYTES;
+    }
+    const int nst = KT / 2;   // KT is a multiple of 4, so nst is even and >= 2
+
+    // source of piece n (0 .. 8*PIECES-1) of the epilogue stages, per lane
+    auto esrc = [&](int n) -> const void* {
+        if (!interior) return g.Xq + voff;  // edge tiles read their epilogue operands from memory later
+        if (n < NEW) {
+            const int f = n * 64 + lane;
+            const int t = f / (8 * WA), cc = f % (8 * WA);
+            const int k = __shfl(myk, t);
+            return g.Wf + ((size_t)k * o + J0w + cc * 8);
+        }
+        if (n < NEW + NEX) {
+            const int f = (n - NEW) * 64 + lane;
+            int ch = f & 3;
+            if (opad < 32) ch &= 1;  // slots 16..31 do not exist (and are not used: cnt <= 16)
+            return g.Xo + ((size_t)(I0w + (f >> 2)) * opad + ch * 8);
+        }
+        if (lane < 32) {
+            const int c = lane < 8 * WA ? lane : 8 * WA - 1;
+            return g.cw + (J0w + c * 8);
+        }
+        const int c = (lane - 32) < 8 * WB ? (lane - 32) : 8 * WB - 1;
+        return g.cx + (I0w + c * 8);
+    };
+    // request piece k of operand stage v / of epilogue stage e into ring slot `slot`
+    auto dma_k = [&](int v, int slot, int k) {
+        int8_t* dst = lds + slot * STAGE + (w * PIECES + k) * TILE_BYTES;
+        __builtin_amdgcn_global_load_lds(GPTR(gpp[k] + (size_t)v * (2 * TILE_BYTES) + voff), LPTR(dst), 16, 0, 0);
+    };
+    auto dma_e = [&](int e, int slot, int k) {
+        int8_t* dst = lds + slot * STAGE + (w * PIECES + k) * TILE_BYTES;
+        __builtin_amdgcn_global_load_lds(GPTR(esrc(e * 4 * PIECES + w * PIECES + k)), LPTR(dst), 16, 0, 0);
+    };
+
+    v16i acc[WA][WB];
 #pragma unroll
-        for (int b = 0; b < 4; b++)
+    for (int a = 0; a < WA; a++)
+#pragma unroll
+        for (int b = 0; b < WB; b++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[a][b][r] = 0;
 
-    const int nst = KT / 2;
-    // stage `st` of the operands -> ring slot `slot`
-    auto issue = [&](int st, int slot) {
-#pragma unroll
-        for (int a = 0; a < 4; a++)
-#pragma unroll
-            for (int c = 0; c < 2; c++)
-                __builtin_amdgcn_global_load_lds(GPTR(gp[a] + (size_t)st * 2048 + c * 1024 + voff),
-                                                 LPTR(lds + slot * STAGE_BYTES + (lslot + a * 2 + c) * 1024), 16, 0, 0);
-    };
-    const int8_t* Pl = lds + (wp * 4) * 2048 + lane * 16;
-    const int8_t* Ql = lds + (8 + wq * 4) * 2048 + lane * 16;
-    auto rdP = [&](v4i(&P)[4], int buf, int c) {
-#pragma unroll
-        for (int a = 0; a < 4; a++) P[a] = *(const v4i*)(Pl + buf * STAGE_BYTES + a * 2048 + c * 1024);
-    };
-    auto rdQ = [&](v4i(&Q)[4], int buf, int c) {
-#pragma unroll
-        for (int b = 0; b < 4; b++) Q[b] = *(const v4i*)(Ql + buf * STAGE_BYTES + b * 2048 + c * 1024);
-    };
-    auto mm = [&](v4i(&P)[4], v4i(&Q)[4]) {
-#pragma unroll
-        for (int a = 0; a < 4; a++)
-#pragma unroll
-            for (int b = 0; b < 4; b++)
-                acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(P[a], Q[b], acc[a][b], 0, 0, 0);
+    // operand registers of two stages: [set][k-step][tile]
+    v4i RP[2][2][WA], RQ[2][2][WB];
+    const int8_t* Pl = lds + (wp * WA) * 2 * TILE_BYTES + lane * 16;
+    const int8_t* Ql = lds + (TW + wq * WB) * 2 * TILE_BYTES + lane * 16;
+    // read number i (0 .. NRD-1) of a stage into register set S
+    auto rd = [&](auto S, int slot, int i) {
+        constexpr int SS = decltype(S)::value;
+        const int c = i / (WA + WB), t = i % (WA + WB);
+        if (t < WA)
+            RP[SS][c][t] = *(const v4i*)(Pl + slot * STAGE + (t * 2 + c) * TILE_BYTES);
+        else
+            RQ[SS][c][t - WA] = *(const v4i*)(Ql + slot * STAGE + ((t - WA) * 2 + c) * TILE_BYTES);
     };
 
-    // prologue: fill the whole ring (stage indices past the end re-read the last stage; never consumed)
+    // prologue: the first NB stages (nv >= NB always; with nst == 2 the epilogue stages are among them)
 #pragma unroll
-    for (int st = 0; st < NB; st++) issue(st < nst ? st : nst - 1, st);
-    WAIT_VMCNT_LGKM0((NB - 1) * LOADS_PER_STAGE);
-    __syncthreads();
-    v4i P0[4], Q0[4], P1[4], Q1[4];
-    rdP(P0, 0, 0);
-    rdQ(Q0, 0, 0);
-    for (int st = 0; st < nst; st++) {
-        const int buf = st % NB;
-        // k-step 0, while the operands of k-step 1 come in from the same stage
-        rdP(P1, buf, 1);
-        rdQ(Q1, buf, 1);
-        mm(P0, Q0);
+    for (int v = 0; v < NB; v++) {
+        if (v < nst) {
 #pragma unroll
-        for (int g = 0; g < 8; g++) {
-            SGB(0x008, 2);
-            SGB(0x100, 1);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // My loads of stage st+1 have landed (the NB-2 younger stages may still fly) and my reads of
-        // stage st are complete; after the barrier the same holds for every wave, so slot `buf` is
-        // free and is refilled with stage st+NB.
-        WAIT_VMCNT_LGKM0((NB - 2) * LOADS_PER_STAGE);
-        __syncthreads();
-        {
-            const int nx = st + NB;
-            issue(nx < nst ? nx : nst - 1, buf);
-        }
-        rdP(P0, (st + 1) % NB, 0);
-        rdQ(Q0, (st + 1) % NB, 0);
-        mm(P1, Q1);
+            for (int k = 0; k < PIECES; k++) dma_k(v, v, k);
+        } else {
 #pragma unroll
-        for (int g = 0; g < 8; g++) {
-            SGB(0x008, 2);
-            SGB(0x020, 1);
-            SGB(0x100, 1);
+            for (int k = 0; k < PIECES; k++) dma_e(v - nst, v, k);
         }
-        __builtin_amdgcn_sched_barrier(0);
     }
-    WAIT_VMCNT_LGKM0(0);  // drain the redundant tail loads before the LDS allocation goes away
+    STAGE_SYNC((NB - 1) * PIECES);
+#pragma unroll
+    for (int i = 0; i < NRD; i++) rd(std::integral_constant<int, 0>{}, 0, i);
+    FENCE();
+
+    // One stage: MFMAs from register set S, interleaved with the requests of stage st+NB into the
+    // slot of stage st and the reads of stage st+1 into the other register set.
+    // MODE 0: operand stage st+NB; 1 / 2: first / second epilogue stage; 3: nothing left to request;
+    // 4: last stage (nothing to request, nothing to read).
+    auto stage = [&](auto S, auto M, int st) {
+        constexpr int SS = decltype(S)::value;
+        constexpr int MODE = decltype(M)::value;
+        // My pieces of stage st+1 have landed (two younger stages may still fly) and my reads of stage st
+        // are complete; after the barrier the same holds for every wave.
+        STAGE_SYNC((NB - 2) * PIECES);
+        FENCE();
+        const int slot = st % NB, nslot = (st + 1) % NB;
+#pragma unroll
+        for (int i = 0; i < NMFMA; i++) {
+            const int c = i / (WA * WB), a = (i / WB) % WA, b = i % WB;
+            acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(RP[SS][c][a], RQ[SS][c][b], acc[a][b], 0, 0, 0);
+            FENCE();
+#pragma unroll
+            for (int q = i * NOPS / NMFMA; q < (i + 1) * NOPS / NMFMA; q++) {
+                if (q < PIECES) {
+                    if (MODE == 0) dma_k(st + NB, slot, q);
+                    if (MODE == 1 || MODE == 2) dma_e(MODE - 1, slot, q);
+                } else if (MODE != 4) {
+                    rd(std::integral_constant<int, 1 - SS>{}, nslot, q - PIECES);
+                }
+            }
+            FENCE();
+        }
+    };
+    using I0_ = std::integral_constant<int, 0>;
+    using I1_ = std::integral_constant<int, 1>;
+    int st = 0;
+    for (; st + 6 <= nst; st += 2) {
+        stage(I0_{}, I0_{}, st);
+        stage(I1_{}, I0_{}, st + 1);
+    }
+    if (nst >= 4) {  // st == nst - 4
+        stage(I0_{}, std::integral_constant<int, 1>{}, st);
+        stage(I1_{}, std::integral_constant<int, 2>{}, st + 1);
+        st += 2;
+    }
+    stage(I0_{}, std::integral_constant<int, 3>{}, st);
+    stage(I1_{}, std::integral_constant<int, 4>{}, st + 1);
+    STAGE_SYNC(0);  // the epilogue stages have landed, every wave is done with the operand slots
 
     // ---- epilogue ----------------------------------------------------------
     // acc[a][b][r] of lane l: token i = I0 + b*32 + (l & 31),
     //                         column j = J0 + a*32 + 8*(r >> 2) + 4*(l >> 5) + (r & 3)
-    int cnt = *count;
-    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
-    const int J0 = pj * 256 + wp * 128;
-    const int I0 = qi * 256 + wq * 128;
-    const int g = lane >> 5;
-    const bool vec_store = (o & 3) == 0;
+    const int J0 = J0w + wp * 32 * WA;
+    const int I0 = I0w + wq * 32 * WB;
+    const int gl = lane >> 5, ll = lane & 31;
 
-    if (Cdbg) {
-#pragma unroll
-        for (int a = 0; a < 4; a++)
-#pragma unroll
-            for (int b = 0; b < 4; b++) {
-                const int i = I0 + b * 32 + (lane & 31);
-#pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const int j = J0 + a * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (i < s && j < o) Cdbg[(size_t)i * o + j] = acc[a][b][r];
-                }
-            }
-    }
+    const int eslot = nst % NB;                       // 0 or 2; the second epilogue stage follows it
+    const int8_t* E = lds + eslot * STAGE;
+    const unsigned short* EW = (const unsigned short*)E;                               // [32][64*WA]
+    const int8_t* EX = E + NEW * TILE_BYTES;                                           // [64*WB][32] fp16
+    const unsigned short* ECw = (const unsigned short*)(E + (NEW + NEX) * TILE_BYTES); // [64*WA]
+    const unsigned short* ECx = ECw + 256;                                             // [64*WB]
+    // output staging in the two ring slots that hold no epilogue operands: NSTG buffers of 8 KiB per wave
+    constexpr int NSTG = (2 * STAGE >= 65536) ? 2 : 1;
+    int8_t* stg = lds + ((eslot + 2) % NB) * STAGE + w * (8192 * NSTG);
 
-    float sx[4];
-#pragma unroll
-    for (int b = 0; b < 4; b++) {
-        const int i = I0 + b * 32 + (lane & 31);
-        // c_x / 127^2 for this lane's token (Eq. 7: S = c_x (x) c_w / 127^2)
-        sx[b] = (i < s) ? f16_bits_to_float(cx[i]) * (1.0f / 16129.0f) : 0.0f;
-    }
-    // Eq. 8, outlier term: the rows O of the original fp16 weights are read straight from W_f16
-    // (|O| * o * 2 bytes in all).  Lane l supplies outlier slots 8*(l>>5) .. +7 of a 16-slot k-step
-    // for column J0 + a*32 + (l & 31) (MFMA "A" operand) and for its token (MFMA "B" operand).
-    auto load_w = [&](int jcol, int t0) {
+    // rows O of the fp16 weights for column jcol, outlier slots t0 + 8*gl .. +7, straight from memory
+    auto load_w_mem = [&](int jcol, int t0) {
         v8h wa;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-            const int t = t0 + 8 * g + e;
+            const int t = t0 + 8 * gl + e;
             unsigned short v = 0;
             if (t < cnt && jcol < o) {
-                const unsigned k = (unsigned)idx[t];
-                if (k < (unsigned)h) v = Wf[(size_t)k * o + jcol];
+                const unsigned k = (unsigned)g.idx[t];
+                if (k < (unsigned)h) v = g.Wf[(size_t)k * o + jcol];
             }
             wa[e] = __builtin_bit_cast(_Float16, v);
         }
         return wa;
     };
-    v8h xb0[4];
+    auto load_x_mem = [&](int i, int t0) {
+        v8h xb = (v8h)(0);
+        if (i < s) xb = *(const v8h*)(g.Xo + (size_t)i * opad + t0 + 8 * gl);
+        return xb;
+    };
+
+    // FAST: interior tile, operands from the LDS image of the epilogue stages, no guards.
+    // Otherwise: operands from memory, every access guarded; also exports the raw accumulators.
+    auto epilogue = [&](auto F) {
+        constexpr bool FAST = decltype(F)::value;
+        if (!FAST && g.Cdbg) {
 #pragma unroll
-    for (int b = 0; b < 4; b++) {
-        const int i = I0 + b * 32 + (lane & 31);
-        xb0[b] = (v8h)(0);
-        if (i < s && cnt > 0) xb0[b] = *(const v8h*)(Xo + (size_t)i * opad + 8 * g);
-    }
+            for (int a = 0; a < WA; a++)
 #pragma unroll
-    for (int a = 0; a < 4; a++) {
-        const int jb = J0 + a * 32 + 4 * g;
-        float cwv[16];
+                for (int b = 0; b < WB; b++) {
+                    const int i = I0 + b * 32 + ll;
 #pragma unroll
-        for (int rr = 0; rr < 4; rr++) {
-            const int j = jb + 8 * rr;
-            if (j + 3 < o) {
-                const uint2 pk = *(const uint2*)(cw + j);  // 4 halves, j % 4 == 0
-                cwv[4 * rr + 0] = f16_bits_to_float((unsigned short)(pk.x & 0xffff));
-                cwv[4 * rr + 1] = f16_bits_to_float((unsigned short)(pk.x >> 16));
-                cwv[4 * rr + 2] = f16_bits_to_float((unsigned short)(pk.y & 0xffff));
-                cwv[4 * rr + 3] = f16_bits_to_float((unsigned short)(pk.y >> 16));
+                    for (int r = 0; r < 16; r++) {
+                        const int j = J0 + a * 32 + 8 * (r >> 2) + 4 * gl + (r & 3);
+                        if (i < s && j < o) g.Cdbg[(size_t)i * o + j] = acc[a][b][r];
+                    }
+                }
+        }
+        float sx[WB];      // c_x / 127^2 of this lane's tokens (Eq. 7: S = c_x (x) c_w / 127^2)
+        v8h xb[WB][2];     // MFMA "B" operand of the outlier product: slots 8*gl .. +7 (+16) of this lane's tokens
+#pragma unroll
+        for (int b = 0; b < WB; b++) {
+            const int il = wq * 32 * WB + b * 32 + ll;  // token within the workgroup tile
+            const int i = I0w + il;
+            if (FAST) {
+                sx[b] = f16_bits_to_float(ECx[il]) * (1.0f / 16129.0f);
+                xb[b][0] = *(const v8h*)(EX + il * 64 + gl * 16);
+                xb[b][1] = *(const v8h*)(EX + il * 64 + (2 + gl) * 16);
             } else {
-#pragma unroll
-                for (int e = 0; e < 4; e++) cwv[4 * rr + e] = (j + e < o) ? f16_bits_to_float(cw[j + e]) : 0.0f;
+                sx[b] = (i < s) ? f16_bits_to_float(g.cx[i]) * (1.0f / 16129.0f) : 0.0f;
+                xb[b][0] = cnt > 0 ? load_x_mem(i, 0) : (v8h)(0);
+                xb[b][1] = cnt > 16 ? load_x_mem(i, 16) : (v8h)(0);
             }
         }
-        const int ja = J0 + a * 32 + (lane & 31);
-        v8h wa0 = (v8h)(0);
-        if (cnt > 0) wa0 = load_w(ja, 0);
+        int unit = 0;
 #pragma unroll
-        for (int b = 0; b < 4; b++) {
-            const int i = I0 + b * 32 + (lane & 31);
-            const bool iok = i < s;
-            v16f d;
+        for (int a0 = 0; a0 < WA; a0 += 2) {
+            constexpr int WA_ = WA;
+            const int na = (WA_ - a0) < 2 ? (WA_ - a0) : 2;  // column tiles in this pass: 2, or 1 at the end of an odd WA
+            float cwv[2][16];
+            v8h wa[2][2];
 #pragma unroll
-            for (int r = 0; r < 16; r++) d[r] = (float)acc[a][b][r] * sx[b] * cwv[r];
-            if (cnt > 0) d = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa0, xb0[b], d, 0, 0, 0);
-            for (int t0 = 16; t0 < cnt; t0 += 16) {  // more than 16 outlier columns: rare
-                v8h wa = load_w(ja, t0);
-                v8h xb = (v8h)(0);
-                if (iok) xb = *(const v8h*)(Xo + (size_t)i * opad + t0 + 8 * g);
-                d = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa, xb, d, 0, 0, 0);
+            for (int aa = 0; aa < 2; aa++) {
+                if (aa >= na) break;
+                const int jl = wp * 32 * WA + (a0 + aa) * 32;  // first column of the MFMA tile within the workgroup tile
+                if (FAST) {
+#pragma unroll
+                    for (int rr = 0; rr < 4; rr++) {
+                        const uint2 pk = *(const uint2*)(ECw + jl + 8 * rr + 4 * gl);
+                        cwv[aa][4 * rr + 0] = f16_bits_to_float((unsigned short)(pk.x & 0xffff));
+                        cwv[aa][4 * rr + 1] = f16_bits_to_float((unsigned short)(pk.x >> 16));
+                        cwv[aa][4 * rr + 2] = f16_bits_to_float((unsigned short)(pk.y & 0xffff));
+                        cwv[aa][4 * rr + 3] = f16_bits_to_float((unsigned short)(pk.y >> 16));
+                    }
+#pragma unroll
+                    for (int ks = 0; ks < 2; ks++)
+#pragma unroll
+                        for (int e = 0; e < 8; e++)
+                            wa[aa][ks][e] =
+                                __builtin_bit_cast(_Float16, EW[(16 * ks + 8 * gl + e) * (64 * WA) + jl + ll]);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        const int j = J0w + jl + 8 * (r >> 2) + 4 * gl + (r & 3);
+                        cwv[aa][r] = (j < o) ? f16_bits_to_float(g.cw[j]) : 0.0f;
+                    }
+                    wa[aa][0] = cnt > 0 ? load_w_mem(J0w + jl + ll, 0) : (v8h)(0);
+                    wa[aa][1] = cnt > 16 ? load_w_mem(J0w + jl + ll, 16) : (v8h)(0);
+                }
             }
-            if (iok) {
 #pragma unroll
-                for (int rr = 0; rr < 4; rr++) {
-                    const int j = jb + 8 * rr;
-                    if (vec_store && j + 3 < o) {
-                        v4h hv = {(_Float16)d[4 * rr], (_Float16)d[4 * rr + 1], (_Float16)d[4 * rr + 2],
-                                  (_Float16)d[4 * rr + 3]};
-                        *(v4h*)(Out + (size_t)i * o + j) = hv;
-                    } else {
+            for (int b0 = 0; b0 < WB; b0 += 2, unit++) {
+                int8_t* sb = stg + (unit % NSTG) * 8192;
+                // ---- 64 tokens x 64 columns: dequantize, add the outlier product, stage as fp16 rows in LDS
 #pragma unroll
-                        for (int e = 0; e < 4; e++)
-                            if (j + e < o) Out[(size_t)i * o + j + e] = (_Float16)d[4 * rr + e];
+                for (int aa = 0; aa < 2; aa++) {
+                    if (aa >= na) break;
+                    const int a = a0 + aa;
+#pragma unroll
+                    for (int bb = 0; bb < 2; bb++) {
+                        if (b0 + bb >= WB) break;
+                        const int b = b0 + bb;
+                        v16f d;
+#pragma unroll
+                        for (int r = 0; r < 16; r++) d[r] = (float)acc[a][b][r] * sx[b] * cwv[aa][r];
+                        if (cnt > 0) d = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[aa][0], xb[b][0], d, 0, 0, 0);
+                        if (cnt > 16) d = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[aa][1], xb[b][1], d, 0, 0, 0);
+                        for (int t0 = OSLOTS; t0 < cnt; t0 += 16) {  // more than 32 outlier columns: rare
+                            const v8h wm = load_w_mem(J0 + a * 32 + ll, t0);
+                            const v8h xm = load_x_mem(I0 + b * 32 + ll, t0);
+                            d = __builtin_amdgcn_mfma_f32_32x32x16_f16(wm, xm, d, 0, 0, 0);
+                        }
+                        // staging row of token tl (0..63): 128 bytes = 8 chunks of 16, chunk q stored at
+                        // q ^ ((tl >> 1) & 7) to spread the banks
+                        const int tl = bb * 32 + ll;
+#pragma unroll
+                        for (int rr = 0; rr < 4; rr++) {
+                            const v4h hv = {(_Float16)d[4 * rr], (_Float16)d[4 * rr + 1], (_Float16)d[4 * rr + 2],
+                                            (_Float16)d[4 * rr + 3]};
+                            const int q = aa * 4 + rr;
+                            *(v4h*)(sb + tl * 128 + ((q ^ ((tl >> 1) & 7)) << 4) + gl * 8) = hv;
+                        }
+                    }
+                }
+                // ---- write the staged block: a lane moves 16 bytes, 8 lanes cover a token's 128 bytes
+#pragma unroll
+                for (int p = 0; p < 8; p++) {
+                    const int tl = p * 8 + (lane >> 3), q = lane & 7;
+                    const u4 v = *(const u4*)(sb + tl * 128 + ((q ^ ((tl >> 1) & 7)) << 4));
+                    const int i = I0 + b0 * 32 + tl;
+                    const int j = J0 + a0 * 32 + q * 8;
+                    if (FAST) {
+                        if (na == 2 || q < 4) *(u4*)(g.Out + (size_t)i * o + j) = v;
+                    } else if ((tl < 32 || b0 + 1 < WB) && i < s && q < 4 * na) {
+                        if (g.fast_ok && j + 8 <= o) {
+                            *(u4*)(g.Out + (size_t)i * o + j) = v;
+                        } else {
+                            const _Float16* hv = (const _Float16*)&v;
+#pragma unroll
+                            for (int e = 0; e < 8; e++)
+                                if (j + e < o) g.Out[(size_t)i * o + j + e] = hv[e];
+                        }
                     }
                 }
             }
         }
-    }
+    };
+    if (interior)
+        epilogue(std::true_type{});
+    else
+        epilogue(std::false_type{});
 }
+
+template <int WA, int WB>
+static hipError_t launch_cfg(GemmArgs& g, hipStream_t st)
+{
+    constexpr int STAGE = (2 * WA + 2 * WB) * 2 * TILE_BYTES;
+    constexpr int shm = NB * STAGE;
+    g.nP = (g.JT + 2 * WA - 1) / (2 * WA);
+    g.nQ = (g.RT + 2 * WB - 1) / (2 * WB);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, shm);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    gemm_prefill_kernel<WA, WB><<<g.nP * g.nQ, 256, shm, st>>>(g);
+    return hipGetLastError();
+}
+
+static inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+// Tile shape: fewest passes of the 256 compute units over the tile grid, larger tiles on a tie
+// (a 256 x 256 tile moves the fewest operand bytes per MFMA).
+static int pick_cfg(int s, int o)
+{
+    static const int WAs[4] = {4, 3, 2, 2}, WBs[4] = {4, 4, 4, 2};
+    static const double eff[4] = {1.0, 0.96, 0.88, 0.75};  // relative MFMA rate of the main loop
+    int best = 0;
+    double bestc = 0;
+    for (int c = 0; c < 4; c++) {
+        const long nP = (o + 64 * WAs[c] - 1) / (64 * WAs[c]), nQ = (s + 64 * WBs[c] - 1) / (64 * WBs[c]);
+        const long passes = (nP * nQ + 255) / 256;
+        const double cost = (double)passes * WAs[c] * WBs[c] / eff[c];
+        if (c == 0 || cost < bestc) { best = c; bestc = cost; }
+    }
+    return best;
+}
+
+int g_force_cfg = -1;  // test hook: tile shape override (-1 = automatic)
 
 hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                                const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
                                const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
                                unsigned short* Out, int32_t* Cdbg, hipStream_t st)
 {
-    const int KT = k_tiles(h), JT = row_tiles(o), RT = row_tiles(s);
-    const int nP = (JT + 7) / 8, nQ = (RT + 7) / 8;
-    static bool attr_set = false;
-    const int shm = NB * STAGE_BYTES;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_prefill_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, shm);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+    GemmArgs g;
+    g.Wq = Wq; g.Xq = Xq;
+    g.KT = k_tiles(h); g.JT = row_tiles(o); g.RT = row_tiles(s);
+    g.nP = g.nQ = 0;
+    g.cw = cw; g.cx = cx; g.Wf = Wf; g.idx = idx; g.Xo = (const _Float16*)Xo; g.count = count;
+    g.cap = cap; g.opad = opad_of(cap);
+    g.Out = (_Float16*)Out; g.Cdbg = Cdbg;
+    g.s = s; g.h = h; g.o = o;
+    g.fast_ok = (o % 8 == 0) && al16(cw) && al16(cx) && al16(Wf) && al16(Xo) && al16(Out);
+    const int c = g_force_cfg >= 0 ? g_force_cfg : pick_cfg(s, o);
+    switch (c) {
+        case 1: return launch_cfg<3, 4>(g, st);
+        case 2: return launch_cfg<2, 4>(g, st);
+        case 3: return launch_cfg<2, 2>(g, st);
+        default: return launch_cfg<4, 4>(g, st);
     }
-    gemm_prefill_kernel<<<nP * nQ, 256, shm, st>>>(Wq, Xq, KT, JT, RT, nP, nQ, cw, cx, Wf, idx,
-                                                   (const _Float16*)Xo, count, cap, opad_of(cap),
-                                                   (_Float16*)Out, Cdbg, s, h, o);
-    return hipGetLastError();
 }
 
 }  // namespace llmint8

@@ -50,6 +50,27 @@ def test_shapes_against_full_oracle(s, h, o, ncol):
     full_compare(wl.make_custom(s, h, o, ncol, seed=s * 7 + o))
 
 
+@pytest.fixture
+def forced_tile():
+    import paper_2208_07339_amd as L
+    yield L.debug_prefill_tile
+    L.debug_prefill_tile(-1)
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+def test_every_prefill_tile_shape(cfg, forced_tile):
+    """Each workgroup tile of the prefill GEMM on: interior + edge tiles with the outlier operands staged
+    through LDS (7 and 20 columns), a 16-slot outlier buffer, more outlier columns than are staged (40),
+    and a shape where nothing is aligned."""
+    forced_tile(cfg)
+    full_compare(wl.make_custom(512, 2048, 1024, 7, seed=1))
+    full_compare(wl.make_custom(600, 640, 776, 20, seed=2))
+    full_compare(wl.make_custom(256, 256, 512, 3, seed=3), cap=8)
+    full_compare(wl.make_custom(300, 384, 520, 40, seed=4), cap=48)
+    full_compare(wl.make_custom(300, 1000, 515, 4, seed=5))
+    full_compare(wl.make_custom(330, 128, 264, 0, seed=6))
+
+
 def test_alpha_zero_is_pure_fp16_matmul_on_both_paths():
     d = wl.make("tiny")
     g, r = full_compare(d, alpha=0.0, cap=256)
