@@ -124,6 +124,12 @@ int llmint8_linear(const void *X_f16, int s, int h, float alpha, const int8_t *W
 #define LLMINT8_PREFILL_TILES 4
 int llmint8_debug_prefill_tile(int cfg);
 
+/* Test/support: force the work split of the decode kernel (column tiles per workgroup, k-tiles per
+ * load batch): 1 = 1 x 8, 2 = 2 x 4, 3 = 2 x 8, 4 = 3 x 4, 5 = 1 x 4; -1 = default.  Process-wide;
+ * results do not depend on it.                                                */
+#define LLMINT8_DECODE_SHAPES 5
+int llmint8_debug_decode_shape(int cfg);
+
 /* Test/support: private layouts -> plain row-major int8 ([h x o], [s x h]). */
 int llmint8_export_weight(const int8_t *Wq, int h, int o, int8_t *W_i8_rowmajor, llmint8_stream_t stream);
 int llmint8_export_rows(const int8_t *Xq, int s, int h, int8_t *X_i8_rowmajor, llmint8_stream_t stream);

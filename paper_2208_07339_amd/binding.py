@@ -11,6 +11,7 @@ SYMBOLS = [
     "llmint8_workspace_bytes", "llmint8_quantize_weight", "llmint8_find_outliers",
     "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_export_weight",
     "llmint8_export_rows", "llmint8_debug_prefill_tile",
+    "llmint8_debug_decode_shape",
 ]
 
 _lib = None
@@ -61,6 +62,8 @@ def lib():
     L.llmint8_export_rows.argtypes = [vp, i32, i32, vp, vp]
     L.llmint8_debug_prefill_tile.restype = i32
     L.llmint8_debug_prefill_tile.argtypes = [i32]
+    L.llmint8_debug_decode_shape.restype = i32
+    L.llmint8_debug_decode_shape.argtypes = [i32]
     _lib = L
     return L
 
@@ -210,6 +213,11 @@ def linear(X, qw, alpha, outl, rows, ws, out=None):
 def debug_prefill_tile(cfg):
     """llmint8_debug_prefill_tile: force the prefill GEMM's workgroup tile (-1 = automatic)."""
     _check(lib().llmint8_debug_prefill_tile(int(cfg)))
+
+
+def debug_decode_shape(cfg):
+    """llmint8_debug_decode_shape: force the decode kernel's work split (-1 = default)."""
+    _check(lib().llmint8_debug_decode_shape(int(cfg)))
 
 
 def export_weight(qw):

@@ -11,7 +11,12 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 inline void* ws_base(void* ws) { return (void*)align_up((uintptr_t)ws, 256); }
 
-inline size_t outlier_ws(int s, int h) { return align_up((size_t)colmax_slabs(s, h) * h * 2, 256); }
+// outlier scan: list scratch first, then the slab maxima
+inline size_t scratch_ws(int h, int cap) { return align_up(outlier_lists_bytes(h, cap), 256); }
+inline size_t outlier_ws(int s, int h, int cap)
+{
+    return scratch_ws(h, cap) + align_up((size_t)colmax_slabs(s, h) * h * 2, 256);
+}
 inline size_t weight_ws(int h, int o) { return align_up((size_t)colmax_slabs(h, o) * o * 2, 256); }
 
 thread_local hipError_t g_last_hip = hipSuccess;  // reported by llmint8_last_hip_error()
@@ -58,7 +63,7 @@ size_t llmint8_xq_bytes(int s, int h)
 size_t llmint8_workspace_bytes(int s, int h, int o, int cap)
 {
     if (s < 1 || h < 1 || o < 1 || cap < 1) return 0;
-    size_t a = outlier_ws(s, h), b = weight_ws(h, o);
+    size_t a = outlier_ws(s, h, cap), b = weight_ws(h, o);
     size_t m = a > b ? a : b;
     return m + 256;  // slack to align the caller's pointer
 }
@@ -86,13 +91,15 @@ int llmint8_find_outliers(const void* X_f16, int s, int h, float alpha, int32_t*
     if (misaligned(X_f16, 2) || misaligned(idx, 4) || misaligned(count, 4) || misaligned(status, 4))
         return LLMINT8_INVALID_ARG;
     if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
-    if (ws_bytes < outlier_ws(s, h) + 256) return LLMINT8_WORKSPACE;
+    if (ws_bytes < outlier_ws(s, h, cap) + 256) return LLMINT8_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    unsigned short* part = (unsigned short*)ws_base(ws);
+    char* base = (char*)ws_base(ws);
+    const OutlierLists L = carve_outlier_lists(base, h, cap);
+    unsigned short* part = (unsigned short*)(base + scratch_ws(h, cap));
     const int nslab = colmax_slabs(s, h);
     hipError_t e = launch_colmax_partial(X_f16, s, h, part, nslab, st);
-    if (e == hipSuccess)
-        e = launch_outlier_compact(part, nslab, h, threshold_bits(alpha), idx, cap, count, status, st);
+    if (e == hipSuccess) e = launch_outlier_lists(part, nslab, h, threshold_bits(alpha), L, cap, st);
+    if (e == hipSuccess) e = launch_merge_lists(L, h, idx, cap, count, status, st);
     return hip_status(e);
 }
 
@@ -141,13 +148,35 @@ int llmint8_linear(const void* X_f16, int s, int h, float alpha, const int8_t* W
                    const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status, int8_t* Xq,
                    void* cx_f16, void* Xo_f16, void* Out_f16, void* ws, size_t ws_bytes, llmint8_stream_t stream)
 {
-    int r = llmint8_find_outliers(X_f16, s, h, alpha, idx, cap, count, status, ws, ws_bytes, stream);
-    if (r != LLMINT8_OK) return r;
-    // validate the remaining arguments before anything else is enqueued
-    if (!Wq || !cw_f16 || !W_f16 || !Out_f16 || o < 1) return LLMINT8_INVALID_ARG;
+    // validate everything before anything is enqueued
+    if (!X_f16 || !idx || !count || !ws || !Xq || !cx_f16 || !Xo_f16 || !Wq || !cw_f16 || !W_f16 || !Out_f16 || s < 1 ||
+        h < 1 || o < 1 || cap < 1)
+        return LLMINT8_INVALID_ARG;
+    if (misaligned(X_f16, 2) || misaligned(idx, 4) || misaligned(count, 4) || misaligned(status, 4) ||
+        misaligned(Xq, 16) || misaligned(Wq, 16) || misaligned(Xo_f16, 16) || misaligned(cw_f16, 8) ||
+        misaligned(cx_f16, 2) || misaligned(W_f16, 2) || misaligned(Out_f16, 8))
+        return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
     if (ws_bytes < llmint8_workspace_bytes(s, h, o, cap)) return LLMINT8_WORKSPACE;
-    r = llmint8_quantize_rows(X_f16, s, h, idx, count, cap, Xq, cx_f16, Xo_f16, stream);
-    if (r != LLMINT8_OK) return r;
+    // Same results as llmint8_find_outliers + llmint8_quantize_rows, in fewer kernels: the row
+    // constants and the quantizer read the column lists of the scan directly.
+    hipStream_t st = (hipStream_t)stream;
+    char* base = (char*)ws_base(ws);
+    const OutlierLists L = carve_outlier_lists(base, h, cap);
+    hipError_t e;
+    if (s <= 32) {
+        e = launch_prepass_small(X_f16, s, h, threshold_bits(alpha), L, idx, cap, count, status,
+                                 (unsigned short*)cx_f16, (unsigned short*)Xo_f16, Xq, st);
+    } else {
+        unsigned short* part = (unsigned short*)(base + scratch_ws(h, cap));
+        const int nslab = colmax_slabs(s, h);
+        e = launch_colmax_partial(X_f16, s, h, part, nslab, st);
+        if (e == hipSuccess) e = launch_outlier_lists(part, nslab, h, threshold_bits(alpha), L, cap, st);
+        if (e == hipSuccess)
+            e = launch_quantize_rows_lists(X_f16, s, h, L, idx, count, status, cap, Xq, (unsigned short*)cx_f16,
+                                           (unsigned short*)Xo_f16, st);
+    }
+    if (e != hipSuccess) return hip_status(e);
     return llmint8_matmul(Xq, cx_f16, Xo_f16, idx, count, cap, Wq, cw_f16, W_f16, s, h, o, Out_f16, nullptr, ws,
                           ws_bytes, stream);
 }
@@ -156,6 +185,13 @@ int llmint8_debug_prefill_tile(int cfg)
 {
     if (cfg < -1 || cfg >= LLMINT8_PREFILL_TILES) return LLMINT8_INVALID_ARG;
     g_force_cfg = cfg;
+    return LLMINT8_OK;
+}
+
+int llmint8_debug_decode_shape(int cfg)
+{
+    if (cfg < -1 || cfg > LLMINT8_DECODE_SHAPES) return LLMINT8_INVALID_ARG;
+    g_decode_cfg = cfg;
     return LLMINT8_OK;
 }
 

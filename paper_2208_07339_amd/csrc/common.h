@@ -51,12 +51,46 @@ __host__ inline unsigned threshold_bits(float alpha)
 // ---- launchers (host side, defined next to their kernels) -------------------
 // All return a hipError_t from hipGetLastError() after the launches.
 
+// Column lists of the outlier scans (see prepass.hip), carved from the caller's workspace.
+constexpr int MAXLISTS = 1024;  // runs of 256 columns; h <= LLMINT8_MAX_H needs 521
+struct OutlierLists {
+    int* count;               // [MAXLISTS] qualifying columns in each run of 256 columns
+    int* cand;                // [lists][capc] their indices, ascending
+    unsigned short* rowpart;  // [ceil(h / 512)][32] partial row maxima (short-X scan only)
+};
+__host__ __device__ inline int list_capacity(int cap) { return cap < 256 ? cap : 256; }
+inline size_t outlier_lists_bytes(int h, int cap)
+{
+    const size_t nl = (size_t)(h + 255) / 256, nwg = (size_t)(h + 511) / 512;
+    return MAXLISTS * 4 + nl * list_capacity(cap) * 4 + nwg * 32 * 2;
+}
+inline OutlierLists carve_outlier_lists(char* base, int h, int cap)
+{
+    const size_t nl = (size_t)(h + 255) / 256;
+    OutlierLists L;
+    L.count = (int*)base;
+    L.cand = (int*)(base + MAXLISTS * 4);
+    L.rowpart = (unsigned short*)(base + MAXLISTS * 4 + nl * list_capacity(cap) * 4);
+    return L;
+}
+
 // partial column maxima of an fp16 matrix M[rows][cols]: part[slab][cols] (u16 magnitude bits)
 int colmax_slabs(int rows, int cols);
 hipError_t launch_colmax_partial(const void* M, int rows, int cols, unsigned short* part, int nslab,
                                  hipStream_t st);
-hipError_t launch_outlier_compact(const unsigned short* part, int nslab, int h, unsigned thr, int32_t* idx,
-                                  int cap, int32_t* count, int32_t* status, hipStream_t st);
+// slab maxima -> column lists; lists -> idx, count, status
+hipError_t launch_outlier_lists(const unsigned short* part, int nslab, int h, unsigned thr, OutlierLists L, int cap,
+                                hipStream_t st);
+hipError_t launch_merge_lists(OutlierLists L, int h, int32_t* idx, int cap, int32_t* count, int32_t* status,
+                              hipStream_t st);
+// row constants + codes + gathered columns fed by the lists; also writes idx, count, status
+hipError_t launch_quantize_rows_lists(const void* X, int s, int h, OutlierLists L, int32_t* idx, int32_t* count,
+                                      int32_t* status, int cap, int8_t* Xq, unsigned short* cx, unsigned short* Xo,
+                                      hipStream_t st);
+// whole pre-pass of a short X (s <= 32): outlier scan, row constants, codes, gathered columns
+hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
+                                int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,
+                                hipStream_t st);
 hipError_t launch_colmax_final(const unsigned short* part, int nslab, int cols, unsigned short* out,
                                hipStream_t st);
 hipError_t launch_quantize_weight(const void* W, int h, int o, const unsigned short* cw, int8_t* Wq,
@@ -76,5 +110,7 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
 
 // tile shape of the prefill GEMM forced by llmint8_debug_prefill_tile (-1: chosen from the shape)
 extern int g_force_cfg;
+// work split of the decode kernel forced by llmint8_debug_decode_shape (-1: default)
+extern int g_decode_cfg;
 
 }  // namespace llmint8

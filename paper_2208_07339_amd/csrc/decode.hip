@@ -1,6 +1,8 @@
 // Decode path of Eq. 7 + Eq. 8 for s <= 32 tokens: the int8 weights are
 // streamed from HBM exactly once; the few tokens ride along as the second MFMA
 // operand.  Bandwidth bound (h * o bytes of W_i8 dominate).
+#include <type_traits>
+
 #include "common.h"
 
 namespace llmint8 {
@@ -8,29 +10,81 @@ namespace llmint8 {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+#define FENCE() __builtin_amdgcn_sched_barrier(0)
+
+constexpr int DSLOTS = 16;  // outlier slots whose operands are fetched before the weight stream starts
+
 // One workgroup = 4 waves owns NJ tiles of 32 output columns.  The waves split
 // K four ways; each streams its quarter of the W tiles (1 KiB contiguous per
-// wave load, U tiles in flight per column tile) and multiplies it with the
-// matching X tile (row tile 0 of Xq: tokens 0..31, zero padded).  The four
-// partial accumulators meet in LDS; int32 sums are exact in any order.
+// wave load) in batches of U k-tiles, two batches in flight, and multiplies
+// them with the matching X tiles (row tile 0 of Xq: tokens 0..31, zero
+// padded).  The four partial accumulators meet in LDS; int32 sums are exact in
+// any order.  What the epilogue needs (c_w, c_x, the outlier columns of X and
+// the matching rows of the fp16 weights) is requested before the stream starts,
+// so that no workgroup ends with a chain of dependent loads.
 template <int NJ, int U>
 __global__ void __launch_bounds__(256)
 gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq, int KT, int JT,
                    const unsigned short* __restrict__ cw, const unsigned short* __restrict__ cx,
                    const unsigned short* __restrict__ Wf, const int32_t* __restrict__ idx,
-                   const unsigned short* __restrict__ Xo, const int32_t* __restrict__ count, int cap, int opad, _Float16* __restrict__ Out,
-                   int32_t* __restrict__ Cdbg, int s, int h, int o)
+                   const unsigned short* __restrict__ Xo, const int32_t* __restrict__ count, int cap, int opad,
+                   _Float16* __restrict__ Out, int32_t* __restrict__ Cdbg, int s, int h, int o)
 {
     __shared__ int red[4][NJ][16][64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kq = KT / 4;  // KT is a multiple of 4
     const int jt0 = blockIdx.x * NJ;
+
+    // ---- epilogue operands, requested first.  Thread -> column jj of a tile, tokens ig, ig+8, ig+16, ig+24.
+    int cnt = *count;
+    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
+    const int jj = tid & 31, ig = tid >> 5;
+    float cwj[NJ], sxi[4];
+    unsigned wo[NJ][DSLOTS / 2];  // fp16 pairs: slots 2q (low half) and 2q+1 of this thread's columns
+    uint4 xo[4][DSLOTS / 8];      // slots 0..15 of this thread's tokens (Xo holds zeros past |O|)
+#pragma unroll
+    for (int n = 0; n < NJ; n++) {
+        const int j = (jt0 + n) * 32 + jj;
+        cwj[n] = (j < o) ? f16_bits_to_float(cw[j]) : 0.0f;
+    }
+#pragma unroll
+    for (int m = 0; m < 4; m++) {
+        const int i = ig + 8 * m;
+        sxi[m] = (i < s) ? f16_bits_to_float(cx[i]) * (1.0f / 16129.0f) : 0.0f;
+    }
+#pragma unroll
+    for (int m = 0; m < 4; m++) {
+        const int i = ig + 8 * m;
+#pragma unroll
+        for (int q = 0; q < DSLOTS / 8; q++) {
+            xo[m][q] = make_uint4(0, 0, 0, 0);
+            if (cnt > 0 && i < s) xo[m][q] = *(const uint4*)(Xo + (size_t)i * opad + 8 * q);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < DSLOTS; t++) {
+        unsigned k = 0;
+        bool ok = t < cnt;
+        if (ok) {
+            k = (unsigned)idx[t];  // uniform: a scalar load
+            ok = k < (unsigned)h;
+        }
+#pragma unroll
+        for (int n = 0; n < NJ; n++) {
+            const int j = (jt0 + n) * 32 + jj;
+            const unsigned v = (ok && j < o) ? (unsigned)Wf[(size_t)k * o + j] : 0u;
+            if (t & 1) wo[n][t >> 1] |= v << 16; else wo[n][t >> 1] = v;
+        }
+    }
+    FENCE();
+
+    // ---- weight stream
     const v4i* wp[NJ];
 #pragma unroll
     for (int n = 0; n < NJ; n++) {
         int jt = jt0 + n;
-        jt = jt < JT ? jt : JT - 1;
+        jt = jt < JT ? jt : JT - 1;  // tiles past the matrix re-read the last one, results unused
         wp[n] = (const v4i*)(Wq + ((size_t)jt * KT + (size_t)w * kq) * TILE_BYTES) + lane;
     }
     const v4i* xp = (const v4i*)(Xq + (size_t)w * kq * TILE_BYTES) + lane;
@@ -41,27 +95,47 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[n][r] = 0;
 
-    int kt = 0;
-    for (; kt + U <= kq; kt += U) {
-        v4i wv[NJ][U], xv[U];
+    v4i wv[2][NJ][U], xv[2][U];
+    auto load = [&](auto B, int kt) {
+        constexpr int BB = decltype(B)::value;
 #pragma unroll
         for (int u = 0; u < U; u++) {
 #pragma unroll
-            for (int n = 0; n < NJ; n++) wv[n][u] = __builtin_nontemporal_load(wp[n] + (size_t)(kt + u) * 64);
-            xv[u] = xp[(size_t)(kt + u) * 64];
+            for (int n = 0; n < NJ; n++) wv[BB][n][u] = __builtin_nontemporal_load(wp[n] + (size_t)(kt + u) * 64);
+            xv[BB][u] = xp[(size_t)(kt + u) * 64];
         }
+    };
+    auto mm = [&](auto B) {
+        constexpr int BB = decltype(B)::value;
 #pragma unroll
         for (int u = 0; u < U; u++)
 #pragma unroll
             for (int n = 0; n < NJ; n++)
-                acc[n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv[n][u], xv[u], acc[n], 0, 0, 0);
+                acc[n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv[BB][n][u], xv[BB][u], acc[n], 0, 0, 0);
+    };
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    const int nb = kq / U;  // full batches
+    if (nb > 0) load(B0{}, 0);
+    FENCE();
+    int b = 0;
+    for (; b + 2 <= nb; b += 2) {
+        load(B1{}, (b + 1) * U);
+        FENCE();
+        mm(B0{});
+        FENCE();
+        if (b + 2 < nb) load(B0{}, (b + 2) * U);
+        FENCE();
+        mm(B1{});
+        FENCE();
     }
-    for (; kt < kq; kt++) {
-        v4i xv = xp[(size_t)kt * 64];
+    if (b < nb) mm(B0{});  // odd number of batches: the last one is already in flight in buffer 0
+    for (int kt = nb * U; kt < kq; kt++) {
+        const v4i x1 = xp[(size_t)kt * 64];
 #pragma unroll
         for (int n = 0; n < NJ; n++) {
-            v4i wv = __builtin_nontemporal_load(wp[n] + (size_t)kt * 64);
-            acc[n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, xv, acc[n], 0, 0, 0);
+            const v4i w1 = __builtin_nontemporal_load(wp[n] + (size_t)kt * 64);
+            acc[n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1, x1, acc[n], 0, 0, 0);
         }
     }
 #pragma unroll
@@ -70,27 +144,33 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
         for (int r = 0; r < 16; r++) red[w][n][r][lane] = acc[n][r];
     __syncthreads();
 
-    // Epilogue: thread -> (token i, column jj of a tile) so that consecutive threads write
-    // consecutive columns.  Accumulator element (i, jj) of a tile lives in register
+    // ---- epilogue.  Accumulator element (token i, column jj) of a tile lives in register
     // r = 4*(jj/8) + jj%4 of lane l = i + 32*((jj/4)%2).
-    int cnt = *count;
-    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
-    const int jj = tid & 31;
     const int r = 4 * (jj >> 3) + (jj & 3);
     const int lsel = 32 * ((jj >> 2) & 1);
 #pragma unroll
     for (int n = 0; n < NJ; n++) {
         const int j = (jt0 + n) * 32 + jj;
         if (j >= o) continue;
-        const float cwj = f16_bits_to_float(cw[j]);
-        for (int i = tid >> 5; i < s; i += 8) {
+#pragma unroll
+        for (int m = 0; m < 4; m++) {
+            const int i = ig + 8 * m;
+            if (i >= s) continue;
             const int l = i + lsel;
             const int c = red[0][n][r][l] + red[1][n][r][l] + red[2][n][r][l] + red[3][n][r][l];
             if (Cdbg) Cdbg[(size_t)i * o + j] = c;
             // Eq. 7 dequantization, then the outlier product of Eq. 8 accumulated in fp32
-            float d = (float)c * (f16_bits_to_float(cx[i]) * (1.0f / 16129.0f)) * cwj;
-            for (int t = 0; t < cnt; t++) {
-                const unsigned k = (unsigned)idx[t];  // row of the original fp16 weights
+            float d = (float)c * sxi[m] * cwj[n];
+#pragma unroll
+            for (int t = 0; t < DSLOTS; t++)
+                if (t < cnt) {
+                    const unsigned xw = ((const unsigned*)&xo[m][t >> 3])[(t & 7) >> 1];
+                    const unsigned short xh = (unsigned short)((t & 1) ? (xw >> 16) : (xw & 0xffff));
+                    const unsigned short wh = (unsigned short)((t & 1) ? (wo[n][t >> 1] >> 16) : (wo[n][t >> 1] & 0xffff));
+                    d = __builtin_fmaf(f16_bits_to_float(xh), f16_bits_to_float(wh), d);
+                }
+            for (int t = DSLOTS; t < cnt; t++) {  // more outlier columns than were prefetched: rare
+                const unsigned k = (unsigned)idx[t];
                 if (k < (unsigned)h)
                     d = __builtin_fmaf(f16_bits_to_float(Xo[(size_t)i * opad + t]),
                                        f16_bits_to_float(Wf[(size_t)k * o + j]), d);
@@ -100,15 +180,26 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     }
 }
 
+int g_decode_cfg = -1;  // test hook, as g_force_cfg
+
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
                               const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
                               unsigned short* Out, int32_t* Cdbg, hipStream_t st)
 {
     const int KT = k_tiles(h), JT = row_tiles(o);
-    constexpr int NJ = 1, U = 8;
-    gemm_decode_kernel<NJ, U><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, idx, Xo, count, cap,
-                                                                 opad_of(cap), (_Float16*)Out, Cdbg, s, h, o);
+#define LAUNCH_DECODE(NJ, U)                                                                                     \
+    gemm_decode_kernel<NJ, U><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, idx, Xo, count, cap, \
+                                                                 opad_of(cap), (_Float16*)Out, Cdbg, s, h, o)
+    switch (g_decode_cfg) {
+        case 1: LAUNCH_DECODE(1, 8); break;
+        case 2: LAUNCH_DECODE(2, 4); break;
+        case 3: LAUNCH_DECODE(2, 8); break;
+        case 4: LAUNCH_DECODE(3, 4); break;
+        case 5: LAUNCH_DECODE(1, 4); break;
+        default: LAUNCH_DECODE(2, 4); break;
+    }
+#undef LAUNCH_DECODE
     return hipGetLastError();
 }
 

@@ -102,69 +102,124 @@ hipError_t launch_colmax_partial(const void* M, int rows, int cols, unsigned sho
 }
 
 // ---------------------------------------------------------------------------
-// Reduce the slabs, apply the threshold, and write the qualifying column
-// indices in ascending order.  One workgroup: flags are collected as wave
-// ballots per 1024-column chunk, then a prefix sum over the ballots gives
-// every set bit its position.
+// Outlier column lists.  The scan kernels cut the h columns into runs of 256;
+// run l gets the list cand[l][0 .. capc) of its columns whose maximum reaches
+// the threshold, ascending, and count[l] = how many there are (capc =
+// min(cap, 256); a longer list can only happen when |O| > cap anyway).  The
+// outlier set is the concatenation of the lists, cut off after cap entries.
+// Kernels that need it (row constants, quantizer) read the lists themselves:
+// scan_lists() gives every list its position in the overall order.
 // ---------------------------------------------------------------------------
-constexpr int CT = 1024;
 
-__global__ void __launch_bounds__(CT) outlier_compact_kernel(const unsigned short* __restrict__ part, int nslab,
-                                                             int h, unsigned thr, int32_t* __restrict__ idx,
-                                                             int cap, int32_t* __restrict__ count,
-                                                             int32_t* __restrict__ status)
+// One workgroup = 256 columns x 4 groups of slabs: reduce the slab maxima, apply the threshold, list.
+__global__ void __launch_bounds__(1024) outlier_lists_kernel(const unsigned short* __restrict__ part, int nslab,
+                                                             int h, unsigned thr, OutlierLists L, int capc)
 {
-    extern __shared__ unsigned long long ballots[];  // [nchunk * 16], then int bases[nchunk * 16]
-    __shared__ int wtot[16];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int nchunk = (h + CT - 1) / CT;
-    const int nent = nchunk * 16;
-    int* bases = (int*)(ballots + nent);
-    for (int c = 0; c < nchunk; c++) {
-        const int j = c * CT + tid;
-        unsigned m = 0;
-        if (j < h)
-            for (int sl = 0; sl < nslab; sl++) {
-                unsigned v = part[(size_t)sl * h + j];
-                m = v > m ? v : m;
+    __shared__ unsigned short red[4][256];
+    __shared__ int wcnt[4];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int c = tid & 255, g = tid >> 8;
+    const int j = blockIdx.x * 256 + c;
+    unsigned m = 0;
+    if (j < h)
+        for (int sl = g; sl < nslab; sl += 32) {  // 8 independent loads in flight
+            unsigned v[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) {
+                const int q = sl + 4 * u;
+                v[u] = q < nslab ? (unsigned)part[(size_t)q * h + j] : 0u;
             }
-        const bool f = (j < h) && (m >= thr);
-        unsigned long long b = __ballot(f);
-        if (lane == 0) ballots[c * 16 + w] = b;
-    }
+#pragma unroll
+            for (int u = 0; u < 8; u++) m = v[u] > m ? v[u] : m;
+        }
+    red[g][c] = (unsigned short)m;
     __syncthreads();
-    const int per = (nent + CT - 1) / CT;
-    const int e0 = tid * per;
-    int mine = 0;
-    for (int q = 0; q < per; q++)
-        if (e0 + q < nent) mine += __popcll(ballots[e0 + q]);
-    int incl = mine;
+    bool f = false;
+    if (g == 0) {
+        const unsigned a = red[0][c] > red[1][c] ? red[0][c] : red[1][c];
+        const unsigned b = red[2][c] > red[3][c] ? red[2][c] : red[3][c];
+        f = (j < h) && ((a > b ? a : b) >= thr);
+    }
+    const unsigned long long bal = __ballot(f);
+    if (g == 0 && lane == 0) wcnt[tid >> 6] = __popcll(bal);
+    __syncthreads();
+    if (g == 0) {
+        const int w = tid >> 6;
+        int woff = 0, total = 0;
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            if (q < w) woff += wcnt[q];
+            total += wcnt[q];
+        }
+        if (f) {
+            const int pos = woff + __popcll(bal & ((1ull << lane) - 1ull));
+            if (pos < capc) L.cand[(size_t)blockIdx.x * capc + pos] = j;
+        }
+        if (tid == 0) L.count[blockIdx.x] = total;
+    }
+}
+
+hipError_t launch_outlier_lists(const unsigned short* part, int nslab, int h, unsigned thr, OutlierLists L, int cap,
+                                hipStream_t st)
+{
+    outlier_lists_kernel<<<(h + 255) / 256, 1024, 0, st>>>(part, nslab, h, thr, L, list_capacity(cap));
+    return hipGetLastError();
+}
+
+// Positions of the lists in the overall order.  Call with all 256 threads of a workgroup; s_cnt and
+// s_base are LDS arrays of MAXLISTS ints.  Returns the total number of qualifying columns.
+__device__ inline int scan_lists(const int* __restrict__ count, int nl, int* s_cnt, int* s_base)
+{
+    __shared__ int s_wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    int c[4], sum = 0;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int l = 4 * tid + q;
+        c[q] = l < nl ? count[l] : 0;
+        sum += c[q];
+    }
+    int incl = sum;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
-        int t = __shfl_up(incl, d);
+        const int t = __shfl_up(incl, d);
         if (lane >= d) incl += t;
     }
-    if (lane == 63) wtot[w] = incl;
+    __syncthreads();  // s_wsum may still be read by a previous call
+    if (lane == 63) s_wsum[w] = incl;
     __syncthreads();
     int woff = 0, total = 0;
 #pragma unroll
-    for (int q = 0; q < 16; q++) {
-        if (q < w) woff += wtot[q];
-        total += wtot[q];
+    for (int q = 0; q < 4; q++) {
+        if (q < w) woff += s_wsum[q];
+        total += s_wsum[q];
     }
-    int run = woff + incl - mine;
-    for (int q = 0; q < per; q++)
-        if (e0 + q < nent) {
-            bases[e0 + q] = run;
-            run += __popcll(ballots[e0 + q]);
+    int run = woff + incl - sum;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int l = 4 * tid + q;
+        if (l < nl) {
+            s_cnt[l] = c[q];
+            s_base[l] = run;
         }
+        run += c[q];
+    }
     __syncthreads();
-    for (int c = 0; c < nchunk; c++) {
-        unsigned long long b = ballots[c * 16 + w];
-        if ((b >> lane) & 1ull) {
-            int pos = bases[c * 16 + w] + __popcll(b & ((1ull << lane) - 1ull));
-            if (pos < cap) idx[pos] = c * CT + tid;
-        }
+    return total;
+}
+
+// idx, count, status from the lists (the stand-alone outlier scan ends with this)
+__global__ void __launch_bounds__(256) merge_lists_kernel(OutlierLists L, int nl, int capc, int32_t* __restrict__ idx,
+                                                          int cap, int32_t* __restrict__ count,
+                                                          int32_t* __restrict__ status)
+{
+    __shared__ int s_cnt[MAXLISTS], s_base[MAXLISTS];
+    const int tid = threadIdx.x;
+    const int total = scan_lists(L.count, nl, s_cnt, s_base);
+    for (int b = tid; b < nl; b += 256) {
+        const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+        const int base = s_base[b];
+        for (int e = 0; e < n && base + e < cap; e++) idx[base + e] = L.cand[(size_t)b * capc + e];
     }
     if (tid == 0) {
         *count = total < cap ? total : cap;
@@ -172,12 +227,251 @@ __global__ void __launch_bounds__(CT) outlier_compact_kernel(const unsigned shor
     }
 }
 
-hipError_t launch_outlier_compact(const unsigned short* part, int nslab, int h, unsigned thr, int32_t* idx,
-                                  int cap, int32_t* count, int32_t* status, hipStream_t st)
+hipError_t launch_merge_lists(OutlierLists L, int h, int32_t* idx, int cap, int32_t* count, int32_t* status,
+                              hipStream_t st)
 {
-    int nchunk = (h + CT - 1) / CT;
-    size_t shm = (size_t)nchunk * 16 * (sizeof(unsigned long long) + sizeof(int));
-    outlier_compact_kernel<<<1, CT, shm, st>>>(part, nslab, h, thr, idx, cap, count, status);
+    merge_lists_kernel<<<1, 256, 0, st>>>(L, (h + 255) / 256, list_capacity(cap), idx, cap, count, status);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Short X (s <= 32 tokens), two kernels for the whole pre-pass.
+//
+// scan_small_kernel: a workgroup owns 512 columns (two lists) and sees all s
+// rows of them, so it knows which of its columns are outliers and can take
+// every row's maximum over the rest of its columns: rowpart[wg][32].
+//
+// quantize_small_kernel: every workgroup (256 features of the one row tile)
+// places the lists, reduces the partial row maxima to the row constants and
+// quantizes its features; workgroup 0 also writes idx, count, status, c_x and
+// the gathered columns Xo.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) scan_small_kernel(const unsigned short* __restrict__ X, int s, int h,
+                                                         unsigned thr, int vec_ok, OutlierLists L, int capc)
+{
+    __shared__ us8 red[4][64];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int c0 = blockIdx.x * 512 + lane * 8;
+    us8 v[8];
+    us8 m = (us8)(0);
+#pragma unroll
+    for (int r = 0; r < 8; r++) {
+        const int i = w + 4 * r;
+        v[r] = (us8)(0);
+        if (i < s && c0 < h) {
+            const unsigned short* p = X + (size_t)i * h + c0;
+            if (vec_ok) {
+                v[r] = *(const us8*)p;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    if (c0 + e < h) v[r][e] = p[e];
+            }
+        }
+        v[r] &= (unsigned short)0x7fff;
+        m = __builtin_elementwise_max(m, v[r]);
+    }
+    red[w][lane] = m;
+    __syncthreads();
+    m = __builtin_elementwise_max(__builtin_elementwise_max(red[0][lane], red[1][lane]),
+                                  __builtin_elementwise_max(red[2][lane], red[3][lane]));
+    unsigned flags = 0;
+#pragma unroll
+    for (int e = 0; e < 8; e++)
+        if (c0 + e < h && (unsigned)m[e] >= thr) flags |= 1u << e;
+    // partial row maxima over this workgroup's non-outlier columns
+#pragma unroll
+    for (int r = 0; r < 8; r++) {
+        unsigned mx = 0;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const unsigned x = ((flags >> e) & 1u) ? 0u : (unsigned)v[r][e];
+            mx = x > mx ? x : mx;
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const unsigned t = (unsigned)__shfl_xor((int)mx, d);
+            mx = t > mx ? t : mx;
+        }
+        if (lane == 0) L.rowpart[(size_t)blockIdx.x * 32 + w + 4 * r] = (unsigned short)mx;  // 0 for rows >= s
+    }
+    if (w == 0) {  // the two lists of this workgroup (lanes 0-31, lanes 32-63), ascending: lane, then bit
+        const int mine = __popc(flags);
+        int incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int t = __shfl_up(incl, d);
+            if (lane >= d) incl += t;
+        }
+        const int low = __shfl(incl, 31), all = __shfl(incl, 63);
+        const int list = blockIdx.x * 2 + (lane >> 5);
+        int pos = incl - mine - (lane >= 32 ? low : 0);
+#pragma unroll
+        for (int e = 0; e < 8; e++)
+            if ((flags >> e) & 1u) {
+                if (pos < capc) L.cand[(size_t)list * capc + pos] = c0 + e;
+                pos++;
+            }
+        if (lane == 0) L.count[list] = low;
+        if (lane == 32 && blockIdx.x * 512 + 256 < h) L.count[list] = all - low;
+    }
+}
+
+__global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned short* __restrict__ X, int s, int h,
+                                                             OutlierLists L, int capc, int vec_ok,
+                                                             int32_t* __restrict__ idx, int cap, int opad,
+                                                             int32_t* __restrict__ count,
+                                                             int32_t* __restrict__ status,
+                                                             unsigned short* __restrict__ cx,
+                                                             unsigned short* __restrict__ Xo,
+                                                             int8_t* __restrict__ Xq, int KT)
+{
+    extern __shared__ unsigned fullmap[];  // ceil(h / 32) words, used only when |O| > cap
+    __shared__ __attribute__((aligned(16))) int8_t stage[8 * TILE_BYTES];
+    __shared__ int s_cnt[MAXLISTS], s_base[MAXLISTS];
+    __shared__ unsigned s_part[8][32];
+    __shared__ unsigned s_cxb[32];
+    __shared__ unsigned bitmap[8];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int k0 = blockIdx.x * 256;
+    const int nl = (h + 255) / 256, nwg = (h + 511) / 512;
+
+    if (tid < 8) bitmap[tid] = 0;
+    const int total = scan_lists(L.count, nl, s_cnt, s_base);
+    const int cnt = total < cap ? total : cap;
+    const bool overflow = total > cap;
+
+    // ---- row constants
+    if (!overflow) {
+        const int i = tid & 31, gq = tid >> 5;
+        unsigned mx = 0;
+        for (int b = gq; b < nwg; b += 8) {
+            const unsigned t = L.rowpart[(size_t)b * 32 + i];
+            mx = t > mx ? t : mx;
+        }
+        s_part[gq][i] = mx;
+        __syncthreads();
+        if (tid < 32) {
+            unsigned m2 = 0;
+#pragma unroll
+            for (int q = 0; q < 8; q++) m2 = s_part[q][tid] > m2 ? s_part[q][tid] : m2;
+            s_cxb[tid] = m2;
+        }
+    } else {
+        // only the first cap columns count as outliers: redo the row maxima with their bitmap
+        const int nw = (h + 31) / 32;
+        for (int q = tid; q < nw; q += 256) fullmap[q] = 0;
+        __syncthreads();
+        for (int b = tid; b < nl; b += 256) {
+            const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+            for (int e = 0; e < n && s_base[b] + e < cap; e++) {
+                const unsigned j = (unsigned)L.cand[(size_t)b * capc + e];
+                atomicOr(&fullmap[j >> 5], 1u << (j & 31));
+            }
+        }
+        __syncthreads();
+        for (int i = w; i < 32; i += 4) {
+            unsigned mx = 0;
+            if (i < s)
+                for (int c = lane; c < h; c += 64) {
+                    const unsigned x =
+                        ((fullmap[c >> 5] >> (c & 31)) & 1u) ? 0u : (unsigned)(X[(size_t)i * h + c] & 0x7fff);
+                    mx = x > mx ? x : mx;
+                }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const unsigned t = (unsigned)__shfl_xor((int)mx, d);
+                mx = t > mx ? t : mx;
+            }
+            if (lane == 0) s_cxb[i] = mx;
+        }
+    }
+    // ---- outlier columns among this workgroup's 256 features: list k0 / 256
+    {
+        const int b = k0 >> 8;
+        const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+        for (int e = tid; e < n; e += 256)
+            if (s_base[b] + e < cap) {
+                const unsigned j = (unsigned)L.cand[(size_t)b * capc + e] - (unsigned)k0;
+                if (j < 256u) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+            }
+    }
+    __syncthreads();
+
+    // ---- workgroup 0: the outputs of the outlier scan, c_x, Xo
+    if (blockIdx.x == 0) {
+        for (int b = tid; b < nl; b += 256) {
+            const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+            const int base = s_base[b];
+            for (int e = 0; e < n && base + e < cap; e++) {
+                const int j = L.cand[(size_t)b * capc + e];
+                idx[base + e] = j;
+                for (int i = 0; i < s; i++) Xo[(size_t)i * opad + base + e] = X[(size_t)i * h + j];
+            }
+        }
+        for (int q = tid; q < s * opad; q += 256) {
+            const int i = q / opad, t = q - i * opad;
+            if (t >= cnt) Xo[(size_t)i * opad + t] = 0;
+        }
+        if (tid == 0) {
+            *count = cnt;
+            if (status) *status = overflow ? 1 : 0;
+        }
+        if (tid < s) cx[tid] = (unsigned short)s_cxb[tid];
+    }
+
+    // ---- codes of 32 rows x 256 features into the tiled layout
+    const int kseg = (tid & 31) * 8;
+    const int k = k0 + kseg;
+    const unsigned bits = (bitmap[kseg >> 5] >> (kseg & 31)) & 0xffu;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int r = q * 8 + (tid >> 5);
+        us8 v = (us8)(0);
+        float c = 0.0f;
+        if (r < s) {
+            c = f16_bits_to_float((unsigned short)s_cxb[r]);
+            const unsigned short* row = X + (size_t)r * h;
+            if (vec_ok && k + 8 <= h) {
+                v = *(const us8*)(row + k);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    if (k + e < h) v[e] = row[k + e];
+            }
+        }
+        unsigned lo = 0, hi = 0;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const int qv = (c > 0.0f && !((bits >> e) & 1u)) ? q8(f16_bits_to_float(v[e]), c) : 0;
+            const unsigned byte = (unsigned)qv & 0xffu;
+            if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
+        }
+        u2 pk = {lo, hi};
+        *(u2*)(stage + (kseg >> 5) * TILE_BYTES + tile_byte(r, kseg & 31)) = pk;
+    }
+    __syncthreads();
+    const int kt0 = k0 >> 5;
+#pragma unroll
+    for (int half = 0; half < 2; half++) {
+        const int off = half * 4096 + tid * 16;
+        if (kt0 + (off >> 10) < KT) *(u4*)(Xq + (size_t)kt0 * TILE_BYTES + off) = *(const u4*)(stage + off);
+    }
+}
+
+hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
+                                int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,
+                                hipStream_t st)
+{
+    const int capc = list_capacity(cap);
+    const int vec_ok = (h % 8 == 0) && aligned16(X);
+    const int KT = k_tiles(h);
+    scan_small_kernel<<<(h + 511) / 512, 256, 0, st>>>((const unsigned short*)X, s, h, thr, vec_ok, L, capc);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t shm = ((size_t)(h + 31) / 32) * sizeof(unsigned);
+    quantize_small_kernel<<<(KT * 32 + 255) / 256, 256, shm, st>>>((const unsigned short*)X, s, h, L, capc, vec_ok, idx,
+                                                                   cap, opad_of(cap), count, status, cx, Xo, Xq, KT);
     return hipGetLastError();
 }
 
@@ -263,29 +557,63 @@ hipError_t launch_quantize_weight(const void* W, int h, int o, const unsigned sh
 
 // ---------------------------------------------------------------------------
 // Row constants over the non-outlier columns, and the gathered outlier
-// columns Xo.  One workgroup per row; the outlier set is a bitmap in LDS.
+// columns Xo.  One workgroup per row; the outlier set is a bitmap in LDS,
+// built from idx / count, or (LISTS) straight from the column lists of the
+// scan, in which case workgroup 0 also writes idx, count and status.
 // ---------------------------------------------------------------------------
+template <bool LISTS>
 __global__ void __launch_bounds__(256) row_absmax_kernel(const unsigned short* __restrict__ X, int s, int h,
-                                                         const int32_t* __restrict__ idx,
-                                                         const int32_t* __restrict__ count, int cap, int opad,
-                                                         unsigned short* __restrict__ cx,
+                                                         int32_t* __restrict__ idx, int32_t* __restrict__ count,
+                                                         int32_t* __restrict__ status, OutlierLists L, int capc,
+                                                         int cap, int opad, unsigned short* __restrict__ cx,
                                                          unsigned short* __restrict__ Xo, int vec_ok)
 {
     extern __shared__ unsigned bitmap[];  // ceil(h / 32) words, then 4 words of reduction space
+    __shared__ int s_cnt[LISTS ? MAXLISTS : 1], s_base[LISTS ? MAXLISTS : 1];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int nw = (h + 31) / 32;
     unsigned* red = bitmap + nw;
-    int cnt = *count;
-    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
-    for (int q = tid; q < nw; q += 256) bitmap[q] = 0;
-    __syncthreads();
-    for (int t = tid; t < cnt; t += 256) {
-        unsigned j = (unsigned)idx[t];
-        if (j < (unsigned)h) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
-    }
-    __syncthreads();
     const int i = blockIdx.x;
     const unsigned short* row = X + (size_t)i * h;
+    int cnt;
+    for (int q = tid; q < nw; q += 256) bitmap[q] = 0;
+    if (LISTS) {
+        const int nl = (h + 255) / 256;
+        const int total = scan_lists(L.count, nl, s_cnt, s_base);  // its barriers also publish the cleared bitmap
+        cnt = total < cap ? total : cap;
+        for (int b = tid; b < nl; b += 256) {
+            const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+            const int base = s_base[b];
+            for (int e = 0; e < n && base + e < cap; e++) {
+                const int j = L.cand[(size_t)b * capc + e];
+                atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+                Xo[(size_t)i * opad + base + e] = row[j];
+                if (i == 0) idx[base + e] = j;
+            }
+        }
+        for (int t = cnt + tid; t < opad; t += 256) Xo[(size_t)i * opad + t] = 0;
+        if (i == 0 && tid == 0) {
+            *count = cnt;
+            if (status) *status = total > cap ? 1 : 0;
+        }
+    } else {
+        cnt = *count;
+        cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
+        __syncthreads();
+        for (int t = tid; t < cnt; t += 256) {
+            unsigned j = (unsigned)idx[t];
+            if (j < (unsigned)h) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+        }
+        for (int t = tid; t < opad; t += 256) {
+            unsigned short v = 0;
+            if (t < cnt) {
+                unsigned j = (unsigned)idx[t];
+                if (j < (unsigned)h) v = row[j];
+            }
+            Xo[(size_t)i * opad + t] = v;
+        }
+    }
+    __syncthreads();
     unsigned m = 0;
     if (vec_ok) {
         for (int c0 = tid * 8; c0 < h; c0 += 2048) {
@@ -315,14 +643,6 @@ __global__ void __launch_bounds__(256) row_absmax_kernel(const unsigned short* _
         unsigned b = red[2] > red[3] ? red[2] : red[3];
         cx[i] = (unsigned short)(a > b ? a : b);
     }
-    for (int t = tid; t < opad; t += 256) {
-        unsigned short v = 0;
-        if (t < cnt) {
-            unsigned j = (unsigned)idx[t];
-            if (j < (unsigned)h) v = row[j];
-        }
-        Xo[(size_t)i * opad + t] = v;
-    }
 }
 
 // ---------------------------------------------------------------------------
@@ -331,24 +651,45 @@ __global__ void __launch_bounds__(256) row_absmax_kernel(const unsigned short* _
 // pieces, coded, scattered into LDS at their tile position and written out as
 // one contiguous 8 KiB run.
 // ---------------------------------------------------------------------------
+template <bool LISTS>
 __global__ void __launch_bounds__(256) quantize_rows_kernel(const unsigned short* __restrict__ X, int s, int h,
                                                             const int32_t* __restrict__ idx,
-                                                            const int32_t* __restrict__ count, int cap,
-                                                            const unsigned short* __restrict__ cx,
+                                                            const int32_t* __restrict__ count, OutlierLists L,
+                                                            int capc, int cap, const unsigned short* __restrict__ cx,
                                                             int8_t* __restrict__ Xq, int KT, int vec_ok)
 {
     __shared__ __attribute__((aligned(16))) int8_t stage[8 * TILE_BYTES];
     __shared__ unsigned bitmap[8];
+    __shared__ int s_red[4];
     const int tid = threadIdx.x;
     const int rt = blockIdx.x;
     const int k0 = blockIdx.y * 256;
-    int cnt = *count;
-    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
     if (tid < 8) bitmap[tid] = 0;
-    __syncthreads();
-    for (int t = tid; t < cnt; t += 256) {
-        unsigned j = (unsigned)idx[t] - (unsigned)k0;
-        if (j < 256u) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+    if (LISTS) {
+        // the outlier columns among these 256 features are list k0 / 256; its position in the overall
+        // order is the number of qualifying columns before it
+        const int b = k0 >> 8;
+        int before = 0;
+        for (int l = tid; l < b; l += 256) before += L.count[l];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) before += __shfl_xor(before, d);
+        if ((tid & 63) == 0) s_red[tid >> 6] = before;
+        __syncthreads();
+        const int base = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+        const int n = L.count[b] < capc ? L.count[b] : capc;
+        for (int e = tid; e < n; e += 256)
+            if (base + e < cap) {
+                const unsigned j = (unsigned)L.cand[(size_t)b * capc + e] - (unsigned)k0;
+                if (j < 256u) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+            }
+    } else {
+        int cnt = *count;
+        cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
+        __syncthreads();
+        for (int t = tid; t < cnt; t += 256) {
+            unsigned j = (unsigned)idx[t] - (unsigned)k0;
+            if (j < 256u) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+        }
     }
     __syncthreads();
     const int kseg = (tid & 31) * 8;
@@ -398,11 +739,33 @@ hipError_t launch_quantize_rows(const void* X, int s, int h, const int32_t* idx,
     const int opad = opad_of(cap);
     int vec_ok = (h % 8 == 0) && aligned16(X);
     size_t shm = ((size_t)(h + 31) / 32 + 4) * sizeof(unsigned);
-    row_absmax_kernel<<<s, 256, shm, st>>>((const unsigned short*)X, s, h, idx, count, cap, opad, cx, Xo, vec_ok);
+    const OutlierLists none = {nullptr, nullptr, nullptr};
+    row_absmax_kernel<false><<<s, 256, shm, st>>>((const unsigned short*)X, s, h, (int32_t*)idx, (int32_t*)count,
+                                                  nullptr, none, 0, cap, opad, cx, Xo, vec_ok);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     dim3 grid(RT, (KT * 32 + 255) / 256);
-    quantize_rows_kernel<<<grid, 256, 0, st>>>((const unsigned short*)X, s, h, idx, count, cap, cx, Xq, KT, vec_ok);
+    quantize_rows_kernel<false><<<grid, 256, 0, st>>>((const unsigned short*)X, s, h, idx, count, none, 0, cap, cx, Xq,
+                                                      KT, vec_ok);
+    return hipGetLastError();
+}
+
+// the same two steps fed by the column lists of the scan; also writes idx, count, status
+hipError_t launch_quantize_rows_lists(const void* X, int s, int h, OutlierLists L, int32_t* idx, int32_t* count,
+                                      int32_t* status, int cap, int8_t* Xq, unsigned short* cx, unsigned short* Xo,
+                                      hipStream_t st)
+{
+    const int KT = k_tiles(h), RT = row_tiles(s);
+    const int opad = opad_of(cap), capc = list_capacity(cap);
+    int vec_ok = (h % 8 == 0) && aligned16(X);
+    size_t shm = ((size_t)(h + 31) / 32 + 4) * sizeof(unsigned);
+    row_absmax_kernel<true><<<s, 256, shm, st>>>((const unsigned short*)X, s, h, idx, count, status, L, capc, cap, opad,
+                                                 cx, Xo, vec_ok);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    dim3 grid(RT, (KT * 32 + 255) / 256);
+    quantize_rows_kernel<true><<<grid, 256, 0, st>>>((const unsigned short*)X, s, h, idx, count, L, capc, cap, cx, Xq, KT,
+                                                     vec_ok);
     return hipGetLastError();
 }
 

@@ -71,6 +71,19 @@ def test_every_prefill_tile_shape(cfg, forced_tile):
     full_compare(wl.make_custom(330, 128, 264, 0, seed=6))
 
 
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_every_decode_work_split(cfg):
+    import paper_2208_07339_amd as L
+    L.debug_decode_shape(cfg)
+    try:
+        full_compare(wl.make_custom(16, 1024, 2048, 5, seed=1))
+        full_compare(wl.make_custom(13, 200, 61, 2, seed=2))      # nothing aligned, last column tile ragged
+        full_compare(wl.make_custom(32, 4160, 96 * 5, 20, seed=3))  # more outlier columns than are prefetched
+        full_compare(wl.make_custom(7, 128 * 11, 64, 0, seed=4))  # odd number of k batches
+    finally:
+        L.debug_decode_shape(-1)
+
+
 def test_alpha_zero_is_pure_fp16_matmul_on_both_paths():
     d = wl.make("tiny")
     g, r = full_compare(d, alpha=0.0, cap=256)
@@ -180,6 +193,72 @@ def test_linear_entry_point_matches_step_by_step():
     out = L.linear(g["Xd"], g["qw"], 6.0, g["outl"], g["rows"], g["ws"])
     torch.cuda.synchronize()
     assert np.array_equal(bits(out.cpu().numpy()), bits(g["Out"]))
+
+
+def linear_compare(d, alpha=None, cap=32):
+    """llmint8_linear (for s <= 32 it runs the fused two-kernel pre-pass) against the oracle, stage by stage."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    alpha = d["alpha"] if alpha is None else alpha
+    X, W = d["X"], d["W"]
+    s, h = X.shape
+    o = W.shape[1]
+    Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
+    Wd = torch.from_numpy(W.view(np.int16)).cuda().view(torch.float16)
+    ws = L.Workspace.allocate(s, h, o, cap)
+    qw = L.quantize_weight(Wd, ws)
+    outl = L.Outliers(torch.full((cap,), -7, dtype=torch.int32, device="cuda"),
+                      torch.full((1,), -7, dtype=torch.int32, device="cuda"),
+                      torch.full((1,), -7, dtype=torch.int32, device="cuda"), cap)
+    rows = L.QuantizedRows(torch.full((L.xq_bytes(s, h),), 99, dtype=torch.int8, device="cuda"),
+                           torch.full((s,), 7.0, dtype=torch.float16, device="cuda"),
+                           torch.full((s, L.opad(cap)), 7.0, dtype=torch.float16, device="cuda"), s, h)
+    for _ in range(2):  # twice: the scratch of the first call must not disturb the second
+        out = L.linear(Xd, qw, alpha, outl, rows, ws)
+    torch.cuda.synchronize()
+    full = oracle.find_outliers(X, alpha)
+    want_idx = full[:cap]
+    n = int(outl.count.item())
+    assert n == len(want_idx) and int(outl.status.item()) == (1 if len(full) > cap else 0)
+    assert outl.idx[:n].cpu().numpy().tolist() == want_idx.tolist()
+    Xq, cx = oracle.quantize_rows(X, want_idx)
+    assert np.array_equal(bits(rows.cx.cpu().numpy()), bits(cx))
+    assert np.array_equal(L.export_rows(rows).cpu().numpy(), Xq)
+    Xo = rows.Xo.cpu().numpy()
+    assert np.array_equal(bits(Xo[:, :n]), bits(X[:, want_idx])) and not bits(Xo[:, n:]).any()
+    Wq, cw = oracle.quantize_weight(W)
+    ref = oracle.output(oracle.igemm(Xq, Wq), cx, cw, X, W, want_idx)
+    assert_out_close(out.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("s,h,o,ncol", [(1, 64, 32, 1), (16, 1024, 2048, 5), (13, 200, 61, 2), (32, 384, 96, 3),
+                                        (8, 4160, 128, 6), (16, 12288, 256, 7)])
+def test_linear_short_x(s, h, o, ncol):
+    linear_compare(wl.make_custom(s, h, o, ncol, seed=s * 11 + h))
+
+
+def test_linear_prefill_sizes():
+    """llmint8_linear for s > 32: the row constants and the quantizer read the scan's column lists."""
+    linear_compare(wl.make_custom(100, 512, 256, 3, seed=41))
+    linear_compare(wl.make_custom(300, 1000, 515, 4, seed=42))
+    linear_compare(wl.make_custom(257, 4160, 264, 6, seed=43))
+    linear_compare(wl.make_custom(70, 384, 96, 9, seed=44), cap=4)          # |O| > cap
+    linear_compare(wl.make_custom(40, 96, 64, 2, seed=45), alpha=0.0, cap=96)  # every column
+    linear_compare(wl.make_custom(64, 600, 64, 300, seed=46, frac=0.3), cap=300)  # a full list of 256
+    linear_compare(wl.make_custom(48, 256, 64, 0, seed=47), alpha=float("inf"))
+
+
+def test_linear_short_x_degenerate_cases():
+    linear_compare(wl.make("tiny"))
+    linear_compare(wl.make("tiny"), alpha=0.0, cap=256)           # every column an outlier
+    linear_compare(wl.make("tiny"), alpha=0.0, cap=100)           # ... and more of them than fit
+    linear_compare(wl.make("tiny"), alpha=float("inf"))           # none
+    linear_compare(wl.make_custom(24, 1536, 64, 9, seed=77), cap=4)   # |O| > cap: first cap columns only
+    linear_compare(wl.make_custom(20, 1100, 64, 600, seed=78, frac=0.3), cap=700)  # lists longer than 512 per call
+    d = wl.make_custom(12, 512, 96, 2, seed=79)
+    d["X"][5] = 0
+    linear_compare(d)
 
 
 def test_argument_errors_are_reported_not_executed():
