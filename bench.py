@@ -27,10 +27,15 @@ sys.path.insert(0, ROOT)
 INT8_MFMA_PEAK_TOPS = 5033.0   # 256 CU x 8192 int8 op/clk/CU x 2.4 GHz, dense
 HBM_PEAK_GBS = 8000.0
 CAP = 32                       # capacity of the outlier index list
+COPY_PROBE_BYTES = 256 << 20   # size of the calibration copies of --copy-probe
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/*pmc*.txt), or None while not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/bench_default_ffn13b_decode_hbm_traffic.txt: FETCH_SIZE / 0.5001 + WRITE_SIZE / 1.0 (KiB -> bytes)
+    "ffn13b": 634.28e6 + 167.77e6,   # gemm_prefill_kernel<4,4>: operand panels re-fetched per XCD and round + Out
+    "decode": 608.03e6 + 1.58e6,     # gemm_decode_kernel<2,4>
+}
 
 
 def algorithmic_bytes_decode(s, h, o, n_out):
@@ -79,16 +84,17 @@ def run_workload(name, steps, warmup, copies=1):
     torch.cuda.synchronize()
     ms_step = (time.perf_counter() - t0) * 1e3 / steps
 
-    # same steps again with HIP events around the dominant kernel (llmint8_matmul is one launch)
-    # and around the two pre-passes, on the stream the library launches on
+    # The same steps again, now with HIP events recorded by the library on its launch stream around
+    # the dominant kernel (llmint8_matmul is one launch): same back-to-back sequence, same thermal
+    # state as the timed region above.
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    for e3 in evs:
+        for e in e3:
+            e.record()  # creates the handles
+    torch.cuda.synchronize()
     for i in range(steps):
         evs[i][0].record()
-        L.find_outliers(Xd, d["alpha"], CAP, ws, outl)
-        L.quantize_rows(Xd, outl, rows)
-        evs[i][1].record()
-        L.matmul(rows, outl, qws[i % len(qws)], ws, out)
-        evs[i][2].record()
+        L.linear(Xd, qws[i % len(qws)], d["alpha"], outl, rows, ws, out, events=(evs[i][1], evs[i][2]))
     torch.cuda.synchronize()
     ms_pre = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
     ms_mm = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
@@ -110,8 +116,13 @@ def cpu_baseline(res, target_seconds=12.0):
     t0 = time.perf_counter()
     _cpu_rows(oracle, X[:r], W, Wq, cw, d["alpha"])
     per_row = (time.perf_counter() - t0) / r
-    r = int(max(1, min(s, target_seconds / max(per_row, 1e-9))))
     cores = oracle.num_threads()
+    # two rows under-use the cores: calibrate again on one row per core
+    r = min(s, cores)
+    t0 = time.perf_counter()
+    _cpu_rows(oracle, X[:r], W, Wq, cw, d["alpha"])
+    per_row = min(per_row, (time.perf_counter() - t0) / r)
+    r = int(max(1, min(s, target_seconds / max(per_row, 1e-9))))
     r = max(min(s, cores), r - r % cores) if r >= cores else r
     t0 = time.perf_counter()
     _cpu_rows(oracle, X[:r], W, Wq, cw, d["alpha"])
@@ -135,6 +146,9 @@ def main():
     ap.add_argument("--workload", default="ffn13b", choices=["ffn13b", "decode", "attn6p7b", "ffn175b_down"])
     ap.add_argument("--no-decode", action="store_true", help="skip the secondary decode measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three device-to-device copies of 256 MiB first: under rocprofv3 --pmc their "
+                         "FETCH_SIZE / WRITE_SIZE readings calibrate the counters (paper_2208_07339_amd/pmc_summary.py)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1. "
@@ -142,6 +156,14 @@ def main():
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback.")
+
+    if a.copy_probe:
+        src = torch.ones(COPY_PROBE_BYTES, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     res = run_workload(a.workload, a.steps, a.warmup, copies=2 if a.workload == "decode" else 1)
     s, h, o = res["s"], res["h"], res["o"]

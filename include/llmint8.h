@@ -118,6 +118,13 @@ int llmint8_linear(const void *X_f16, int s, int h, float alpha, const int8_t *W
                    int8_t *Xq, void *cx_f16, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
                    llmint8_stream_t stream);
 
+/* Measurement support: llmint8_linear that also records two caller-created hipEvent_t on the stream,
+ * one between the pre-pass and the matmul kernel and one after it (either may be NULL).          */
+int llmint8_linear_events(const void *X_f16, int s, int h, float alpha, const int8_t *Wq, const void *cw_f16,
+                          const void *W_f16, int o, int32_t *idx, int cap, int32_t *count, int32_t *status,
+                          int8_t *Xq, void *cx_f16, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
+                          llmint8_stream_t stream, void *ev_before_matmul, void *ev_after_matmul);
+
 /* Test/support: force the workgroup tile of the prefill GEMM (output columns x tokens):
  * 0 = 256 x 256, 1 = 192 x 256, 2 = 128 x 256, 3 = 128 x 128; -1 = choose from the shape (default).
  * Process-wide; results do not depend on it.                                  */
@@ -127,7 +134,7 @@ int llmint8_debug_prefill_tile(int cfg);
 /* Test/support: force the work split of the decode kernel (column tiles per workgroup, k-tiles per
  * load batch): 1 = 1 x 8, 2 = 2 x 4, 3 = 2 x 8, 4 = 3 x 4, 5 = 1 x 4; -1 = default.  Process-wide;
  * results do not depend on it.                                                */
-#define LLMINT8_DECODE_SHAPES 5
+#define LLMINT8_DECODE_SHAPES 11
 int llmint8_debug_decode_shape(int cfg);
 
 /* Test/support: private layouts -> plain row-major int8 ([h x o], [s x h]). */

@@ -9,7 +9,7 @@ LIB_PATH = os.path.join(HERE, "libllmint8.so")
 SYMBOLS = [
     "llmint8_status_string", "llmint8_last_hip_error", "llmint8_opad", "llmint8_wq_bytes", "llmint8_xq_bytes",
     "llmint8_workspace_bytes", "llmint8_quantize_weight", "llmint8_find_outliers",
-    "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_export_weight",
+    "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_linear_events", "llmint8_export_weight",
     "llmint8_export_rows", "llmint8_debug_prefill_tile",
     "llmint8_debug_decode_shape",
 ]
@@ -56,6 +56,8 @@ def lib():
     L.llmint8_matmul.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     L.llmint8_linear.restype = i32
     L.llmint8_linear.argtypes = [vp, i32, i32, f32, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.llmint8_linear_events.restype = i32
+    L.llmint8_linear_events.argtypes = L.llmint8_linear.argtypes + [vp, vp]
     L.llmint8_export_weight.restype = i32
     L.llmint8_export_weight.argtypes = [vp, i32, i32, vp, vp]
     L.llmint8_export_rows.restype = i32
@@ -198,15 +200,21 @@ def matmul(rows, outl, qw, ws, out=None, want_c_i32=False):
     return (out, Cd) if want_c_i32 else out
 
 
-def linear(X, qw, alpha, outl, rows, ws, out=None):
-    """llmint8_linear: the three per-call steps in one C call, into preallocated buffers."""
+def linear(X, qw, alpha, outl, rows, ws, out=None, events=None):
+    """llmint8_linear: the three per-call steps in one C call, into preallocated buffers.
+    events = (before_matmul, after_matmul): two torch.cuda.Event(enable_timing=True) that have been
+    recorded once already (so that their handles exist); llmint8_linear_events records them again."""
     torch = _torch()
     s, h = X.shape
     if out is None:
         out = torch.empty((s, qw.o), dtype=torch.float16, device=X.device)
-    _check(lib().llmint8_linear(_ptr(X), s, h, float(alpha), _ptr(qw.Wq), _ptr(qw.cw), _ptr(qw.W), qw.o,
-                                _ptr(outl.idx), outl.cap, _ptr(outl.count), _ptr(outl.status), _ptr(rows.Xq),
-                                _ptr(rows.cx), _ptr(rows.Xo), _ptr(out), _ptr(ws.buf), ws.nbytes, _stream()))
+    args = (_ptr(X), s, h, float(alpha), _ptr(qw.Wq), _ptr(qw.cw), _ptr(qw.W), qw.o, _ptr(outl.idx), outl.cap,
+            _ptr(outl.count), _ptr(outl.status), _ptr(rows.Xq), _ptr(rows.cx), _ptr(rows.Xo), _ptr(out),
+            _ptr(ws.buf), ws.nbytes, _stream())
+    if events is None:
+        _check(lib().llmint8_linear(*args))
+    else:
+        _check(lib().llmint8_linear_events(*args, C.c_void_p(events[0].cuda_event), C.c_void_p(events[1].cuda_event)))
     return out
 
 

@@ -144,9 +144,10 @@ int llmint8_matmul(const int8_t* Xq, const void* cx_f16, const void* Xo_f16, con
     return hip_status(e);
 }
 
-int llmint8_linear(const void* X_f16, int s, int h, float alpha, const int8_t* Wq, const void* cw_f16,
-                   const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status, int8_t* Xq,
-                   void* cx_f16, void* Xo_f16, void* Out_f16, void* ws, size_t ws_bytes, llmint8_stream_t stream)
+static int linear_impl(const void* X_f16, int s, int h, float alpha, const int8_t* Wq, const void* cw_f16,
+                       const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status, int8_t* Xq,
+                       void* cx_f16, void* Xo_f16, void* Out_f16, void* ws, size_t ws_bytes, llmint8_stream_t stream,
+                       hipEvent_t ev_before, hipEvent_t ev_after)
 {
     // validate everything before anything is enqueued
     if (!X_f16 || !idx || !count || !ws || !Xq || !cx_f16 || !Xo_f16 || !Wq || !cw_f16 || !W_f16 || !Out_f16 || s < 1 ||
@@ -176,9 +177,29 @@ int llmint8_linear(const void* X_f16, int s, int h, float alpha, const int8_t* W
             e = launch_quantize_rows_lists(X_f16, s, h, L, idx, count, status, cap, Xq, (unsigned short*)cx_f16,
                                            (unsigned short*)Xo_f16, st);
     }
+    if (e == hipSuccess && ev_before) e = hipEventRecord(ev_before, st);
     if (e != hipSuccess) return hip_status(e);
-    return llmint8_matmul(Xq, cx_f16, Xo_f16, idx, count, cap, Wq, cw_f16, W_f16, s, h, o, Out_f16, nullptr, ws,
-                          ws_bytes, stream);
+    const int r = llmint8_matmul(Xq, cx_f16, Xo_f16, idx, count, cap, Wq, cw_f16, W_f16, s, h, o, Out_f16, nullptr,
+                                 ws, ws_bytes, stream);
+    if (r == LLMINT8_OK && ev_after) return hip_status(hipEventRecord(ev_after, st));
+    return r;
+}
+
+int llmint8_linear(const void* X_f16, int s, int h, float alpha, const int8_t* Wq, const void* cw_f16,
+                   const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status, int8_t* Xq,
+                   void* cx_f16, void* Xo_f16, void* Out_f16, void* ws, size_t ws_bytes, llmint8_stream_t stream)
+{
+    return linear_impl(X_f16, s, h, alpha, Wq, cw_f16, W_f16, o, idx, cap, count, status, Xq, cx_f16, Xo_f16, Out_f16,
+                       ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+int llmint8_linear_events(const void* X_f16, int s, int h, float alpha, const int8_t* Wq, const void* cw_f16,
+                          const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status,
+                          int8_t* Xq, void* cx_f16, void* Xo_f16, void* Out_f16, void* ws, size_t ws_bytes,
+                          llmint8_stream_t stream, void* ev_before_matmul, void* ev_after_matmul)
+{
+    return linear_impl(X_f16, s, h, alpha, Wq, cw_f16, W_f16, o, idx, cap, count, status, Xq, cx_f16, Xo_f16, Out_f16,
+                       ws, ws_bytes, stream, (hipEvent_t)ev_before_matmul, (hipEvent_t)ev_after_matmul);
 }
 
 int llmint8_debug_prefill_tile(int cfg)

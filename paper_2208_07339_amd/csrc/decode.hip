@@ -197,6 +197,12 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
         case 3: LAUNCH_DECODE(2, 8); break;
         case 4: LAUNCH_DECODE(3, 4); break;
         case 5: LAUNCH_DECODE(1, 4); break;
+        case 6: LAUNCH_DECODE(2, 2); break;
+        case 7: LAUNCH_DECODE(2, 6); break;
+        case 8: LAUNCH_DECODE(4, 2); break;
+        case 9: LAUNCH_DECODE(3, 3); break;
+        case 10: LAUNCH_DECODE(4, 3); break;
+        case 11: LAUNCH_DECODE(2, 3); break;
         default: LAUNCH_DECODE(2, 4); break;
     }
 #undef LAUNCH_DECODE

@@ -336,6 +336,38 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
     const int k0 = blockIdx.x * 256;
     const int nl = (h + 255) / 256, nwg = (h + 511) / 512;
 
+    // Everything whose address is known is requested first, so that the latencies overlap: this
+    // thread's 8 features of 4 rows, and its share of the partial row maxima.
+    const int kseg = (tid & 31) * 8;
+    const int k = k0 + kseg;
+    us8 xv[4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int r = q * 8 + (tid >> 5);
+        xv[q] = (us8)(0);
+        if (r < s) {
+            const unsigned short* row = X + (size_t)r * h;
+            if (vec_ok && k + 8 <= h) {
+                xv[q] = *(const us8*)(row + k);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    if (k + e < h) xv[q][e] = row[k + e];
+            }
+        }
+    }
+    unsigned rp_max = 0;  // max over workgroups gq, gq+8, .. of rowpart[.][i]
+    {
+        const int i = tid & 31, gq = tid >> 5;
+        for (int b = gq; b < nwg; b += 32) {  // 4 independent loads in flight
+            unsigned t4[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) t4[u] = (b + 8 * u < nwg) ? (unsigned)L.rowpart[(size_t)(b + 8 * u) * 32 + i] : 0u;
+#pragma unroll
+            for (int u = 0; u < 4; u++) rp_max = t4[u] > rp_max ? t4[u] : rp_max;
+        }
+    }
+
     if (tid < 8) bitmap[tid] = 0;
     const int total = scan_lists(L.count, nl, s_cnt, s_base);
     const int cnt = total < cap ? total : cap;
@@ -343,13 +375,7 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
 
     // ---- row constants
     if (!overflow) {
-        const int i = tid & 31, gq = tid >> 5;
-        unsigned mx = 0;
-        for (int b = gq; b < nwg; b += 8) {
-            const unsigned t = L.rowpart[(size_t)b * 32 + i];
-            mx = t > mx ? t : mx;
-        }
-        s_part[gq][i] = mx;
+        s_part[tid >> 5][tid & 31] = rp_max;
         __syncthreads();
         if (tid < 32) {
             unsigned m2 = 0;
@@ -421,25 +447,12 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
     }
 
     // ---- codes of 32 rows x 256 features into the tiled layout
-    const int kseg = (tid & 31) * 8;
-    const int k = k0 + kseg;
     const unsigned bits = (bitmap[kseg >> 5] >> (kseg & 31)) & 0xffu;
 #pragma unroll
     for (int q = 0; q < 4; q++) {
         const int r = q * 8 + (tid >> 5);
-        us8 v = (us8)(0);
-        float c = 0.0f;
-        if (r < s) {
-            c = f16_bits_to_float((unsigned short)s_cxb[r]);
-            const unsigned short* row = X + (size_t)r * h;
-            if (vec_ok && k + 8 <= h) {
-                v = *(const us8*)(row + k);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; e++)
-                    if (k + e < h) v[e] = row[k + e];
-            }
-        }
+        const us8 v = xv[q];
+        const float c = (r < s) ? f16_bits_to_float((unsigned short)s_cxb[r]) : 0.0f;
         unsigned lo = 0, hi = 0;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
