@@ -115,10 +115,11 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     }
     const int wp = w >> 1, wq = w & 1;              // wave position: column half, token half
     const int J0w = pj * 64 * WA, I0w = qi * 64 * WB;  // first column / token of the workgroup
-    const bool interior = g.fast_ok && !g.Cdbg && (J0w + 64 * WA <= o) && (I0w + 64 * WB <= s);
-
     int cnt = *g.count;
     cnt = cnt < 0 ? 0 : (cnt > g.cap ? g.cap : cnt);
+    // interior tiles with at most OSLOTS outlier columns take the epilogue that is fed from LDS and has no guards
+    const bool interior =
+        g.fast_ok && !g.Cdbg && cnt <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 64 * WB <= s);
     // lane t < 32 keeps the weight row of outlier slot t (row 0 for unused slots: finite values that
     // meet the zeros of Xo)
     int myk = 0;
@@ -383,15 +384,25 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                     for (int bb = 0; bb < 2; bb++) {
                         if (b0 + bb >= WB) break;
                         const int b = b0 + bb;
+                        // Eq. 8: outlier product first (fp32 accumulation in the matrix unit), then one fused
+                        // multiply-add per output puts the dequantized int8 product (Eq. 7) on top
                         v16f d;
+                        if (cnt > 0) {
+                            v16f t = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                            t = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[aa][0], xb[b][0], t, 0, 0, 0);
+                            if (cnt > 16) t = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[aa][1], xb[b][1], t, 0, 0, 0);
+                            if (!FAST)
+                                for (int t0 = OSLOTS; t0 < cnt; t0 += 16) {  // more than 32 outlier columns: rare
+                                    const v8h wm = load_w_mem(J0 + a * 32 + ll, t0);
+                                    const v8h xm = load_x_mem(I0 + b * 32 + ll, t0);
+                                    t = __builtin_amdgcn_mfma_f32_32x32x16_f16(wm, xm, t, 0, 0, 0);
+                                }
 #pragma unroll
-                        for (int r = 0; r < 16; r++) d[r] = (float)acc[a][b][r] * sx[b] * cwv[aa][r];
-                        if (cnt > 0) d = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[aa][0], xb[b][0], d, 0, 0, 0);
-                        if (cnt > 16) d = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[aa][1], xb[b][1], d, 0, 0, 0);
-                        for (int t0 = OSLOTS; t0 < cnt; t0 += 16) {  // more than 32 outlier columns: rare
-                            const v8h wm = load_w_mem(J0 + a * 32 + ll, t0);
-                            const v8h xm = load_x_mem(I0 + b * 32 + ll, t0);
-                            d = __builtin_amdgcn_mfma_f32_32x32x16_f16(wm, xm, d, 0, 0, 0);
+                            for (int r = 0; r < 16; r++)
+                                d[r] = __builtin_fmaf((float)acc[a][b][r] * sx[b], cwv[aa][r], t[r]);
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 16; r++) d[r] = (float)acc[a][b][r] * sx[b] * cwv[aa][r];
                         }
                         // staging row of token tl (0..63): 128 bytes = 8 chunks of 16, chunk q stored at
                         // q ^ ((tl >> 1) & 7) to spread the banks
