@@ -70,6 +70,13 @@ struct GemmArgs {
 // that bring c_w, c_x, the gathered outlier columns Xo and rows O of the
 // original fp16 weights into the ring slots that fall free first, so that the
 // epilogue finds them in LDS without having waited for them.
+//
+// Workgroups are persistent: the grid is one workgroup per compute unit and
+// each walks its share of the tiles.  The first two stages of the next tile
+// are requested before the epilogue of the current one starts (into the two
+// slots its last two stages leave), the next two right after it (into the
+// slots of the epilogue stages), so a tile does not start with an empty
+// pipeline.  Ring slots are addressed relative to a per-tile base for that.
 // ---------------------------------------------------------------------------
 constexpr int NB = 4;
 constexpr int OSLOTS = 32;  // outlier slots staged through LDS; more are read from memory directly
@@ -83,43 +90,30 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     constexpr int NMFMA = 2 * WA * WB;
     constexpr int NRD = 2 * (WA + WB);
     constexpr int NOPS = PIECES + NRD;
-    constexpr int NEW = 4 * WA;                  // epilogue-stage pieces holding W rows: [32 slots][64*WA columns] fp16
-    constexpr int NEX = 4 * WB;                  // pieces holding Xo: [64*WB tokens][32 slots] fp16
+    constexpr int NEW = 16;                      // epilogue-stage pieces holding W rows: [32 slots][256 columns] fp16
+    constexpr int NEX = 4 * WB;                  // pieces holding Xo: [64*WB tokens][opad <= 32 slots] fp16
     static_assert(NEW + NEX + 1 <= 8 * PIECES, "epilogue operands must fit two stages");
-    static_assert(2 * STAGE >= 32768, "output staging needs 8 KiB per wave");
 
     extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int s = g.s, h = g.h, o = g.o, KT = g.KT, opad = g.opad;
+    const int wp = w >> 1, wq = w & 1;  // wave position: column half, token half
 
-    // ---- workgroup -> output tile.  Hardware deals consecutive workgroup ids
-    // round-robin to the 8 XCDs; give each XCD a contiguous run of the tile
-    // order so that tiles sharing operand panels meet in one L2.  Within the
-    // order, bands of 4 token blocks are walked column block by column block.
-    int pj, qi;
-    {
-        const int nP = g.nP, nQ = g.nQ;
-        const int total = nP * nQ;
-        const int wg = blockIdx.x;
-        const int xcd = wg & 7, within = wg >> 3;
-        const int base = total >> 3, rem = total & 7;
-        const int logical = xcd * base + (xcd < rem ? xcd : rem) + within;
-        constexpr int BAND = 4;
-        const int band = logical / (BAND * nP);
-        const int inband = logical - band * BAND * nP;
-        const int q0 = band * BAND;
-        const int bh = (nQ - q0) < BAND ? (nQ - q0) : BAND;  // rows in this band
-        pj = inband / bh;
-        qi = q0 + inband - pj * bh;
-    }
-    const int wp = w >> 1, wq = w & 1;              // wave position: column half, token half
-    const int J0w = pj * 64 * WA, I0w = qi * 64 * WB;  // first column / token of the workgroup
+    // ---- this workgroup's tiles.  Hardware deals consecutive workgroup ids round-robin to the 8
+    // XCDs; each XCD gets a contiguous run of the tile order, so that tiles sharing operand panels
+    // meet in one L2, and its workgroups walk that run side by side.  Within the order, bands of 4
+    // token blocks are walked column block by column block.
+    const int total = g.nP * g.nQ;
+    const int xcd = blockIdx.x & 7;
+    const int x0 = xcd * (total >> 3) + (xcd < (total & 7) ? xcd : (total & 7));  // first tile of the XCD's run
+    const int n_x = (total >> 3) + (xcd < (total & 7) ? 1 : 0);                  // its length
+    const int gx = ((int)gridDim.x - xcd + 7) >> 3;                              // workgroups on this XCD
+    int pos = blockIdx.x >> 3;
+    if (pos >= n_x) return;
+
     int cnt = *g.count;
     cnt = cnt < 0 ? 0 : (cnt > g.cap ? g.cap : cnt);
-    // interior tiles with at most OSLOTS outlier columns take the epilogue that is fed from LDS and has no guards
-    const bool interior =
-        g.fast_ok && !g.Cdbg && cnt <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 64 * WB <= s);
     // lane t < 32 keeps the weight row of outlier slot t (row 0 for unused slots: finite values that
     // meet the zeros of Xo)
     int myk = 0;
@@ -127,49 +121,72 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         const unsigned k = (unsigned)g.idx[lane & 31];
         myk = k < (unsigned)h ? (int)k : 0;
     }
+    // once per kernel: with this load known to be complete, the compiler has no reason to drain the
+    // direct-to-LDS loads in flight when myk is used later in the K pipeline
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
 
-    // ---- loader role: piece p = w*PIECES + k of a stage is k-half (p & 1) of row tile p >> 1
-    // (W tiles first, then X tiles); it lands at byte p * 1024 of the stage's ring slot.
+    // ---- loader state: the tile whose stages are being requested.
+    // Piece p = w*PIECES + k of a stage is k-half (p & 1) of row tile p >> 1 (W tiles first, then
+    // X tiles); it lands at byte p * 1024 of the stage's ring slot.
     const unsigned voff = lane * 16;
     const int8_t* gpp[PIECES];
+    int J0w, I0w;   // first column / token of the tile
+    bool interior;  // its epilogue is fed from LDS and needs no guards
+    auto set_loader = [&](int logical) {
+        constexpr int BAND = 4;
+        const int nP = g.nP, nQ = g.nQ;
+        const int band = logical / (BAND * nP);
+        const int inband = logical - band * BAND * nP;
+        const int q0 = band * BAND;
+        const int bh = (nQ - q0) < BAND ? (nQ - q0) : BAND;  // token blocks in this band
+        const int pj = inband / bh;
+        const int qi = q0 + inband - pj * bh;
+        J0w = pj * 64 * WA;
+        I0w = qi * 64 * WB;
+        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 64 * WB <= s);
 #pragma unroll
-    for (int k = 0; k < PIECES; k++) {
-        const int p = w * PIECES + k;
-        const int r = p >> 1;
-        const int8_t* base;
-        if (r < TW) {
-            int t = pj * TW + r;
-            t = t < g.JT ? t : g.JT - 1;  // rows past the matrix re-read the last tile, results unused
-            base = g.Wq + (size_t)t * KT * TILE_BYTES;
-        } else {
-            int t = qi * TX + (r - TW);
-            t = t < g.RT ? t : g.RT - 1;
-            base = g.Xq + (size_t)t * KT * TILE_BYTES;
+        for (int k = 0; k < PIECES; k++) {
+            const int p = w * PIECES + k;
+            const int r = p >> 1;
+            const int8_t* base;
+            if (r < TW) {
+                int t = pj * TW + r;
+                t = t < g.JT ? t : g.JT - 1;  // rows past the matrix re-read the last tile, results unused
+                base = g.Wq + (size_t)t * KT * TILE_BYTES;
+            } else {
+                int t = qi * TX + (r - TW);
+                t = t < g.RT ? t : g.RT - 1;
+                base = g.Xq + (size_t)t * KT * TILE_BYTES;
+            }
+            gpp[k] = base + (p & 1) * TILE_BYTES;
         }
-        gpp[k] = base + (p & 1) * TILE_BYTES;
-    }
+    };
+    set_loader(x0 + pos);
     const int nst = KT / 2;   // KT is a multiple of 4, so nst is even and >= 2
+    int sbase = 0;            // ring slot of the current tile's stage 0 (0 or 2); stage v sits in slot (sbase + v) % NB
 
-    // source of piece n (0 .. 8*PIECES-1) of the epilogue stages, per lane
+    // Source of piece n (0 .. 8*PIECES-1) of the epilogue stages, per lane.  Layout of the two stages:
+    // pieces 0..15: rows O of W_f16, [32 slots][256 columns] (a slot row is 512 bytes whatever WA is; lanes past
+    // the tile's 64*WA columns repeat chunk 0); then 4*WB pieces of Xo, [64*WB tokens][opad slots] as it lies in
+    // memory; then one piece with c_w (lanes 0-31) and c_x (lanes 32-63); the rest repeats that piece.
     auto esrc = [&](int n) -> const void* {
-        if (!interior) return g.Xq + voff;  // edge tiles read their epilogue operands from memory later
+        // The addresses depend on the tile only; the opaque copy of the lane number keeps the compiler from
+        // computing all of them at the start of the tile and carrying them through the K loop in registers.
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        if (!interior) return g.Xq + ln * 16;  // edge tiles read their epilogue operands from memory later
+        const int wchunk = ((ln & 31) < 8 * WA ? (ln & 31) : 0) * 8;  // column offset of this lane in a W row
         if (n < NEW) {
-            const int f = n * 64 + lane;
-            const int t = f / (8 * WA), cc = f % (8 * WA);
-            const int k = __shfl(myk, t);
-            return g.Wf + ((size_t)k * o + J0w + cc * 8);
+            const int k0 = __builtin_amdgcn_readlane(myk, 2 * n), k1 = __builtin_amdgcn_readlane(myk, 2 * n + 1);
+            const int k = (ln >> 5) ? k1 : k0;  // the piece holds slots 2n (lanes 0-31) and 2n+1 (lanes 32-63)
+            return g.Wf + ((size_t)k * o + J0w + wchunk);
         }
         if (n < NEW + NEX) {
-            const int f = (n - NEW) * 64 + lane;
-            int ch = f & 3;
-            if (opad < 32) ch &= 1;  // slots 16..31 do not exist (and are not used: cnt <= 16)
-            return g.Xo + ((size_t)(I0w + (f >> 2)) * opad + ch * 8);
+            const int pn = (n - NEW) * 32 < NEX * opad ? (n - NEW) : 0;  // opad == 16: half as many pieces
+            return g.Xo + ((size_t)I0w * opad + pn * 512 + ln * 8);
         }
-        if (lane < 32) {
-            const int c = lane < 8 * WA ? lane : 8 * WA - 1;
-            return g.cw + (J0w + c * 8);
-        }
-        const int c = (lane - 32) < 8 * WB ? (lane - 32) : 8 * WB - 1;
+        if (ln < 32) return g.cw + (J0w + wchunk);
+        const int c = (ln - 32) < 8 * WB ? (ln - 32) : 0;
         return g.cx + (I0w + c * 8);
     };
     // request piece k of operand stage v / of epilogue stage e into ring slot `slot`
@@ -183,13 +200,6 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     };
 
     v16i acc[WA][WB];
-#pragma unroll
-    for (int a = 0; a < WA; a++)
-#pragma unroll
-        for (int b = 0; b < WB; b++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[a][b][r] = 0;
-
     // operand registers of two stages: [set][k-step][tile]
     v4i RP[2][2][WA], RQ[2][2][WB];
     const int8_t* Pl = lds + (wp * WA) * 2 * TILE_BYTES + lane * 16;
@@ -203,22 +213,16 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         else
             RQ[SS][c][t - WA] = *(const v4i*)(Ql + slot * STAGE + ((t - WA) * 2 + c) * TILE_BYTES);
     };
-
-    // prologue: the first NB stages (nv >= NB always; with nst == 2 the epilogue stages are among them)
-#pragma unroll
-    for (int v = 0; v < NB; v++) {
+    // request all pieces of stage v (operand stage, or epilogue stage v - nst) of the loader tile
+    auto issue_stage = [&](int v, int slot) {
         if (v < nst) {
 #pragma unroll
-            for (int k = 0; k < PIECES; k++) dma_k(v, v, k);
+            for (int k = 0; k < PIECES; k++) dma_k(v, slot, k);
         } else {
 #pragma unroll
-            for (int k = 0; k < PIECES; k++) dma_e(v - nst, v, k);
+            for (int k = 0; k < PIECES; k++) dma_e(v - nst, slot, k);
         }
-    }
-    STAGE_SYNC((NB - 1) * PIECES);
-#pragma unroll
-    for (int i = 0; i < NRD; i++) rd(std::integral_constant<int, 0>{}, 0, i);
-    FENCE();
+    };
 
     // One stage: MFMAs from register set S, interleaved with the requests of stage st+NB into the
     // slot of stage st and the reads of stage st+1 into the other register set.
@@ -231,7 +235,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         // are complete; after the barrier the same holds for every wave.
         STAGE_SYNC((NB - 2) * PIECES);
         FENCE();
-        const int slot = st % NB, nslot = (st + 1) % NB;
+        const int slot = (sbase + st) % NB, nslot = (sbase + st + 1) % NB;
 #pragma unroll
         for (int i = 0; i < NMFMA; i++) {
             const int c = i / (WA * WB), a = (i / WB) % WA, b = i % WB;
@@ -251,205 +255,262 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     };
     using I0_ = std::integral_constant<int, 0>;
     using I1_ = std::integral_constant<int, 1>;
-    int st = 0;
-    for (; st + 6 <= nst; st += 2) {
-        stage(I0_{}, I0_{}, st);
-        stage(I1_{}, I0_{}, st + 1);
-    }
-    if (nst >= 4) {  // st == nst - 4
-        stage(I0_{}, std::integral_constant<int, 1>{}, st);
-        stage(I1_{}, std::integral_constant<int, 2>{}, st + 1);
-        st += 2;
-    }
-    stage(I0_{}, std::integral_constant<int, 3>{}, st);
-    stage(I1_{}, std::integral_constant<int, 4>{}, st + 1);
-    STAGE_SYNC(0);  // the epilogue stages have landed, every wave is done with the operand slots
 
-    // ---- epilogue ----------------------------------------------------------
-    // acc[a][b][r] of lane l: token i = I0 + b*32 + (l & 31),
-    //                         column j = J0 + a*32 + 8*(r >> 2) + 4*(l >> 5) + (r & 3)
-    const int J0 = J0w + wp * 32 * WA;
-    const int I0 = I0w + wq * 32 * WB;
-    const int gl = lane >> 5, ll = lane & 31;
+    // stages 0 and 1 of the first tile (later tiles get theirs before the epilogue of the tile before)
+    issue_stage(0, 0);
+    issue_stage(1, 1);
 
-    const int eslot = nst % NB;                       // 0 or 2; the second epilogue stage follows it
-    const int8_t* E = lds + eslot * STAGE;
-    const unsigned short* EW = (const unsigned short*)E;                               // [32][64*WA]
-    const int8_t* EX = E + NEW * TILE_BYTES;                                           // [64*WB][32] fp16
-    const unsigned short* ECw = (const unsigned short*)(E + (NEW + NEX) * TILE_BYTES); // [64*WA]
-    const unsigned short* ECx = ECw + 256;                                             // [64*WB]
-    // output staging in the two ring slots that hold no epilogue operands: NSTG buffers of 8 KiB per wave
-    constexpr int NSTG = (2 * STAGE >= 65536) ? 2 : 1;
-    int8_t* stg = lds + ((eslot + 2) % NB) * STAGE + w * (8192 * NSTG);
-
-    // rows O of the fp16 weights for column jcol, outlier slots t0 + 8*gl .. +7, straight from memory
-    auto load_w_mem = [&](int jcol, int t0) {
-        v8h wa;
+    for (;;) {  // tiles of this workgroup
+        const int cJ0w = J0w, cI0w = I0w;  // the tile being computed (the loader moves on before its epilogue)
+        const bool cinterior = interior;
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const int t = t0 + 8 * gl + e;
-            unsigned short v = 0;
-            if (t < cnt && jcol < o) {
-                const unsigned k = (unsigned)g.idx[t];
-                if (k < (unsigned)h) v = g.Wf[(size_t)k * o + jcol];
-            }
-            wa[e] = __builtin_bit_cast(_Float16, v);
+        for (int a = 0; a < WA; a++)
+#pragma unroll
+            for (int b = 0; b < WB; b++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[a][b][r] = 0;
+        // Stage 0 has landed once at most the pieces of stage 1 are in flight (stores of the previous
+        // epilogue can only make this wait longer).  The barrier also tells that every wave is done with
+        // the previous tile's epilogue stages, whose slots take stages 2 and 3 (with nst == 2: this
+        // tile's own epilogue stages) once stage 0 is on its way into registers.
+        STAGE_SYNC(PIECES);
+#pragma unroll
+        for (int i = 0; i < NRD; i++) rd(I0_{}, sbase, i);
+        FENCE();
+        issue_stage(2, (sbase + 2) % NB);
+        issue_stage(3, (sbase + 3) % NB);
+        FENCE();
+        int st = 0;
+        for (; st + 6 <= nst; st += 2) {
+            stage(I0_{}, I0_{}, st);
+            stage(I1_{}, I0_{}, st + 1);
         }
-        return wa;
-    };
-    auto load_x_mem = [&](int i, int t0) {
-        v8h xb = (v8h)(0);
-        if (i < s) xb = *(const v8h*)(g.Xo + (size_t)i * opad + t0 + 8 * gl);
-        return xb;
-    };
+        if (nst >= 4) {  // st == nst - 4
+            stage(I0_{}, std::integral_constant<int, 1>{}, st);
+            stage(I1_{}, std::integral_constant<int, 2>{}, st + 1);
+            st += 2;
+        }
+        stage(I0_{}, std::integral_constant<int, 3>{}, st);
+        stage(I1_{}, std::integral_constant<int, 4>{}, st + 1);
+        STAGE_SYNC(0);  // the epilogue stages have landed, every wave is done with the operand slots
 
-    // FAST: interior tile, operands from the LDS image of the epilogue stages, no guards.
-    // Otherwise: operands from memory, every access guarded; also exports the raw accumulators.
-    auto epilogue = [&](auto F) {
-        constexpr bool FAST = decltype(F)::value;
-        if (!FAST && g.Cdbg) {
+        const int eslot = (sbase + nst) % NB;  // 0 or 2; the second epilogue stage follows it
+        const bool has_next = pos + gx < n_x;
+        if (has_next) {
+            // next tile: its stages 0 and 1 go to the slots of this tile's last two stages
+            set_loader(x0 + pos + gx);
+            issue_stage(0, (eslot + 2) % NB);
+            issue_stage(1, (eslot + 3) % NB);
+        }
+
+        // ---- epilogue ----------------------------------------------------------
+        // acc[a][b][r] of lane l: token i = I0 + b*32 + (l & 31),
+        //                         column j = J0 + a*32 + 8*(r >> 2) + 4*(l >> 5) + (r & 3)
+        const int J0 = cJ0w + wp * 32 * WA;
+        const int I0 = cI0w + wq * 32 * WB;
+        // lane-derived offsets are taken from an opaque copy of the lane number, so that they are recomputed
+        // here for every tile instead of being carried through the K loop in registers
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        const int gl = lane_e >> 5, ll = lane_e & 31;
+
+        const int8_t* E = lds + eslot * STAGE;
+        const unsigned short* EW = (const unsigned short*)E;                               // [32][256]
+        const int8_t* EX = E + NEW * TILE_BYTES;                                           // [64*WB][opad] fp16
+        const unsigned short* ECw = (const unsigned short*)(E + (NEW + NEX) * TILE_BYTES); // [64*WA]
+        const unsigned short* ECx = ECw + 256;                                             // [64*WB]
+        // output staging behind the ring (the ring slots are busy with the next tile): 8 KiB per wave
+        constexpr int NSTG = 1;
+        int8_t* stg = lds + NB * STAGE + w * (8192 * NSTG);
+
+        // rows O of the fp16 weights for column jcol, outlier slots t0 + 8*gl .. +7, straight from memory
+        auto load_w_mem = [&](int jcol, int t0) {
+            v8h wa;
 #pragma unroll
-            for (int a = 0; a < WA; a++)
-#pragma unroll
-                for (int b = 0; b < WB; b++) {
-                    const int i = I0 + b * 32 + ll;
-#pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const int j = J0 + a * 32 + 8 * (r >> 2) + 4 * gl + (r & 3);
-                        if (i < s && j < o) g.Cdbg[(size_t)i * o + j] = acc[a][b][r];
-                    }
+            for (int e = 0; e < 8; e++) {
+                const int t = t0 + 8 * gl + e;
+                unsigned short v = 0;
+                if (t < cnt && jcol < o) {
+                    const unsigned k = (unsigned)g.idx[t];
+                    if (k < (unsigned)h) v = g.Wf[(size_t)k * o + jcol];
                 }
-        }
-        float sx[WB];      // c_x / 127^2 of this lane's tokens (Eq. 7: S = c_x (x) c_w / 127^2)
-        v8h xb[WB][2];     // MFMA "B" operand of the outlier product: slots 8*gl .. +7 (+16) of this lane's tokens
-#pragma unroll
-        for (int b = 0; b < WB; b++) {
-            const int il = wq * 32 * WB + b * 32 + ll;  // token within the workgroup tile
-            const int i = I0w + il;
-            if (FAST) {
-                sx[b] = f16_bits_to_float(ECx[il]) * (1.0f / 16129.0f);
-                xb[b][0] = *(const v8h*)(EX + il * 64 + gl * 16);
-                xb[b][1] = *(const v8h*)(EX + il * 64 + (2 + gl) * 16);
-            } else {
-                sx[b] = (i < s) ? f16_bits_to_float(g.cx[i]) * (1.0f / 16129.0f) : 0.0f;
-                xb[b][0] = cnt > 0 ? load_x_mem(i, 0) : (v8h)(0);
-                xb[b][1] = cnt > 16 ? load_x_mem(i, 16) : (v8h)(0);
+                wa[e] = __builtin_bit_cast(_Float16, v);
             }
-        }
-        int unit = 0;
+            return wa;
+        };
+        auto load_x_mem = [&](int i, int t0) {
+            v8h xb = (v8h)(0);
+            if (i < s) xb = *(const v8h*)(g.Xo + (size_t)i * opad + t0 + 8 * gl);
+            return xb;
+        };
+
+        // FAST: interior tile, operands from the LDS image of the epilogue stages, no guards.
+        // Otherwise: operands from memory, every access guarded; also exports the raw accumulators.
+        auto epilogue = [&](auto F) {
+            constexpr bool FAST = decltype(F)::value;
+            if (!FAST && g.Cdbg) {
 #pragma unroll
-        for (int a0 = 0; a0 < WA; a0 += 2) {
-            constexpr int WA_ = WA;
-            const int na = (WA_ - a0) < 2 ? (WA_ - a0) : 2;  // column tiles in this pass: 2, or 1 at the end of an odd WA
-            float cwv[2][16];
-            v8h wa[2][2];
+                for (int a = 0; a < WA; a++)
 #pragma unroll
-            for (int aa = 0; aa < 2; aa++) {
-                if (aa >= na) break;
-                const int jl = wp * 32 * WA + (a0 + aa) * 32;  // first column of the MFMA tile within the workgroup tile
+                    for (int b = 0; b < WB; b++) {
+                        const int i = I0 + b * 32 + ll;
+#pragma unroll
+                        for (int r = 0; r < 16; r++) {
+                            const int j = J0 + a * 32 + 8 * (r >> 2) + 4 * gl + (r & 3);
+                            if (i < s && j < o) g.Cdbg[(size_t)i * o + j] = acc[a][b][r];
+                        }
+                    }
+            }
+            float sx[WB];      // c_x / 127^2 of this lane's tokens (Eq. 7: S = c_x (x) c_w / 127^2)
+            v8h xb[WB][2];     // MFMA "B" operand of the outlier product: slots 8*gl .. +7 (+16) of this lane's tokens
+#pragma unroll
+            for (int b = 0; b < WB; b++) {
+                const int il = wq * 32 * WB + b * 32 + ll;  // token within the workgroup tile
+                const int i = cI0w + il;
                 if (FAST) {
-#pragma unroll
-                    for (int rr = 0; rr < 4; rr++) {
-                        const uint2 pk = *(const uint2*)(ECw + jl + 8 * rr + 4 * gl);
-                        cwv[aa][4 * rr + 0] = f16_bits_to_float((unsigned short)(pk.x & 0xffff));
-                        cwv[aa][4 * rr + 1] = f16_bits_to_float((unsigned short)(pk.x >> 16));
-                        cwv[aa][4 * rr + 2] = f16_bits_to_float((unsigned short)(pk.y & 0xffff));
-                        cwv[aa][4 * rr + 3] = f16_bits_to_float((unsigned short)(pk.y >> 16));
-                    }
-#pragma unroll
-                    for (int ks = 0; ks < 2; ks++)
-#pragma unroll
-                        for (int e = 0; e < 8; e++)
-                            wa[aa][ks][e] =
-                                __builtin_bit_cast(_Float16, EW[(16 * ks + 8 * gl + e) * (64 * WA) + jl + ll]);
+                    sx[b] = f16_bits_to_float(ECx[il]) * (1.0f / 16129.0f);
+                    xb[b][0] = *(const v8h*)(EX + il * (2 * opad) + gl * 16);
+                    xb[b][1] = (v8h)(0);
+                    if (cnt > 16) xb[b][1] = *(const v8h*)(EX + il * (2 * opad) + (2 + gl) * 16);  // then opad == 32
                 } else {
-#pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const int j = J0w + jl + 8 * (r >> 2) + 4 * gl + (r & 3);
-                        cwv[aa][r] = (j < o) ? f16_bits_to_float(g.cw[j]) : 0.0f;
-                    }
-                    wa[aa][0] = cnt > 0 ? load_w_mem(J0w + jl + ll, 0) : (v8h)(0);
-                    wa[aa][1] = cnt > 16 ? load_w_mem(J0w + jl + ll, 16) : (v8h)(0);
+                    sx[b] = (i < s) ? f16_bits_to_float(g.cx[i]) * (1.0f / 16129.0f) : 0.0f;
+                    xb[b][0] = cnt > 0 ? load_x_mem(i, 0) : (v8h)(0);
+                    xb[b][1] = cnt > 16 ? load_x_mem(i, 16) : (v8h)(0);
                 }
             }
+            int unit = 0;
 #pragma unroll
-            for (int b0 = 0; b0 < WB; b0 += 2, unit++) {
-                int8_t* sb = stg + (unit % NSTG) * 8192;
-                // ---- 64 tokens x 64 columns: dequantize, add the outlier product, stage as fp16 rows in LDS
+            for (int a0 = 0; a0 < WA; a0 += 2) {
+                constexpr int WA_ = WA;
+                const int na = (WA_ - a0) < 2 ? (WA_ - a0) : 2;  // column tiles in this pass: 2, or 1 at the end of an odd WA
+                float cwv[2][16];
+                v8h wa[2][2];
 #pragma unroll
                 for (int aa = 0; aa < 2; aa++) {
                     if (aa >= na) break;
-                    const int a = a0 + aa;
-#pragma unroll
-                    for (int bb = 0; bb < 2; bb++) {
-                        if (b0 + bb >= WB) break;
-                        const int b = b0 + bb;
-                        // Eq. 8: outlier product first (fp32 accumulation in the matrix unit), then one fused
-                        // multiply-add per output puts the dequantized int8 product (Eq. 7) on top
-                        v16f d;
-                        if (cnt > 0) {
-                            v16f t = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                            t = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[aa][0], xb[b][0], t, 0, 0, 0);
-                            if (cnt > 16) t = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[aa][1], xb[b][1], t, 0, 0, 0);
-                            if (!FAST)
-                                for (int t0 = OSLOTS; t0 < cnt; t0 += 16) {  // more than 32 outlier columns: rare
-                                    const v8h wm = load_w_mem(J0 + a * 32 + ll, t0);
-                                    const v8h xm = load_x_mem(I0 + b * 32 + ll, t0);
-                                    t = __builtin_amdgcn_mfma_f32_32x32x16_f16(wm, xm, t, 0, 0, 0);
-                                }
-#pragma unroll
-                            for (int r = 0; r < 16; r++)
-                                d[r] = __builtin_fmaf((float)acc[a][b][r] * sx[b], cwv[aa][r], t[r]);
-                        } else {
-#pragma unroll
-                            for (int r = 0; r < 16; r++) d[r] = (float)acc[a][b][r] * sx[b] * cwv[aa][r];
-                        }
-                        // staging row of token tl (0..63): 128 bytes = 8 chunks of 16, chunk q stored at
-                        // q ^ ((tl >> 1) & 7) to spread the banks
-                        const int tl = bb * 32 + ll;
+                    const int jl = wp * 32 * WA + (a0 + aa) * 32;  // first column of the MFMA tile within the workgroup tile
+                    if (FAST) {
 #pragma unroll
                         for (int rr = 0; rr < 4; rr++) {
-                            const v4h hv = {(_Float16)d[4 * rr], (_Float16)d[4 * rr + 1], (_Float16)d[4 * rr + 2],
-                                            (_Float16)d[4 * rr + 3]};
-                            const int q = aa * 4 + rr;
-                            *(v4h*)(sb + tl * 128 + ((q ^ ((tl >> 1) & 7)) << 4) + gl * 8) = hv;
+                            const uint2 pk = *(const uint2*)(ECw + jl + 8 * rr + 4 * gl);
+                            cwv[aa][4 * rr + 0] = f16_bits_to_float((unsigned short)(pk.x & 0xffff));
+                            cwv[aa][4 * rr + 1] = f16_bits_to_float((unsigned short)(pk.x >> 16));
+                            cwv[aa][4 * rr + 2] = f16_bits_to_float((unsigned short)(pk.y & 0xffff));
+                            cwv[aa][4 * rr + 3] = f16_bits_to_float((unsigned short)(pk.y >> 16));
                         }
-                    }
-                }
-                // ---- write the staged block: a lane moves 16 bytes, 8 lanes cover a token's 128 bytes
 #pragma unroll
-                for (int p = 0; p < 8; p++) {
-                    const int tl = p * 8 + (lane >> 3), q = lane & 7;
-                    const u4 v = *(const u4*)(sb + tl * 128 + ((q ^ ((tl >> 1) & 7)) << 4));
-                    const int i = I0 + b0 * 32 + tl;
-                    const int j = J0 + a0 * 32 + q * 8;
-                    if (FAST) {
-                        if (na == 2 || q < 4) *(u4*)(g.Out + (size_t)i * o + j) = v;
-                    } else if ((tl < 32 || b0 + 1 < WB) && i < s && q < 4 * na) {
-                        if (g.fast_ok && j + 8 <= o) {
-                            *(u4*)(g.Out + (size_t)i * o + j) = v;
-                        } else {
-                            const _Float16* hv = (const _Float16*)&v;
+                        for (int ks = 0; ks < 2; ks++)
 #pragma unroll
                             for (int e = 0; e < 8; e++)
-                                if (j + e < o) g.Out[(size_t)i * o + j + e] = hv[e];
+                                wa[aa][ks][e] =
+                                    __builtin_bit_cast(_Float16, EW[(16 * ks + 8 * gl + e) * 256 + jl + ll]);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; r++) {
+                            const int j = cJ0w + jl + 8 * (r >> 2) + 4 * gl + (r & 3);
+                            cwv[aa][r] = (j < o) ? f16_bits_to_float(g.cw[j]) : 0.0f;
+                        }
+                        wa[aa][0] = cnt > 0 ? load_w_mem(cJ0w + jl + ll, 0) : (v8h)(0);
+                        wa[aa][1] = cnt > 16 ? load_w_mem(cJ0w + jl + ll, 16) : (v8h)(0);
+                    }
+                }
+#pragma unroll
+                for (int b0 = 0; b0 < WB; b0 += 2, unit++) {
+                    int8_t* sb = stg + (unit % NSTG) * 8192;
+                    // ---- 64 tokens x 64 columns: dequantize, add the outlier product, stage as fp16 rows in LDS
+#pragma unroll
+                    for (int aa = 0; aa < 2; aa++) {
+                        if (aa >= na) break;
+                        const int a = a0 + aa;
+#pragma unroll
+                        for (int bb = 0; bb < 2; bb++) {
+                            if (b0 + bb >= WB) break;
+                            const int b = b0 + bb;
+                            // Eq. 8: outlier product first (fp32 accumulation in the matrix unit), then one fused
+                            // multiply-add per output puts the dequantized int8 product (Eq. 7) on top
+                            v16f d;
+                            if (cnt > 0) {
+                                v16f t = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                                t = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[aa][0], xb[b][0], t, 0, 0, 0);
+                                if (cnt > 16) t = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[aa][1], xb[b][1], t, 0, 0, 0);
+                                if (!FAST)
+                                    for (int t0 = OSLOTS; t0 < cnt; t0 += 16) {  // more than 32 outlier columns: rare
+                                        const v8h wm = load_w_mem(J0 + a * 32 + ll, t0);
+                                        const v8h xm = load_x_mem(I0 + b * 32 + ll, t0);
+                                        t = __builtin_amdgcn_mfma_f32_32x32x16_f16(wm, xm, t, 0, 0, 0);
+                                    }
+#pragma unroll
+                                for (int r = 0; r < 16; r++)
+                                    d[r] = __builtin_fmaf((float)acc[a][b][r] * sx[b], cwv[aa][r], t[r]);
+                            } else {
+#pragma unroll
+                                for (int r = 0; r < 16; r++) d[r] = (float)acc[a][b][r] * sx[b] * cwv[aa][r];
+                            }
+                            // staging row of token tl (0..63): 128 bytes = 8 chunks of 16, chunk q stored at
+                            // q ^ ((tl >> 1) & 7) to spread the banks
+                            const int tl = bb * 32 + ll;
+#pragma unroll
+                            for (int rr = 0; rr < 4; rr++) {
+                                const v4h hv = {(_Float16)d[4 * rr], (_Float16)d[4 * rr + 1], (_Float16)d[4 * rr + 2],
+                                                (_Float16)d[4 * rr + 3]};
+                                const int q = aa * 4 + rr;
+                                *(v4h*)(sb + tl * 128 + ((q ^ ((tl >> 1) & 7)) << 4) + gl * 8) = hv;
+                            }
+                        }
+                    }
+                    // ---- write the staged block: a lane moves 16 bytes, 8 lanes cover a token's 128 bytes
+#pragma unroll
+                    for (int p = 0; p < 8; p++) {
+                        const int tl = p * 8 + (lane_e >> 3), q = lane_e & 7;
+                        const u4 v = *(const u4*)(sb + tl * 128 + ((q ^ ((tl >> 1) & 7)) << 4));
+                        const int i = I0 + b0 * 32 + tl;
+                        const int j = J0 + a0 * 32 + q * 8;
+                        if (FAST) {
+                            if (na == 2 || q < 4) *(u4*)(g.Out + (size_t)i * o + j) = v;
+                        } else if ((tl < 32 || b0 + 1 < WB) && i < s && q < 4 * na) {
+                            if (g.fast_ok && j + 8 <= o) {
+                                *(u4*)(g.Out + (size_t)i * o + j) = v;
+                            } else {
+                                const _Float16* hv = (const _Float16*)&v;
+#pragma unroll
+                                for (int e = 0; e < 8; e++)
+                                    if (j + e < o) g.Out[(size_t)i * o + j + e] = hv[e];
+                            }
                         }
                     }
                 }
             }
-        }
-    };
-    if (interior)
-        epilogue(std::true_type{});
-    else
-        epilogue(std::false_type{});
+        };
+        if (cinterior)
+            epilogue(std::true_type{});
+        else
+            epilogue(std::false_type{});
+
+        if (!has_next) break;
+        sbase = (eslot + 2) % NB;
+        pos += gx;
+    }  // tiles
+}
+
+// compute units of the current device (one persistent workgroup each)
+static int compute_units()
+{
+    static int cached[16] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
 }
 
 template <int WA, int WB>
 static hipError_t launch_cfg(GemmArgs& g, hipStream_t st)
 {
     constexpr int STAGE = (2 * WA + 2 * WB) * 2 * TILE_BYTES;
-    constexpr int shm = NB * STAGE;
+    constexpr int shm = NB * STAGE + 4 * 8192;  // operand ring + output staging
     g.nP = (g.JT + 2 * WA - 1) / (2 * WA);
     g.nQ = (g.RT + 2 * WB - 1) / (2 * WB);
     static bool attr_set = false;
@@ -459,7 +520,8 @@ static hipError_t launch_cfg(GemmArgs& g, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_prefill_kernel<WA, WB><<<g.nP * g.nQ, 256, shm, st>>>(g);
+    const int total = g.nP * g.nQ, ncu = compute_units();
+    gemm_prefill_kernel<WA, WB><<<total < ncu ? total : ncu, 256, shm, st>>>(g);
     return hipGetLastError();
 }
 
