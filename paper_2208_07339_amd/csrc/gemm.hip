@@ -192,7 +192,14 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     // request piece k of operand stage v / of epilogue stage e into ring slot `slot`
     auto dma_k = [&](int v, int slot, int k) {
         int8_t* dst = lds + slot * STAGE + (w * PIECES + k) * TILE_BYTES;
-        __builtin_amdgcn_global_load_lds(GPTR(gpp[k] + (size_t)v * (2 * TILE_BYTES) + voff), LPTR(dst), 16, 0, 0);
+        // uniform 64-bit base (scalar registers) + 32-bit lane offset: the scalar-base form of the load,
+        // no vector address arithmetic in the K pipeline
+        const unsigned long long b = (unsigned long long)(gpp[k] + (size_t)v * (2 * TILE_BYTES));
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
+        const __attribute__((address_space(1))) int8_t* sb =
+            (const __attribute__((address_space(1))) int8_t*)(((unsigned long long)hi << 32) | lo);
+        __builtin_amdgcn_global_load_lds(sb + voff, LPTR(dst), 16, 0, 0);
     };
     auto dma_e = [&](int e, int slot, int k) {
         int8_t* dst = lds + slot * STAGE + (w * PIECES + k) * TILE_BYTES;
