@@ -429,15 +429,12 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
         for (int b = tid; b < nl; b += 256) {
             const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
             const int base = s_base[b];
-            for (int e = 0; e < n && base + e < cap; e++) {
-                const int j = L.cand[(size_t)b * capc + e];
-                idx[base + e] = j;
-                for (int i = 0; i < s; i++) Xo[(size_t)i * opad + base + e] = X[(size_t)i * h + j];
-            }
+            for (int e = 0; e < n && base + e < cap; e++) idx[base + e] = L.cand[(size_t)b * capc + e];
         }
+        __syncthreads();  // idx is read back by other threads of this workgroup
         for (int q = tid; q < s * opad; q += 256) {
             const int i = q / opad, t = q - i * opad;
-            if (t >= cnt) Xo[(size_t)i * opad + t] = 0;
+            Xo[q] = t < cnt ? X[(size_t)i * h + idx[t]] : (unsigned short)0;
         }
         if (tid == 0) {
             *count = cnt;

@@ -233,7 +233,8 @@ def linear_compare(d, alpha=None, cap=32):
 
 
 @pytest.mark.parametrize("s,h,o,ncol", [(1, 64, 32, 1), (16, 1024, 2048, 5), (13, 200, 61, 2), (32, 384, 96, 3),
-                                        (8, 4160, 128, 6), (16, 12288, 256, 7)])
+                                        (8, 4160, 128, 6), (16, 12288, 256, 7), (32, 40000, 64, 5),
+                                        (17, 70000, 32, 9), (9, 1100, 64, 3)])
 def test_linear_short_x(s, h, o, ncol):
     linear_compare(wl.make_custom(s, h, o, ncol, seed=s * 11 + h))
 
