@@ -38,6 +38,13 @@ def lib():
         L.oracle_output.restype = None
         L.oracle_output.argtypes = [i32p, u16p, u16p, u16p, u16p, i32p, C.c_int, C.c_int, C.c_int,
                                     C.c_int, u16p]
+        L.oracle_dequant_weight.restype = C.c_uint16
+        L.oracle_dequant_weight.argtypes = [C.c_int8, C.c_uint16]
+        L.oracle_dequant_rows.restype = None
+        L.oracle_dequant_rows.argtypes = [i8p, u16p, C.c_int, C.c_int, i32p, C.c_int, u16p]
+        L.oracle_output_dq.restype = None
+        L.oracle_output_dq.argtypes = [i32p, u16p, u16p, u16p, i8p, i32p, C.c_int, C.c_int, C.c_int,
+                                       C.c_int, u16p]
         L.oracle_linear.restype = C.c_int
         L.oracle_linear.argtypes = [u16p, u16p, C.c_int, C.c_int, C.c_int, C.c_double, i32p, i8p,
                                     u16p, i8p, u16p, i32p, u16p]
@@ -131,6 +138,38 @@ def output(Cm, cx, cw, X, W, idx):
     lib().oracle_output(_p(Cm, C.c_int32), _p(_bits(cx), C.c_uint16), _p(_bits(cw), C.c_uint16),
                         _p(Xb, C.c_uint16), _p(Wb, C.c_uint16), _p(idx, C.c_int32), len(idx), s, h,
                         o, _p(Out, C.c_uint16))
+    return Out.view(np.float16)
+
+
+def dequant_weight(q, cw):
+    """fp16( q * cw / 127 ), the inverse of the absmax quantization, as fp16 bits -> np.float16."""
+    b = lib().oracle_dequant_weight(int(q), int(np.float16(cw).view(np.uint16)))
+    return np.uint16(b).view(np.float16)
+
+
+def dequant_rows(Wq, cw, idx):
+    """Rows idx of W rebuilt from the codes: [len(idx) x o] fp16."""
+    Wq = np.ascontiguousarray(Wq, dtype=np.int8)
+    h, o = Wq.shape
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    rows = np.zeros((len(idx), o), dtype=np.uint16)
+    lib().oracle_dequant_rows(_p(Wq, C.c_int8), _p(_bits(cw), C.c_uint16), h, o, _p(idx, C.c_int32), len(idx),
+                              _p(rows, C.c_uint16))
+    return rows.view(np.float16)
+
+
+def output_dq(Cm, cx, cw, X, Wq, idx):
+    """Eq. 8 with the outlier rows of W rebuilt from the int8 codes (no 16-bit weights kept)."""
+    Xb = _bits(X)
+    s, h = Xb.shape
+    Wq = np.ascontiguousarray(Wq, dtype=np.int8)
+    o = Wq.shape[1]
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    Cm = np.ascontiguousarray(Cm, dtype=np.int32)
+    Out = np.zeros((s, o), dtype=np.uint16)
+    lib().oracle_output_dq(_p(Cm, C.c_int32), _p(_bits(cx), C.c_uint16), _p(_bits(cw), C.c_uint16),
+                           _p(Xb, C.c_uint16), _p(Wq, C.c_int8), _p(idx, C.c_int32), len(idx), s, h, o,
+                           _p(Out, C.c_uint16))
     return Out.view(np.float16)
 
 

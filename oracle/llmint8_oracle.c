@@ -23,7 +23,8 @@
  * Q() against pure-integer rational arithmetic, the integer GEMM against a
  * triple loop and closed forms, alpha = 0 against a float64 library matmul,
  * alpha = inf against Eq. 7 alone, the half-step error bound of rounding to
- * nearest.  Numbers printed by the paper: none exist for this path, so
+ * nearest; the int8-rows variant against exact rational arithmetic, its own
+ * half-step bound and a float64 library matmul of the dequantized weights.  Numbers printed by the paper: none exist for this path, so
  * end-to-end agreement with the authors' own runs is unpinned.
  */
 #include <fenv.h>
@@ -216,6 +217,50 @@ void oracle_output(const int32_t *C, const uint16_t *cx, const uint16_t *cw, con
             double x = oracle_f16_to_double(X[(size_t)i * h + k]);
             for (int j = 0; j < o; j++)
                 acc[j] += x * oracle_f16_to_double(W[(size_t)k * o + j]);
+        }
+        double ci = oracle_f16_to_double(cx[i]);
+        for (int j = 0; j < o; j++) {
+            double d = (double)C[(size_t)i * o + j] * ci * oracle_f16_to_double(cw[j]) / 16129.0;
+            Out[(size_t)i * o + j] = oracle_double_to_f16(d + acc[j]);
+        }
+        free(acc);
+    }
+}
+
+/* ---- variant: outlier rows of W rebuilt from the int8 codes ---------------- */
+
+/* Section 3.2 counts only "about 0.1% additional memory" for the decomposition,
+ * which keeping all of W in 16 bits would not give.  This variant stores no
+ * 16-bit weights: the rows O of W are rebuilt from the codes by inverting the
+ * absmax quantization of Section 2.1, W^[k][j] = fp16( W_i8[k][j] * c_w[j] / 127 )
+ * (one rounding, to nearest even), and take the place of W_f16 in Eq. 8.      */
+uint16_t oracle_dequant_weight(int8_t q, uint16_t cw_bits)
+{
+    return oracle_double_to_f16((double)q * oracle_f16_to_double(cw_bits) / 127.0);
+}
+
+/* rows[t][j] = W^[idx[t]][j] for t < count                                    */
+void oracle_dequant_rows(const int8_t *Wq, const uint16_t *cw, int h, int o, const int32_t *idx, int count,
+                         uint16_t *rows)
+{
+    (void)h;
+    for (int t = 0; t < count; t++)
+        for (int j = 0; j < o; j++)
+            rows[(size_t)t * o + j] = oracle_dequant_weight(Wq[(size_t)idx[t] * o + j], cw[j]);
+}
+
+/* Eq. 8 with W^ in the 16-bit term                                            */
+void oracle_output_dq(const int32_t *C, const uint16_t *cx, const uint16_t *cw, const uint16_t *X,
+                      const int8_t *Wq, const int32_t *idx, int count, int s, int h, int o, uint16_t *Out)
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < s; i++) {
+        double *acc = (double *)calloc((size_t)o, sizeof(double));
+        for (int t = 0; t < count; t++) {
+            int k = idx[t];
+            double x = oracle_f16_to_double(X[(size_t)i * h + k]);
+            for (int j = 0; j < o; j++)
+                acc[j] += x * oracle_f16_to_double(oracle_dequant_weight(Wq[(size_t)k * o + j], cw[j]));
         }
         double ci = oracle_f16_to_double(cx[i]);
         for (int j = 0; j < o; j++) {
