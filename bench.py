@@ -48,7 +48,7 @@ def to_dev(a):
     return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
 
 
-def run_workload(name, steps, warmup, copies=1):
+def run_workload(name, steps, warmup, copies=1, int8_rows=False):
     import torch
 
     import paper_2208_07339_amd as L
@@ -63,6 +63,8 @@ def run_workload(name, steps, warmup, copies=1):
     qws = [L.quantize_weight(Wd, ws)]
     torch.cuda.synchronize()
     t_wq = time.perf_counter() - t0
+    if int8_rows:  # variant that keeps no fp16 weights: the outlier rows are rebuilt from the codes
+        qws[0].W = None
     for _ in range(copies - 1):  # rotate weight copies so that no last-level cache flatters a streaming read
         q = qws[0]
         qws.append(L.QuantizedWeight(q.Wq.clone(), q.cw.clone(), q.W, q.h, q.o))
@@ -146,6 +148,9 @@ def main():
     ap.add_argument("--workload", default="ffn13b", choices=["ffn13b", "decode", "attn6p7b", "ffn175b_down"])
     ap.add_argument("--no-decode", action="store_true", help="skip the secondary decode measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--outlier-rows", default="fp16", choices=["fp16", "int8"],
+                    help="fp16: outlier product with the original weight rows (Eq. 8 as printed); int8: rows "
+                         "rebuilt from the int8 codes, no fp16 weights kept (measured separately, not the headline)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three device-to-device copies of 256 MiB first: under rocprofv3 --pmc their "
                          "FETCH_SIZE / WRITE_SIZE readings calibrate the counters (paper_2208_07339_amd/pmc_summary.py)")
@@ -165,7 +170,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    res = run_workload(a.workload, a.steps, a.warmup, copies=2 if a.workload == "decode" else 1)
+    i8 = a.outlier_rows == "int8"
+    res = run_workload(a.workload, a.steps, a.warmup, copies=2 if a.workload == "decode" else 1, int8_rows=i8)
     s, h, o = res["s"], res["h"], res["o"]
     ops = 2.0 * s * h * o
     line = {
@@ -178,7 +184,7 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": a.workload, "s": s, "h": h, "o": o, "alpha": 6.0,
                    "outlier_columns_planted": res["planted"], "outlier_columns_found": res["n_out"],
-                   "outlier_capacity": CAP},
+                   "outlier_capacity": CAP, "outlier_rows": a.outlier_rows},
         "ms_prepass": res["ms_prepass"], "ms_matmul_kernel": res["ms_matmul"],
         "weight_quantize_ms_once": res["weight_quantize_ms"],
     }
@@ -213,7 +219,7 @@ def main():
     del res["inputs"]
 
     if a.workload != "decode" and not a.no_decode:
-        dres = run_workload("decode", a.steps, a.warmup, copies=2)
+        dres = run_workload("decode", a.steps, a.warmup, copies=2, int8_rows=i8)
         nbytes = algorithmic_bytes_decode(dres["s"], dres["h"], dres["o"], dres["n_out"])
         line["decode"] = {
             "workload": "decode", "s": dres["s"], "h": dres["h"], "o": dres["o"],

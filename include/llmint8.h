@@ -99,10 +99,18 @@ int llmint8_find_outliers(const void *X_f16, int s, int h, float alpha, int32_t 
 int llmint8_quantize_rows(const void *X_f16, int s, int h, const int32_t *idx, const int32_t *count,
                           int cap, int8_t *Xq, void *cx_f16, void *Xo_f16, llmint8_stream_t stream);
 
+/* Variant that keeps no 16-bit weights (Section 3.2 counts about 0.1% extra memory for the
+ * decomposition): the rows O of W are rebuilt from the codes by inverting the absmax quantization,
+ * Wo[t][j] = fp16( W_i8[O_t][j] * c_w[j] / 127 ), rounded once to nearest even; rows t >= |O| are 0.
+ *   Wo_f16 out  [llmint8_opad(cap) x o] fp16                                  */
+int llmint8_dequantize_rows(const int8_t *Wq, const void *cw_f16, int h, int o, const int32_t *idx,
+                            const int32_t *count, int cap, void *Wo_f16, llmint8_stream_t stream);
+
 /* Eq. 7 + Eq. 8: C_i32 = X_i8 W_i8 (int32 accumulation),
  * Out = fp16( C_i32 * c_x (x) c_w / 127^2 + Xo W_f16[O,:] ), the outlier product
  * accumulated in fp32.  Token counts s <= 32 take a weight-streaming path.
- *   W_f16       in   the original weights; only rows O are read
+ *   W_f16       in   the original weights; only rows O are read.  NULL: the rows rebuilt from
+ *                    the codes (llmint8_dequantize_rows, done here into ws) take their place
  *   Out_f16     out  [s x o] fp16
  *   C_i32_debug out  NULL, or [s x o] int32 receiving the raw accumulators   */
 int llmint8_matmul(const int8_t *Xq, const void *cx_f16, const void *Xo_f16, const int32_t *idx,
@@ -110,7 +118,8 @@ int llmint8_matmul(const int8_t *Xq, const void *cx_f16, const void *Xo_f16, con
                    const void *W_f16, int s, int h, int o, void *Out_f16, int32_t *C_i32_debug,
                    void *ws, size_t ws_bytes, llmint8_stream_t stream);
 
-/* The per-call sequence find_outliers -> quantize_rows -> matmul on one stream.
+/* The per-call sequence find_outliers -> quantize_rows -> matmul on one stream (W_f16 may be NULL
+ * as for llmint8_matmul).
  * Xq, cx_f16, Xo_f16, idx, count, status are caller-provided scratch/outputs
  * of the sizes given above.                                                   */
 int llmint8_linear(const void *X_f16, int s, int h, float alpha, const int8_t *Wq, const void *cw_f16,

@@ -8,5 +8,5 @@ HIP library is missing, loading fails.
 from .binding import (  # noqa: F401
     LIB_PATH, Llmint8Error, QuantizedWeight, Outliers, QuantizedRows, Workspace,
     lib, find_outliers, quantize_rows, quantize_weight, matmul, linear, export_rows, export_weight,
-    workspace_bytes, wq_bytes, xq_bytes, opad, debug_prefill_tile, debug_decode_shape,
+    workspace_bytes, wq_bytes, xq_bytes, opad, debug_prefill_tile, debug_decode_shape, dequantize_rows,
 )

@@ -9,7 +9,7 @@ LIB_PATH = os.path.join(HERE, "libllmint8.so")
 SYMBOLS = [
     "llmint8_status_string", "llmint8_last_hip_error", "llmint8_opad", "llmint8_wq_bytes", "llmint8_xq_bytes",
     "llmint8_workspace_bytes", "llmint8_quantize_weight", "llmint8_find_outliers",
-    "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_linear_events", "llmint8_export_weight",
+    "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_linear_events", "llmint8_dequantize_rows", "llmint8_export_weight",
     "llmint8_export_rows", "llmint8_debug_prefill_tile",
     "llmint8_debug_decode_shape",
 ]
@@ -56,6 +56,8 @@ def lib():
     L.llmint8_matmul.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     L.llmint8_linear.restype = i32
     L.llmint8_linear.argtypes = [vp, i32, i32, f32, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.llmint8_dequantize_rows.restype = i32
+    L.llmint8_dequantize_rows.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, vp]
     L.llmint8_linear_events.restype = i32
     L.llmint8_linear_events.argtypes = L.llmint8_linear.argtypes + [vp, vp]
     L.llmint8_export_weight.restype = i32
@@ -123,7 +125,7 @@ class Workspace:
 class QuantizedWeight:
     Wq: object     # uint8/int8 device tensor, private tiled layout
     cw: object     # [o] fp16
-    W: object      # [h, o] fp16 original (rows O are read by matmul)
+    W: object      # [h, o] fp16 original (rows O are read by matmul), or None: rows rebuilt from the codes
     h: int
     o: int
 
@@ -226,6 +228,15 @@ def debug_prefill_tile(cfg):
 def debug_decode_shape(cfg):
     """llmint8_debug_decode_shape: force the decode kernel's work split (-1 = default)."""
     _check(lib().llmint8_debug_decode_shape(int(cfg)))
+
+
+def dequantize_rows(qw, outl):
+    """llmint8_dequantize_rows: rows O of W rebuilt from the codes -> [opad, o] fp16."""
+    torch = _torch()
+    out = torch.empty((opad(outl.cap), qw.o), dtype=torch.float16, device=qw.Wq.device)
+    _check(lib().llmint8_dequantize_rows(_ptr(qw.Wq), _ptr(qw.cw), qw.h, qw.o, _ptr(outl.idx), _ptr(outl.count),
+                                         outl.cap, _ptr(out), _stream()))
+    return out
 
 
 def export_weight(qw):

@@ -18,6 +18,13 @@ inline size_t outlier_ws(int s, int h, int cap)
     return scratch_ws(h, cap) + align_up((size_t)colmax_slabs(s, h) * h * 2, 256);
 }
 inline size_t weight_ws(int h, int o) { return align_up((size_t)colmax_slabs(h, o) * o * 2, 256); }
+// rebuilt outlier rows of W (used when no fp16 weights are given): [opad x o] fp16, behind everything else
+inline size_t rows_ws(int o, int cap) { return align_up((size_t)opad_of(cap) * o * 2, 256); }
+inline size_t scan_ws(int s, int h, int o, int cap)
+{
+    const size_t a = outlier_ws(s, h, cap), b = weight_ws(h, o);
+    return a > b ? a : b;
+}
 
 thread_local hipError_t g_last_hip = hipSuccess;  // reported by llmint8_last_hip_error()
 
@@ -63,9 +70,7 @@ size_t llmint8_xq_bytes(int s, int h)
 size_t llmint8_workspace_bytes(int s, int h, int o, int cap)
 {
     if (s < 1 || h < 1 || o < 1 || cap < 1) return 0;
-    size_t a = outlier_ws(s, h, cap), b = weight_ws(h, o);
-    size_t m = a > b ? a : b;
-    return m + 256;  // slack to align the caller's pointer
+    return scan_ws(s, h, o, cap) + rows_ws(o, cap) + 256;  // slack to align the caller's pointer
 }
 
 int llmint8_quantize_weight(const void* W_f16, int h, int o, int8_t* Wq, void* cw_f16, void* ws, size_t ws_bytes,
@@ -116,30 +121,52 @@ int llmint8_quantize_rows(const void* X_f16, int s, int h, const int32_t* idx, c
                                            (unsigned short*)Xo_f16, (hipStream_t)stream));
 }
 
+int llmint8_dequantize_rows(const int8_t* Wq, const void* cw_f16, int h, int o, const int32_t* idx,
+                            const int32_t* count, int cap, void* Wo_f16, llmint8_stream_t stream)
+{
+    if (!Wq || !cw_f16 || !idx || !count || !Wo_f16 || h < 1 || o < 1 || cap < 1) return LLMINT8_INVALID_ARG;
+    if (misaligned(Wq, 16) || misaligned(cw_f16, 2) || misaligned(idx, 4) || misaligned(count, 4) ||
+        misaligned(Wo_f16, 16))
+        return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
+    return hip_status(launch_dequant_rows(Wq, (const unsigned short*)cw_f16, h, o, idx, count, cap,
+                                          (unsigned short*)Wo_f16, (hipStream_t)stream));
+}
+
 int llmint8_matmul(const int8_t* Xq, const void* cx_f16, const void* Xo_f16, const int32_t* idx,
                    const int32_t* count, int cap, const int8_t* Wq, const void* cw_f16, const void* W_f16, int s,
                    int h, int o, void* Out_f16, int32_t* C_i32_debug, void* ws, size_t ws_bytes,
                    llmint8_stream_t stream)
 {
-    if (!Xq || !cx_f16 || !Xo_f16 || !idx || !count || !Wq || !cw_f16 || !W_f16 || !Out_f16 || s < 1 || h < 1 ||
-        o < 1 || cap < 1)
+    if (!Xq || !cx_f16 || !Xo_f16 || !idx || !count || !Wq || !cw_f16 || !Out_f16 || s < 1 || h < 1 || o < 1 ||
+        cap < 1)
         return LLMINT8_INVALID_ARG;
     if (misaligned(Xq, 16) || misaligned(Wq, 16) || misaligned(Xo_f16, 16) || misaligned(cw_f16, 8) ||
         misaligned(cx_f16, 2) || misaligned(W_f16, 2) || misaligned(Out_f16, 8) || misaligned(idx, 4) ||
         misaligned(count, 4) || misaligned(C_i32_debug, 4))
         return LLMINT8_INVALID_ARG;
     if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
-    (void)ws;
-    (void)ws_bytes;
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e;
+    hipError_t e = hipSuccess;
+    const unsigned short* Wrows = (const unsigned short*)W_f16;
+    int rows_are_slots = 0;
+    if (!W_f16) {
+        // no 16-bit weights kept: rebuild the outlier rows from the codes into the workspace
+        if (!ws) return LLMINT8_INVALID_ARG;
+        if (ws_bytes < llmint8_workspace_bytes(s, h, o, cap)) return LLMINT8_WORKSPACE;
+        unsigned short* Wo = (unsigned short*)((char*)ws_base(ws) + scan_ws(s, h, o, cap));
+        e = launch_dequant_rows(Wq, (const unsigned short*)cw_f16, h, o, idx, count, cap, Wo, st);
+        if (e != hipSuccess) return hip_status(e);
+        Wrows = Wo;
+        rows_are_slots = 1;
+    }
     if (s <= 32)
         e = launch_gemm_decode(Xq, (const unsigned short*)cx_f16, (const unsigned short*)Xo_f16, count, cap, Wq,
-                               (const unsigned short*)cw_f16, (const unsigned short*)W_f16, idx, s, h, o,
+                               (const unsigned short*)cw_f16, Wrows, rows_are_slots, idx, s, h, o,
                                (unsigned short*)Out_f16, C_i32_debug, st);
     else
         e = launch_gemm_prefill(Xq, (const unsigned short*)cx_f16, (const unsigned short*)Xo_f16, count, cap, Wq,
-                                (const unsigned short*)cw_f16, (const unsigned short*)W_f16, idx, s, h, o,
+                                (const unsigned short*)cw_f16, Wrows, rows_are_slots, idx, s, h, o,
                                 (unsigned short*)Out_f16, C_i32_debug, st);
     return hip_status(e);
 }
@@ -150,8 +177,8 @@ static int linear_impl(const void* X_f16, int s, int h, float alpha, const int8_
                        hipEvent_t ev_before, hipEvent_t ev_after)
 {
     // validate everything before anything is enqueued
-    if (!X_f16 || !idx || !count || !ws || !Xq || !cx_f16 || !Xo_f16 || !Wq || !cw_f16 || !W_f16 || !Out_f16 || s < 1 ||
-        h < 1 || o < 1 || cap < 1)
+    if (!X_f16 || !idx || !count || !ws || !Xq || !cx_f16 || !Xo_f16 || !Wq || !cw_f16 || !Out_f16 || s < 1 || h < 1 ||
+        o < 1 || cap < 1)
         return LLMINT8_INVALID_ARG;
     if (misaligned(X_f16, 2) || misaligned(idx, 4) || misaligned(count, 4) || misaligned(status, 4) ||
         misaligned(Xq, 16) || misaligned(Wq, 16) || misaligned(Xo_f16, 16) || misaligned(cw_f16, 8) ||

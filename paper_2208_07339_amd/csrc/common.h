@@ -99,14 +99,18 @@ hipError_t launch_quantize_rows(const void* X, int s, int h, const int32_t* idx,
                                 int8_t* Xq, unsigned short* cx, unsigned short* Xo, hipStream_t st);
 hipError_t launch_export_tiled(const int8_t* T, int rows, int h, int8_t* out, int ld_rows_major,
                                hipStream_t st);
+// Wf: the original fp16 weights [h x o] (rows_are_slots = 0: outlier slot t uses row idx[t]), or the
+// rebuilt rows [opad x o] of launch_dequant_rows (rows_are_slots = 1: slot t uses row t)
 hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                                const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
-                               const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
+                               const unsigned short* Wf, int rows_are_slots, const int32_t* idx, int s, int h, int o,
                                unsigned short* Out, int32_t* Cdbg, hipStream_t st);
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
-                              const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
+                              const unsigned short* Wf, int rows_are_slots, const int32_t* idx, int s, int h, int o,
                               unsigned short* Out, int32_t* Cdbg, hipStream_t st);
+hipError_t launch_dequant_rows(const int8_t* Wq, const unsigned short* cw, int h, int o, const int32_t* idx,
+                               const int32_t* count, int cap, unsigned short* Wo, hipStream_t st);
 
 // tile shape of the prefill GEMM forced by llmint8_debug_prefill_tile (-1: chosen from the shape)
 extern int g_force_cfg;

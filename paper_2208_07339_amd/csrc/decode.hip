@@ -26,8 +26,9 @@ template <int NJ, int U>
 __global__ void __launch_bounds__(256)
 gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq, int KT, int JT,
                    const unsigned short* __restrict__ cw, const unsigned short* __restrict__ cx,
-                   const unsigned short* __restrict__ Wf, const int32_t* __restrict__ idx,
-                   const unsigned short* __restrict__ Xo, const int32_t* __restrict__ count, int cap, int opad,
+                   const unsigned short* __restrict__ Wf, int rows_are_slots, int wrows,
+                   const int32_t* __restrict__ idx, const unsigned short* __restrict__ Xo,
+                   const int32_t* __restrict__ count, int cap, int opad,
                    _Float16* __restrict__ Out, int32_t* __restrict__ Cdbg, int s, int h, int o)
 {
     __shared__ int red[4][NJ][16][64];
@@ -67,8 +68,8 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
         unsigned k = 0;
         bool ok = t < cnt;
         if (ok) {
-            k = (unsigned)idx[t];  // uniform: a scalar load
-            ok = k < (unsigned)h;
+            k = rows_are_slots ? (unsigned)t : (unsigned)idx[t];  // uniform: a scalar load
+            ok = k < (unsigned)wrows;
         }
 #pragma unroll
         for (int n = 0; n < NJ; n++) {
@@ -170,8 +171,8 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
                     d = __builtin_fmaf(f16_bits_to_float(xh), f16_bits_to_float(wh), d);
                 }
             for (int t = DSLOTS; t < cnt; t++) {  // more outlier columns than were prefetched: rare
-                const unsigned k = (unsigned)idx[t];
-                if (k < (unsigned)h)
+                const unsigned k = rows_are_slots ? (unsigned)t : (unsigned)idx[t];
+                if (k < (unsigned)wrows)
                     d = __builtin_fmaf(f16_bits_to_float(Xo[(size_t)i * opad + t]),
                                        f16_bits_to_float(Wf[(size_t)k * o + j]), d);
             }
@@ -184,12 +185,13 @@ int g_decode_cfg = -1;  // test hook, as g_force_cfg
 
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
-                              const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
+                              const unsigned short* Wf, int rows_are_slots, const int32_t* idx, int s, int h, int o,
                               unsigned short* Out, int32_t* Cdbg, hipStream_t st)
 {
     const int KT = k_tiles(h), JT = row_tiles(o);
+    const int wrows = rows_are_slots ? opad_of(cap) : h;
 #define LAUNCH_DECODE(NJ, U)                                                                                     \
-    gemm_decode_kernel<NJ, U><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, idx, Xo, count, cap, \
+    gemm_decode_kernel<NJ, U><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo, count, cap, \
                                                                  opad_of(cap), (_Float16*)Out, Cdbg, s, h, o)
     switch (g_decode_cfg) {
         case 1: LAUNCH_DECODE(1, 8); break;

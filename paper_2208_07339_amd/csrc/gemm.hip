@@ -37,7 +37,9 @@ struct GemmArgs {
     int nP, nQ;                  // workgroup grid: column blocks, token blocks
     const unsigned short* cw;    // [o] fp16 bits
     const unsigned short* cx;    // [s]
-    const unsigned short* Wf;    // [h x o] original fp16 weights
+    const unsigned short* Wf;    // [h x o] original fp16 weights, or [opad x o] rebuilt outlier rows
+    int rows_are_slots;          // 0: outlier slot t uses row idx[t] of Wf; 1: row t
+    int wrows;                   // rows of Wf (h or opad)
     const int32_t* idx;          // [cap] outlier columns
     const _Float16* Xo;          // [s x opad] gathered outlier columns of X
     const int32_t* count;
@@ -97,7 +99,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int s = g.s, h = g.h, o = g.o, KT = g.KT, opad = g.opad;
+    const int s = g.s, o = g.o, KT = g.KT, opad = g.opad;
     const int wp = w >> 1, wq = w & 1;  // wave position: column half, token half
 
     // ---- this workgroup's tiles.  Hardware deals consecutive workgroup ids round-robin to the 8
@@ -118,8 +120,8 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     // meet the zeros of Xo)
     int myk = 0;
     if ((lane & 31) < cnt) {
-        const unsigned k = (unsigned)g.idx[lane & 31];
-        myk = k < (unsigned)h ? (int)k : 0;
+        const unsigned k = g.rows_are_slots ? (unsigned)(lane & 31) : (unsigned)g.idx[lane & 31];
+        myk = k < (unsigned)g.wrows ? (int)k : 0;
     }
     // once per kernel: with this load known to be complete, the compiler has no reason to drain the
     // direct-to-LDS loads in flight when myk is used later in the K pipeline
@@ -338,8 +340,8 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                 const int t = t0 + 8 * gl + e;
                 unsigned short v = 0;
                 if (t < cnt && jcol < o) {
-                    const unsigned k = (unsigned)g.idx[t];
-                    if (k < (unsigned)h) v = g.Wf[(size_t)k * o + jcol];
+                    const unsigned k = g.rows_are_slots ? (unsigned)t : (unsigned)g.idx[t];
+                    if (k < (unsigned)g.wrows) v = g.Wf[(size_t)k * o + jcol];
                 }
                 wa[e] = __builtin_bit_cast(_Float16, v);
             }
@@ -555,10 +557,12 @@ int g_force_cfg = -1;  // test hook: tile shape override (-1 = automatic)
 
 hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                                const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
-                               const unsigned short* Wf, const int32_t* idx, int s, int h, int o,
+                               const unsigned short* Wf, int rows_are_slots, const int32_t* idx, int s, int h, int o,
                                unsigned short* Out, int32_t* Cdbg, hipStream_t st)
 {
     GemmArgs g;
+    g.rows_are_slots = rows_are_slots;
+    g.wrows = rows_are_slots ? opad_of(cap) : h;
     g.Wq = Wq; g.Xq = Xq;
     g.KT = k_tiles(h); g.JT = row_tiles(o); g.RT = row_tiles(s);
     g.nP = g.nQ = 0;

@@ -262,6 +262,70 @@ def test_linear_short_x_degenerate_cases():
     linear_compare(d)
 
 
+def test_rebuilt_outlier_rows_match_the_oracle_bit_for_bit():
+    """llmint8_dequantize_rows: fp16(W_i8 * c_w / 127) in integer arithmetic on the GPU against the oracle's
+    double-precision path, over column constants from the subnormal range to the largest fp16."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    rng = np.random.default_rng(3)
+    h, o, cap = 160, 4096, 48
+    W = wl.make_w(h, o, seed=31).astype(np.float32)
+    scale = np.exp2(rng.integers(-19, 20, size=o)).astype(np.float32)  # 0.02 * 2^-19 .. 0.02 * 2^19
+    W = np.clip(W * scale[None, :], -60000, 60000).astype(np.float16)
+    W[:, 5] = 0
+    W[3, 7] = 65504
+    Wd = torch.from_numpy(W.view(np.int16)).cuda().view(torch.float16)
+    ws = L.Workspace.allocate(64, h, o, cap)
+    qw = L.quantize_weight(Wd, ws)
+    Wq, cw = oracle.quantize_weight(W)
+    assert np.array_equal(hip_weight_i8(qw), Wq)
+    rows = np.sort(rng.choice(h, size=40, replace=False)).astype(np.int32)
+    outl = L.Outliers(torch.zeros(cap, dtype=torch.int32, device="cuda"), torch.tensor([40], dtype=torch.int32, device="cuda"),
+                      torch.zeros(1, dtype=torch.int32, device="cuda"), cap)
+    outl.idx[:40] = torch.from_numpy(rows).cuda()
+    got = L.dequantize_rows(qw, outl).cpu().numpy()
+    want = oracle.dequant_rows(Wq, cw, rows)
+    assert np.array_equal(bits(got[:40]), bits(want))
+    assert not bits(got[40:]).any()
+    assert np.isfinite(got.astype(np.float32)).all()
+    sub = (np.abs(want.astype(np.float32)) < 6.2e-5) & (want != 0)
+    assert sub.sum() > 100  # the subnormal branch was exercised
+
+
+def int8_rows_compare(d, cap=32, via_linear=False):
+    """The variant without 16-bit weights (W_f16 = NULL) against the oracle's int8-rows branch."""
+    import dataclasses
+
+    import torch
+
+    import paper_2208_07339_amd as L
+    X, W = d["X"], d["W"]
+    g = run_hip(X, W, d["alpha"], cap, want_c=False)
+    qw = dataclasses.replace(g["qw"], W=None)
+    if via_linear:
+        out = L.linear(g["Xd"], qw, d["alpha"], g["outl"], g["rows"], g["ws"])
+    else:
+        out = L.matmul(g["rows"], g["outl"], qw, g["ws"])
+    torch.cuda.synchronize()
+    r = oracle.linear(X, W, d["alpha"])
+    ref = oracle.output_dq(r["C"], r["cx"], r["cw"], X, r["Wq"], r["idx"][:cap])
+    assert_out_close(out.cpu().numpy(), ref)
+    # and it is a different result from the fp16-rows one wherever outliers contribute
+    if len(r["idx"]):
+        assert not np.array_equal(bits(out.cpu().numpy()), bits(g["Out"]))
+
+
+@pytest.mark.parametrize("via_linear", [False, True])
+def test_int8_rows_variant(via_linear):
+    int8_rows_compare(wl.make("tiny"), via_linear=via_linear)
+    int8_rows_compare(wl.make_custom(16, 1024, 2048, 5, seed=51), via_linear=via_linear)       # decode kernel
+    int8_rows_compare(wl.make_custom(13, 200, 61, 2, seed=52), via_linear=via_linear)          # ... unaligned
+    int8_rows_compare(wl.make_custom(512, 2048, 1024, 7, seed=53), via_linear=via_linear)      # prefill, LDS-fed epilogue
+    int8_rows_compare(wl.make_custom(300, 1000, 515, 20, seed=54), via_linear=via_linear)      # prefill, guarded epilogue
+    int8_rows_compare(wl.make_custom(300, 384, 520, 40, seed=55), cap=48, via_linear=via_linear)  # > 32 outlier columns
+
+
 def test_argument_errors_are_reported_not_executed():
     import ctypes as C
 
