@@ -51,6 +51,16 @@ def lib():
         L.oracle_sampled.restype = None
         L.oracle_sampled.argtypes = [u16p, u16p, C.c_int, C.c_int, C.c_int, i32p, C.c_int, i32p,
                                      i32p, C.c_int, i32p, u16p]
+        L.oracle_quantize_weight_tensor.restype = None
+        L.oracle_quantize_weight_tensor.argtypes = [u16p, C.c_int, C.c_int, i8p, u16p]
+        L.oracle_quantize_rows_tensor.restype = None
+        L.oracle_quantize_rows_tensor.argtypes = [u16p, C.c_int, C.c_int, i32p, C.c_int, i8p, u16p]
+        L.oracle_linear_granular.restype = C.c_int
+        L.oracle_linear_granular.argtypes = [u16p, u16p, C.c_int, C.c_int, C.c_int, C.c_double, C.c_int,
+                                             i32p, i8p, u16p, i8p, u16p, i32p, u16p]
+        L.oracle_sampled_granular.restype = None
+        L.oracle_sampled_granular.argtypes = [u16p, u16p, C.c_int, C.c_int, C.c_int, i32p, C.c_int,
+                                              C.c_int, i32p, i32p, C.c_int, i32p, u16p]
         L.oracle_num_threads.restype = C.c_int
         L.oracle_set_num_threads.argtypes = [C.c_int]
         _lib = L
@@ -212,6 +222,76 @@ def sampled(X, W, idx, rows, cols):
     lib().oracle_sampled(_p(Xb, C.c_uint16), _p(Wb, C.c_uint16), s, h, o, _p(idx, C.c_int32),
                          len(idx), _p(rows, C.c_int32), _p(cols, C.c_int32), n, _p(Cs, C.c_int32),
                          _p(Os, C.c_uint16))
+    return Cs, Os.view(np.float16)
+
+
+GRANULARITY = {"vectorwise": 0, "rowwise": 1, "tensorwise": 2}
+
+
+def quantize_weight_tensor(W):
+    """Section 2.1: one absmax constant for the whole weight matrix (returned in every entry of cw)."""
+    Wb = _bits(W)
+    h, o = Wb.shape
+    Wq = np.zeros((h, o), dtype=np.int8)
+    cw = np.zeros(o, dtype=np.uint16)
+    lib().oracle_quantize_weight_tensor(_p(Wb, C.c_uint16), h, o, _p(Wq, C.c_int8), _p(cw, C.c_uint16))
+    return Wq, cw.view(np.float16)
+
+
+def quantize_rows_tensor(X, idx):
+    """One absmax constant over all non-outlier entries of X; zeros in outlier columns."""
+    Xb = _bits(X)
+    s, h = Xb.shape
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    Xq = np.zeros((s, h), dtype=np.int8)
+    cx = np.zeros(s, dtype=np.uint16)
+    lib().oracle_quantize_rows_tensor(_p(Xb, C.c_uint16), s, h, _p(idx, C.c_int32), len(idx),
+                                      _p(Xq, C.c_int8), _p(cx, C.c_uint16))
+    return Xq, cx.view(np.float16)
+
+
+def linear_granular(X, W, alpha, granularity):
+    """linear() with the constants of Table 1's baselines: "vectorwise", "rowwise" or "tensorwise"."""
+    Xb, Wb = _bits(X), _bits(W)
+    s, h = Xb.shape
+    h2, o = Wb.shape
+    assert h == h2
+    idx = np.zeros(max(h, 1), dtype=np.int32)
+    Xq = np.zeros((s, h), dtype=np.int8)
+    cx = np.zeros(s, dtype=np.uint16)
+    Wq = np.zeros((h, o), dtype=np.int8)
+    cw = np.zeros(o, dtype=np.uint16)
+    Cm = np.zeros((s, o), dtype=np.int32)
+    Out = np.zeros((s, o), dtype=np.uint16)
+    n = lib().oracle_linear_granular(_p(Xb, C.c_uint16), _p(Wb, C.c_uint16), s, h, o, float(alpha),
+                                     GRANULARITY[granularity], _p(idx, C.c_int32), _p(Xq, C.c_int8),
+                                     _p(cx, C.c_uint16), _p(Wq, C.c_int8), _p(cw, C.c_uint16),
+                                     _p(Cm, C.c_int32), _p(Out, C.c_uint16))
+    if n == -1:
+        raise OverflowError("int32 accumulator overflow")
+    if n == -2:
+        raise ValueError("inputs must be finite")
+    assert n >= 0
+    return {"idx": idx[:n].copy(), "Xq": Xq, "cx": cx.view(np.float16), "Wq": Wq,
+            "cw": cw.view(np.float16), "C": Cm, "Out": Out.view(np.float16)}
+
+
+def sampled_granular(X, W, idx, rows, cols, granularity):
+    """sampled() for "rowwise" / "tensorwise" constants ("vectorwise" is sampled() itself)."""
+    if GRANULARITY[granularity] == 0:
+        return sampled(X, W, idx, rows, cols)
+    Xb, Wb = _bits(X), _bits(W)
+    s, h = Xb.shape
+    o = Wb.shape[1]
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    cols = np.ascontiguousarray(cols, dtype=np.int32)
+    n = len(rows)
+    Cs = np.zeros(n, dtype=np.int32)
+    Os = np.zeros(n, dtype=np.uint16)
+    lib().oracle_sampled_granular(_p(Xb, C.c_uint16), _p(Wb, C.c_uint16), s, h, o, _p(idx, C.c_int32),
+                                  len(idx), GRANULARITY[granularity], _p(rows, C.c_int32),
+                                  _p(cols, C.c_int32), n, _p(Cs, C.c_int32), _p(Os, C.c_uint16))
     return Cs, Os.view(np.float16)
 
 

@@ -24,7 +24,10 @@
  * triple loop and closed forms, alpha = 0 against a float64 library matmul,
  * alpha = inf against Eq. 7 alone, the half-step error bound of rounding to
  * nearest; the int8-rows variant against exact rational arithmetic, its own
- * half-step bound and a float64 library matmul of the dequantized weights.  Numbers printed by the paper: none exist for this path, so
+ * half-step bound and a float64 library matmul of the dequantized weights;
+ * the row-wise and tensor-wise baselines against exact rational arithmetic,
+ * closed forms on integer-valued inputs and the vector-wise functions on inputs
+ * whose rows / columns share one maximum.  Numbers printed by the paper: none exist for this path, so
  * end-to-end agreement with the authors' own runs is unpinned.
  */
 #include <fenv.h>
@@ -295,6 +298,98 @@ int oracle_linear(const uint16_t *X, const uint16_t *W, int s, int h, int o, dou
     return count;
 }
 
+/* ---- baselines of Table 1: coarser scaling constants ---------------------- */
+
+/* Section 2.1 defines absmax quantization with ONE constant for a whole tensor
+ * (127 over the largest magnitude of all its entries); Section 3 calls the
+ * common refinement with one constant per row "row-wise" and its own, with a
+ * constant per row of X and per column of W, "vector-wise".  Table 1 lists
+ * all three, each with and without the decomposition of Section 3.2.  Here:
+ *   granularity 0 (vector-wise): c_x per row of X, c_w per column of W
+ *   granularity 1 (row-wise):    c_x per row of X, one c_w for all of W
+ *   granularity 2 (tensor-wise): one c_x for all of X, one c_w for all of W
+ * A shared constant is stored in every entry of the c_x / c_w vector, so Eq. 7
+ * and Eq. 8 read the same way in all three.  With the decomposition the
+ * constants of X are taken over the non-outlier columns only, as before.      */
+
+/* one constant for the whole matrix */
+void oracle_quantize_weight_tensor(const uint16_t *W, int h, int o, int8_t *Wq, uint16_t *cw)
+{
+    double m = 0.0;
+    uint16_t mb = 0;
+    for (size_t n = 0; n < (size_t)h * o; n++) {
+        double a = fabs(oracle_f16_to_double(W[n]));
+        if (a > m) {
+            m = a;
+            mb = (uint16_t)(W[n] & 0x7fffu);
+        }
+    }
+    for (int j = 0; j < o; j++)
+        cw[j] = mb;
+#pragma omp parallel for schedule(static)
+    for (int k = 0; k < h; k++)
+        for (int j = 0; j < o; j++)
+            Wq[(size_t)k * o + j] = (int8_t)oracle_q(oracle_f16_to_double(W[(size_t)k * o + j]), m);
+}
+
+/* one constant for all non-outlier entries of X; zeros in the outlier columns */
+void oracle_quantize_rows_tensor(const uint16_t *X, int s, int h, const int32_t *idx, int count,
+                                 int8_t *Xq, uint16_t *cx)
+{
+    uint8_t *is_out = (uint8_t *)calloc((size_t)h, 1);
+    for (int t = 0; t < count; t++)
+        is_out[idx[t]] = 1;
+    double m = 0.0;
+    uint16_t mb = 0;
+    for (int i = 0; i < s; i++)
+        for (int j = 0; j < h; j++) {
+            if (is_out[j])
+                continue;
+            double a = fabs(oracle_f16_to_double(X[(size_t)i * h + j]));
+            if (a > m) {
+                m = a;
+                mb = (uint16_t)(X[(size_t)i * h + j] & 0x7fffu);
+            }
+        }
+    for (int i = 0; i < s; i++)
+        cx[i] = mb;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < s; i++)
+        for (int j = 0; j < h; j++)
+            Xq[(size_t)i * h + j] =
+                is_out[j] ? (int8_t)0 : (int8_t)oracle_q(oracle_f16_to_double(X[(size_t)i * h + j]), m);
+    free(is_out);
+}
+
+/* oracle_linear with the constants at the given granularity (0, 1 or 2 as above);
+ * same buffers and return values, -3 for an unknown granularity.              */
+int oracle_linear_granular(const uint16_t *X, const uint16_t *W, int s, int h, int o, double alpha,
+                           int granularity, int32_t *idx, int8_t *Xq, uint16_t *cx, int8_t *Wq,
+                           uint16_t *cw, int32_t *C, uint16_t *Out)
+{
+    if (granularity < 0 || granularity > 2)
+        return -3;
+    for (size_t n = 0; n < (size_t)s * h; n++)
+        if ((X[n] & 0x7c00u) == 0x7c00u)
+            return -2;
+    for (size_t n = 0; n < (size_t)h * o; n++)
+        if ((W[n] & 0x7c00u) == 0x7c00u)
+            return -2;
+    int count = oracle_find_outliers(X, s, h, alpha, idx, h);
+    if (granularity == 0)
+        oracle_quantize_weight(W, h, o, Wq, cw);
+    else
+        oracle_quantize_weight_tensor(W, h, o, Wq, cw);
+    if (granularity == 2)
+        oracle_quantize_rows_tensor(X, s, h, idx, count, Xq, cx);
+    else
+        oracle_quantize_rows(X, s, h, idx, count, Xq, cx);
+    if (oracle_igemm(Xq, Wq, s, h, o, C))
+        return -1;
+    oracle_output(C, cx, cw, X, W, idx, count, s, h, o, Out);
+    return count;
+}
+
 /* ---- single outputs of a large problem ------------------------------------ */
 
 /* Computes Out[i][j] and C[i][j] for n listed (i, j) pairs from the definition,
@@ -321,6 +416,60 @@ void oracle_sampled(const uint16_t *X, const uint16_t *W, int s, int h, int o, c
             double x = fabs(oracle_f16_to_double(X[(size_t)i * h + k]));
             if (x > mx)
                 mx = x;
+        }
+        int64_t acc = 0;
+        double hi = 0.0;
+        for (int k = 0; k < h; k++) {
+            double x = oracle_f16_to_double(X[(size_t)i * h + k]);
+            double w = oracle_f16_to_double(W[(size_t)k * o + j]);
+            if (is_out[k])
+                hi += x * w;
+            else
+                acc += (int64_t)oracle_q(x, mx) * (int64_t)oracle_q(w, mw);
+        }
+        C_out[p] = (int32_t)acc;
+        Out_out[p] = oracle_double_to_f16((double)acc * mx * mw / 16129.0 + hi);
+    }
+    free(is_out);
+}
+
+/* oracle_sampled at a coarser granularity (1 or 2; 0 is oracle_sampled itself):
+ * the shared constants are found once over the whole tensors, then every pair
+ * is computed from the definition as above.                                   */
+void oracle_sampled_granular(const uint16_t *X, const uint16_t *W, int s, int h, int o, const int32_t *idx,
+                             int count, int granularity, const int32_t *rows, const int32_t *cols, int n,
+                             int32_t *C_out, uint16_t *Out_out)
+{
+    uint8_t *is_out = (uint8_t *)calloc((size_t)h, 1);
+    for (int t = 0; t < count; t++)
+        is_out[idx[t]] = 1;
+    double gw = 0.0, gx = 0.0;
+    for (size_t q = 0; q < (size_t)h * o; q++) {
+        double a = fabs(oracle_f16_to_double(W[q]));
+        if (a > gw)
+            gw = a;
+    }
+    for (int i = 0; i < s; i++)
+        for (int k = 0; k < h; k++) {
+            if (is_out[k])
+                continue;
+            double a = fabs(oracle_f16_to_double(X[(size_t)i * h + k]));
+            if (a > gx)
+                gx = a;
+        }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int p = 0; p < n; p++) {
+        int i = rows[p], j = cols[p];
+        double mx = gx, mw = gw;
+        if (granularity == 1) { /* row-wise: the row of X keeps its own constant */
+            mx = 0.0;
+            for (int k = 0; k < h; k++) {
+                if (is_out[k])
+                    continue;
+                double x = fabs(oracle_f16_to_double(X[(size_t)i * h + k]));
+                if (x > mx)
+                    mx = x;
+            }
         }
         int64_t acc = 0;
         double hi = 0.0;
