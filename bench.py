@@ -48,19 +48,21 @@ def to_dev(a):
     return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
 
 
-def run_workload(name, steps, warmup, copies=1, int8_rows=False):
+def run_workload(name, steps, warmup, copies=1, int8_rows=False, granularity="vectorwise", alpha=None):
     import torch
 
     import paper_2208_07339_amd as L
     from paper_2208_07339_amd import workloads as wl
 
     d = wl.make(name)
+    if alpha is not None:
+        d["alpha"] = alpha
     s, h, o = d["s"], d["h"], d["o"]
     Xd = to_dev(d["X"])
     Wd = to_dev(d["W"])
     ws = L.Workspace.allocate(s, h, o, CAP)
     t0 = time.perf_counter()
-    qws = [L.quantize_weight(Wd, ws)]
+    qws = [L.quantize_weight(Wd, ws, granularity=granularity)]
     torch.cuda.synchronize()
     t_wq = time.perf_counter() - t0
     if int8_rows:  # variant that keeps no fp16 weights: the outlier rows are rebuilt from the codes
@@ -69,13 +71,13 @@ def run_workload(name, steps, warmup, copies=1, int8_rows=False):
         q = qws[0]
         qws.append(L.QuantizedWeight(q.Wq.clone(), q.cw.clone(), q.W, q.h, q.o))
     outl = L.find_outliers(Xd, d["alpha"], CAP, ws)
-    rows = L.quantize_rows(Xd, outl)
+    rows = L.quantize_rows(Xd, outl, granularity=granularity)
     out = torch.empty((s, o), dtype=torch.float16, device="cuda")
     torch.cuda.synchronize()
     n_out = int(outl.count.item())
 
     def step(i):
-        L.linear(Xd, qws[i % len(qws)], d["alpha"], outl, rows, ws, out)
+        L.linear(Xd, qws[i % len(qws)], d["alpha"], outl, rows, ws, out, granularity=granularity)
 
     for i in range(warmup):
         step(i)
@@ -96,7 +98,8 @@ def run_workload(name, steps, warmup, copies=1, int8_rows=False):
     torch.cuda.synchronize()
     for i in range(steps):
         evs[i][0].record()
-        L.linear(Xd, qws[i % len(qws)], d["alpha"], outl, rows, ws, out, events=(evs[i][1], evs[i][2]))
+        L.linear(Xd, qws[i % len(qws)], d["alpha"], outl, rows, ws, out, events=(evs[i][1], evs[i][2]),
+                 granularity=granularity)
     torch.cuda.synchronize()
     ms_pre = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
     ms_mm = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
@@ -151,6 +154,11 @@ def main():
     ap.add_argument("--outlier-rows", default="fp16", choices=["fp16", "int8"],
                     help="fp16: outlier product with the original weight rows (Eq. 8 as printed); int8: rows "
                          "rebuilt from the int8 codes, no fp16 weights kept (measured separately, not the headline)")
+    ap.add_argument("--granularity", default="vectorwise", choices=["vectorwise", "rowwise", "tensorwise"],
+                    help="absmax constants: vectorwise is the method (Section 3.1); rowwise / tensorwise are the "
+                         "baselines of Table 1 (measured separately, not the headline)")
+    ap.add_argument("--alpha", type=float, default=6.0,
+                    help="outlier threshold; inf switches the decomposition off (the baselines without it)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three device-to-device copies of 256 MiB first: under rocprofv3 --pmc their "
                          "FETCH_SIZE / WRITE_SIZE readings calibrate the counters (paper_2208_07339_amd/pmc_summary.py)")
@@ -171,7 +179,8 @@ def main():
         del src, dst
 
     i8 = a.outlier_rows == "int8"
-    res = run_workload(a.workload, a.steps, a.warmup, copies=2 if a.workload == "decode" else 1, int8_rows=i8)
+    res = run_workload(a.workload, a.steps, a.warmup, copies=2 if a.workload == "decode" else 1, int8_rows=i8,
+                       granularity=a.granularity, alpha=a.alpha)
     s, h, o = res["s"], res["h"], res["o"]
     ops = 2.0 * s * h * o
     line = {
@@ -182,7 +191,7 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": res["ms_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": a.workload, "s": s, "h": h, "o": o, "alpha": 6.0,
+        "config": {"workload": a.workload, "s": s, "h": h, "o": o, "alpha": a.alpha if np.isfinite(a.alpha) else "inf", "granularity": a.granularity,
                    "outlier_columns_planted": res["planted"], "outlier_columns_found": res["n_out"],
                    "outlier_capacity": CAP, "outlier_rows": a.outlier_rows},
         "ms_prepass": res["ms_prepass"], "ms_matmul_kernel": res["ms_matmul"],
@@ -204,7 +213,7 @@ def main():
                             "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": ach / INT8_MFMA_PEAK_TOPS,
                             "traffic": MEASURED_TRAFFIC.get(a.workload)}
 
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and a.granularity == "vectorwise":  # the oracle leg times the method itself
         r, t, cores = cpu_baseline(res)
         if a.workload == "decode":
             # the oracle reads fp16 weights; quote it in the metric's unit on the same algorithmic bytes
@@ -219,7 +228,8 @@ def main():
     del res["inputs"]
 
     if a.workload != "decode" and not a.no_decode:
-        dres = run_workload("decode", a.steps, a.warmup, copies=2, int8_rows=i8)
+        dres = run_workload("decode", a.steps, a.warmup, copies=2, int8_rows=i8, granularity=a.granularity,
+                            alpha=a.alpha)
         nbytes = algorithmic_bytes_decode(dres["s"], dres["h"], dres["o"], dres["n_out"])
         line["decode"] = {
             "workload": "decode", "s": dres["s"], "h": dres["h"], "o": dres["o"],

@@ -42,7 +42,7 @@ extern "C" {
 
 enum {
     LLMINT8_OK = 0,
-    LLMINT8_INVALID_ARG = 1, /* null pointer, non-positive dimension, cap < 1 */
+    LLMINT8_INVALID_ARG = 1, /* null pointer, non-positive dimension, cap < 1, unknown granularity */
     LLMINT8_SHAPE = 2,       /* h > LLMINT8_MAX_H, or a size beyond 2^31 elements per row block */
     LLMINT8_WORKSPACE = 3,   /* workspace smaller than llmint8_workspace_bytes() */
     LLMINT8_HIP = 4          /* a kernel launch failed (hipGetLastError) */
@@ -127,10 +127,31 @@ int llmint8_linear(const void *X_f16, int s, int h, float alpha, const int8_t *W
                    int8_t *Xq, void *cx_f16, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
                    llmint8_stream_t stream);
 
-/* Measurement support: llmint8_linear that also records two caller-created hipEvent_t on the stream,
- * one between the pre-pass and the matmul kernel and one after it (either may be NULL).          */
-int llmint8_linear_events(const void *X_f16, int s, int h, float alpha, const int8_t *Wq, const void *cw_f16,
-                          const void *W_f16, int o, int32_t *idx, int cap, int32_t *count, int32_t *status,
+/* Baselines of Table 1: the same calls with coarser absmax constants.
+ *   LLMINT8_VECTORWISE  one constant per row of X and per column of W (Section 3.1; the calls above)
+ *   LLMINT8_ROWWISE     one constant per row of X, ONE for all of W (Section 3 reads row-wise
+ *                       quantization as the finer constants on the hidden-state side only)
+ *   LLMINT8_TENSORWISE  ONE constant for X and one for W (absmax quantization of Section 2.1)
+ * A shared constant is written into every entry of cx_f16 / cw_f16, so Eq. 7 and Eq. 8 and therefore
+ * llmint8_matmul are unchanged.  With alpha < inf the constants of X are taken over the non-outlier
+ * columns only ("row-wise + decomposition" in Table 1); alpha = +inf switches the decomposition off,
+ * and llmint8_linear* then skips the scan of X.  The weight side of the granularity is fixed by
+ * llmint8_quantize_weight_granular; the per-call functions apply the hidden-state side.          */
+enum { LLMINT8_VECTORWISE = 0, LLMINT8_ROWWISE = 1, LLMINT8_TENSORWISE = 2 };
+int llmint8_quantize_weight_granular(const void *W_f16, int h, int o, int granularity, int8_t *Wq, void *cw_f16,
+                                     void *ws, size_t ws_bytes, llmint8_stream_t stream);
+int llmint8_quantize_rows_granular(const void *X_f16, int s, int h, const int32_t *idx, const int32_t *count,
+                                   int cap, int granularity, int8_t *Xq, void *cx_f16, void *Xo_f16,
+                                   llmint8_stream_t stream);
+int llmint8_linear_granular(const void *X_f16, int s, int h, float alpha, int granularity, const int8_t *Wq,
+                            const void *cw_f16, const void *W_f16, int o, int32_t *idx, int cap, int32_t *count,
+                            int32_t *status, int8_t *Xq, void *cx_f16, void *Xo_f16, void *Out_f16, void *ws,
+                            size_t ws_bytes, llmint8_stream_t stream);
+
+/* Measurement support: llmint8_linear_granular that also records two caller-created hipEvent_t on the
+ * stream, one between the pre-pass and the matmul kernel and one after it (either may be NULL).  */
+int llmint8_linear_events(const void *X_f16, int s, int h, float alpha, int granularity, const int8_t *Wq,
+                          const void *cw_f16, const void *W_f16, int o, int32_t *idx, int cap, int32_t *count, int32_t *status,
                           int8_t *Xq, void *cx_f16, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
                           llmint8_stream_t stream, void *ev_before_matmul, void *ev_after_matmul);
 

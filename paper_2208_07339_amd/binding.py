@@ -9,7 +9,9 @@ LIB_PATH = os.path.join(HERE, "libllmint8.so")
 SYMBOLS = [
     "llmint8_status_string", "llmint8_last_hip_error", "llmint8_opad", "llmint8_wq_bytes", "llmint8_xq_bytes",
     "llmint8_workspace_bytes", "llmint8_quantize_weight", "llmint8_find_outliers",
-    "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_linear_events", "llmint8_dequantize_rows", "llmint8_export_weight",
+    "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_linear_events", "llmint8_dequantize_rows",
+    "llmint8_quantize_weight_granular", "llmint8_quantize_rows_granular", "llmint8_linear_granular",
+    "llmint8_export_weight",
     "llmint8_export_rows", "llmint8_debug_prefill_tile",
     "llmint8_debug_decode_shape",
 ]
@@ -58,8 +60,15 @@ def lib():
     L.llmint8_linear.argtypes = [vp, i32, i32, f32, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.llmint8_dequantize_rows.restype = i32
     L.llmint8_dequantize_rows.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, vp]
+    L.llmint8_quantize_weight_granular.restype = i32
+    L.llmint8_quantize_weight_granular.argtypes = [vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    L.llmint8_quantize_rows_granular.restype = i32
+    L.llmint8_quantize_rows_granular.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp]
+    L.llmint8_linear_granular.restype = i32
+    L.llmint8_linear_granular.argtypes = [vp, i32, i32, f32, i32, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp,
+                                          vp, sz, vp]
     L.llmint8_linear_events.restype = i32
-    L.llmint8_linear_events.argtypes = L.llmint8_linear.argtypes + [vp, vp]
+    L.llmint8_linear_events.argtypes = L.llmint8_linear_granular.argtypes + [vp, vp]
     L.llmint8_export_weight.restype = i32
     L.llmint8_export_weight.argtypes = [vp, i32, i32, vp, vp]
     L.llmint8_export_rows.restype = i32
@@ -147,8 +156,11 @@ class QuantizedRows:
     h: int
 
 
-def quantize_weight(W, ws=None):
-    """llmint8_quantize_weight: W [h, o] fp16 (device, contiguous) -> QuantizedWeight."""
+GRANULARITY = {"vectorwise": 0, "rowwise": 1, "tensorwise": 2}  # LLMINT8_VECTORWISE / _ROWWISE / _TENSORWISE
+
+
+def quantize_weight(W, ws=None, granularity="vectorwise"):
+    """llmint8_quantize_weight(_granular): W [h, o] fp16 (device, contiguous) -> QuantizedWeight."""
     torch = _torch()
     assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous() and W.dim() == 2
     h, o = W.shape
@@ -156,7 +168,11 @@ def quantize_weight(W, ws=None):
     cw = torch.empty(o, dtype=torch.float16, device=W.device)
     if ws is None:
         ws = Workspace.allocate(1, h, o, 1, W.device)
-    _check(lib().llmint8_quantize_weight(_ptr(W), h, o, _ptr(Wq), _ptr(cw), _ptr(ws.buf), ws.nbytes, _stream()))
+    if granularity == "vectorwise":
+        _check(lib().llmint8_quantize_weight(_ptr(W), h, o, _ptr(Wq), _ptr(cw), _ptr(ws.buf), ws.nbytes, _stream()))
+    else:
+        _check(lib().llmint8_quantize_weight_granular(_ptr(W), h, o, GRANULARITY[granularity], _ptr(Wq), _ptr(cw),
+                                                      _ptr(ws.buf), ws.nbytes, _stream()))
     return QuantizedWeight(Wq, cw, W, h, o)
 
 
@@ -174,8 +190,8 @@ def find_outliers(X, alpha, cap, ws, out=None):
     return out
 
 
-def quantize_rows(X, outl, out=None):
-    """llmint8_quantize_rows: X [s, h] fp16 + Outliers -> QuantizedRows."""
+def quantize_rows(X, outl, out=None, granularity="vectorwise"):
+    """llmint8_quantize_rows(_granular): X [s, h] fp16 + Outliers -> QuantizedRows."""
     torch = _torch()
     assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.dim() == 2
     s, h = X.shape
@@ -183,8 +199,13 @@ def quantize_rows(X, outl, out=None):
         out = QuantizedRows(torch.empty(xq_bytes(s, h), dtype=torch.int8, device=X.device),
                             torch.empty(s, dtype=torch.float16, device=X.device),
                             torch.empty((s, opad(outl.cap)), dtype=torch.float16, device=X.device), s, h)
-    _check(lib().llmint8_quantize_rows(_ptr(X), s, h, _ptr(outl.idx), _ptr(outl.count), outl.cap, _ptr(out.Xq),
-                                       _ptr(out.cx), _ptr(out.Xo), _stream()))
+    if granularity == "vectorwise":
+        _check(lib().llmint8_quantize_rows(_ptr(X), s, h, _ptr(outl.idx), _ptr(outl.count), outl.cap, _ptr(out.Xq),
+                                           _ptr(out.cx), _ptr(out.Xo), _stream()))
+    else:
+        _check(lib().llmint8_quantize_rows_granular(_ptr(X), s, h, _ptr(outl.idx), _ptr(outl.count), outl.cap,
+                                                    GRANULARITY[granularity], _ptr(out.Xq), _ptr(out.cx),
+                                                    _ptr(out.Xo), _stream()))
     return out
 
 
@@ -202,21 +223,27 @@ def matmul(rows, outl, qw, ws, out=None, want_c_i32=False):
     return (out, Cd) if want_c_i32 else out
 
 
-def linear(X, qw, alpha, outl, rows, ws, out=None, events=None):
-    """llmint8_linear: the three per-call steps in one C call, into preallocated buffers.
+def linear(X, qw, alpha, outl, rows, ws, out=None, events=None, granularity="vectorwise"):
+    """llmint8_linear(_granular): the three per-call steps in one C call, into preallocated buffers.
+    granularity must be the one qw was quantized with (it selects the constants of X here).
     events = (before_matmul, after_matmul): two torch.cuda.Event(enable_timing=True) that have been
     recorded once already (so that their handles exist); llmint8_linear_events records them again."""
     torch = _torch()
     s, h = X.shape
     if out is None:
         out = torch.empty((s, qw.o), dtype=torch.float16, device=X.device)
-    args = (_ptr(X), s, h, float(alpha), _ptr(qw.Wq), _ptr(qw.cw), _ptr(qw.W), qw.o, _ptr(outl.idx), outl.cap,
+    head = (_ptr(X), s, h, float(alpha))
+    tail = (_ptr(qw.Wq), _ptr(qw.cw), _ptr(qw.W), qw.o, _ptr(outl.idx), outl.cap,
             _ptr(outl.count), _ptr(outl.status), _ptr(rows.Xq), _ptr(rows.cx), _ptr(rows.Xo), _ptr(out),
             _ptr(ws.buf), ws.nbytes, _stream())
-    if events is None:
-        _check(lib().llmint8_linear(*args))
+    g = GRANULARITY[granularity]
+    if events is not None:
+        _check(lib().llmint8_linear_events(*head, g, *tail, C.c_void_p(events[0].cuda_event),
+                                           C.c_void_p(events[1].cuda_event)))
+    elif g == 0:
+        _check(lib().llmint8_linear(*head, *tail))
     else:
-        _check(lib().llmint8_linear_events(*args, C.c_void_p(events[0].cuda_event), C.c_void_p(events[1].cuda_event)))
+        _check(lib().llmint8_linear_granular(*head, g, *tail))
     return out
 
 

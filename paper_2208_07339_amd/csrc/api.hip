@@ -1,5 +1,7 @@
 // C-ABI entry points of libllmint8: argument checks, workspace carving and the
 // kernel sequences.  Declarations and argument contracts: include/llmint8.h.
+#include <cmath>
+
 #include "../../include/llmint8.h"
 #include "common.h"
 
@@ -73,10 +75,13 @@ size_t llmint8_workspace_bytes(int s, int h, int o, int cap)
     return scan_ws(s, h, o, cap) + rows_ws(o, cap) + 256;  // slack to align the caller's pointer
 }
 
-int llmint8_quantize_weight(const void* W_f16, int h, int o, int8_t* Wq, void* cw_f16, void* ws, size_t ws_bytes,
-                            llmint8_stream_t stream)
+static inline bool bad_granularity(int g) { return g < LLMINT8_VECTORWISE || g > LLMINT8_TENSORWISE; }
+
+int llmint8_quantize_weight_granular(const void* W_f16, int h, int o, int granularity, int8_t* Wq, void* cw_f16,
+                                     void* ws, size_t ws_bytes, llmint8_stream_t stream)
 {
-    if (!W_f16 || !Wq || !cw_f16 || !ws || h < 1 || o < 1) return LLMINT8_INVALID_ARG;
+    if (!W_f16 || !Wq || !cw_f16 || !ws || h < 1 || o < 1 || bad_granularity(granularity))
+        return LLMINT8_INVALID_ARG;
     if (misaligned(W_f16, 2) || misaligned(Wq, 16) || misaligned(cw_f16, 8)) return LLMINT8_INVALID_ARG;
     if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
     if (ws_bytes < weight_ws(h, o) + 256) return LLMINT8_WORKSPACE;
@@ -85,8 +90,15 @@ int llmint8_quantize_weight(const void* W_f16, int h, int o, int8_t* Wq, void* c
     const int nslab = colmax_slabs(h, o);
     hipError_t e = launch_colmax_partial(W_f16, h, o, part, nslab, st);
     if (e == hipSuccess) e = launch_colmax_final(part, nslab, o, (unsigned short*)cw_f16, st);
+    if (e == hipSuccess && granularity != LLMINT8_VECTORWISE) e = launch_spread_max((unsigned short*)cw_f16, o, st);
     if (e == hipSuccess) e = launch_quantize_weight(W_f16, h, o, (const unsigned short*)cw_f16, Wq, st);
     return hip_status(e);
+}
+
+int llmint8_quantize_weight(const void* W_f16, int h, int o, int8_t* Wq, void* cw_f16, void* ws, size_t ws_bytes,
+                            llmint8_stream_t stream)
+{
+    return llmint8_quantize_weight_granular(W_f16, h, o, LLMINT8_VECTORWISE, Wq, cw_f16, ws, ws_bytes, stream);
 }
 
 int llmint8_find_outliers(const void* X_f16, int s, int h, float alpha, int32_t* idx, int cap, int32_t* count,
@@ -108,17 +120,26 @@ int llmint8_find_outliers(const void* X_f16, int s, int h, float alpha, int32_t*
     return hip_status(e);
 }
 
-int llmint8_quantize_rows(const void* X_f16, int s, int h, const int32_t* idx, const int32_t* count, int cap,
-                          int8_t* Xq, void* cx_f16, void* Xo_f16, llmint8_stream_t stream)
+int llmint8_quantize_rows_granular(const void* X_f16, int s, int h, const int32_t* idx, const int32_t* count, int cap,
+                                   int granularity, int8_t* Xq, void* cx_f16, void* Xo_f16, llmint8_stream_t stream)
 {
-    if (!X_f16 || !idx || !count || !Xq || !cx_f16 || !Xo_f16 || s < 1 || h < 1 || cap < 1)
+    if (!X_f16 || !idx || !count || !Xq || !cx_f16 || !Xo_f16 || s < 1 || h < 1 || cap < 1 ||
+        bad_granularity(granularity))
         return LLMINT8_INVALID_ARG;
     if (misaligned(X_f16, 2) || misaligned(idx, 4) || misaligned(count, 4) || misaligned(Xq, 16) ||
         misaligned(cx_f16, 2) || misaligned(Xo_f16, 16))
         return LLMINT8_INVALID_ARG;
     if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
     return hip_status(launch_quantize_rows(X_f16, s, h, idx, count, cap, Xq, (unsigned short*)cx_f16,
-                                           (unsigned short*)Xo_f16, (hipStream_t)stream));
+                                           (unsigned short*)Xo_f16, granularity == LLMINT8_TENSORWISE,
+                                           (hipStream_t)stream));
+}
+
+int llmint8_quantize_rows(const void* X_f16, int s, int h, const int32_t* idx, const int32_t* count, int cap,
+                          int8_t* Xq, void* cx_f16, void* Xo_f16, llmint8_stream_t stream)
+{
+    return llmint8_quantize_rows_granular(X_f16, s, h, idx, count, cap, LLMINT8_VECTORWISE, Xq, cx_f16, Xo_f16,
+                                          stream);
 }
 
 int llmint8_dequantize_rows(const int8_t* Wq, const void* cw_f16, int h, int o, const int32_t* idx,
@@ -171,14 +192,14 @@ int llmint8_matmul(const int8_t* Xq, const void* cx_f16, const void* Xo_f16, con
     return hip_status(e);
 }
 
-static int linear_impl(const void* X_f16, int s, int h, float alpha, const int8_t* Wq, const void* cw_f16,
+static int linear_impl(const void* X_f16, int s, int h, float alpha, int granularity, const int8_t* Wq, const void* cw_f16,
                        const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status, int8_t* Xq,
                        void* cx_f16, void* Xo_f16, void* Out_f16, void* ws, size_t ws_bytes, llmint8_stream_t stream,
                        hipEvent_t ev_before, hipEvent_t ev_after)
 {
     // validate everything before anything is enqueued
     if (!X_f16 || !idx || !count || !ws || !Xq || !cx_f16 || !Xo_f16 || !Wq || !cw_f16 || !Out_f16 || s < 1 || h < 1 ||
-        o < 1 || cap < 1)
+        o < 1 || cap < 1 || bad_granularity(granularity))
         return LLMINT8_INVALID_ARG;
     if (misaligned(X_f16, 2) || misaligned(idx, 4) || misaligned(count, 4) || misaligned(status, 4) ||
         misaligned(Xq, 16) || misaligned(Wq, 16) || misaligned(Xo_f16, 16) || misaligned(cw_f16, 8) ||
@@ -191,18 +212,25 @@ static int linear_impl(const void* X_f16, int s, int h, float alpha, const int8_
     hipStream_t st = (hipStream_t)stream;
     char* base = (char*)ws_base(ws);
     const OutlierLists L = carve_outlier_lists(base, h, cap);
+    // the constants of W were fixed when it was quantized; here only those of X depend on the granularity
+    const int shared_cx = granularity == LLMINT8_TENSORWISE;
     hipError_t e;
     if (s <= 32) {
         e = launch_prepass_small(X_f16, s, h, threshold_bits(alpha), L, idx, cap, count, status,
-                                 (unsigned short*)cx_f16, (unsigned short*)Xo_f16, Xq, st);
+                                 (unsigned short*)cx_f16, (unsigned short*)Xo_f16, Xq, shared_cx, st);
     } else {
-        unsigned short* part = (unsigned short*)(base + scratch_ws(h, cap));
-        const int nslab = colmax_slabs(s, h);
-        e = launch_colmax_partial(X_f16, s, h, part, nslab, st);
-        if (e == hipSuccess) e = launch_outlier_lists(part, nslab, h, threshold_bits(alpha), L, cap, st);
+        if (std::isinf(alpha) && alpha > 0.0f) {
+            // no decomposition (the baselines of Table 1 without it): O is empty, X need not be scanned
+            e = launch_clear_lists(L, h, st);
+        } else {
+            unsigned short* part = (unsigned short*)(base + scratch_ws(h, cap));
+            const int nslab = colmax_slabs(s, h);
+            e = launch_colmax_partial(X_f16, s, h, part, nslab, st);
+            if (e == hipSuccess) e = launch_outlier_lists(part, nslab, h, threshold_bits(alpha), L, cap, st);
+        }
         if (e == hipSuccess)
             e = launch_quantize_rows_lists(X_f16, s, h, L, idx, count, status, cap, Xq, (unsigned short*)cx_f16,
-                                           (unsigned short*)Xo_f16, st);
+                                           (unsigned short*)Xo_f16, shared_cx, st);
     }
     if (e == hipSuccess && ev_before) e = hipEventRecord(ev_before, st);
     if (e != hipSuccess) return hip_status(e);
@@ -216,17 +244,27 @@ int llmint8_linear(const void* X_f16, int s, int h, float alpha, const int8_t* W
                    const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status, int8_t* Xq,
                    void* cx_f16, void* Xo_f16, void* Out_f16, void* ws, size_t ws_bytes, llmint8_stream_t stream)
 {
-    return linear_impl(X_f16, s, h, alpha, Wq, cw_f16, W_f16, o, idx, cap, count, status, Xq, cx_f16, Xo_f16, Out_f16,
-                       ws, ws_bytes, stream, nullptr, nullptr);
+    return linear_impl(X_f16, s, h, alpha, LLMINT8_VECTORWISE, Wq, cw_f16, W_f16, o, idx, cap, count, status, Xq,
+                       cx_f16, Xo_f16, Out_f16, ws, ws_bytes, stream, nullptr, nullptr);
 }
 
-int llmint8_linear_events(const void* X_f16, int s, int h, float alpha, const int8_t* Wq, const void* cw_f16,
+int llmint8_linear_granular(const void* X_f16, int s, int h, float alpha, int granularity, const int8_t* Wq,
+                            const void* cw_f16, const void* W_f16, int o, int32_t* idx, int cap, int32_t* count,
+                            int32_t* status, int8_t* Xq, void* cx_f16, void* Xo_f16, void* Out_f16, void* ws,
+                            size_t ws_bytes, llmint8_stream_t stream)
+{
+    return linear_impl(X_f16, s, h, alpha, granularity, Wq, cw_f16, W_f16, o, idx, cap, count, status, Xq, cx_f16,
+                       Xo_f16, Out_f16, ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+int llmint8_linear_events(const void* X_f16, int s, int h, float alpha, int granularity, const int8_t* Wq, const void* cw_f16,
                           const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status,
                           int8_t* Xq, void* cx_f16, void* Xo_f16, void* Out_f16, void* ws, size_t ws_bytes,
                           llmint8_stream_t stream, void* ev_before_matmul, void* ev_after_matmul)
 {
-    return linear_impl(X_f16, s, h, alpha, Wq, cw_f16, W_f16, o, idx, cap, count, status, Xq, cx_f16, Xo_f16, Out_f16,
-                       ws, ws_bytes, stream, (hipEvent_t)ev_before_matmul, (hipEvent_t)ev_after_matmul);
+    return linear_impl(X_f16, s, h, alpha, granularity, Wq, cw_f16, W_f16, o, idx, cap, count, status, Xq, cx_f16,
+                       Xo_f16, Out_f16, ws, ws_bytes, stream, (hipEvent_t)ev_before_matmul,
+                       (hipEvent_t)ev_after_matmul);
 }
 
 int llmint8_debug_prefill_tile(int cfg)

@@ -83,20 +83,24 @@ hipError_t launch_outlier_lists(const unsigned short* part, int nslab, int h, un
                                 hipStream_t st);
 hipError_t launch_merge_lists(OutlierLists L, int h, int32_t* idx, int cap, int32_t* count, int32_t* status,
                               hipStream_t st);
+// empty lists without a scan (no outlier columns: alpha = +inf)
+hipError_t launch_clear_lists(OutlierLists L, int h, hipStream_t st);
+// c[0 .. n) <- max(c): one constant for a whole tensor (shared_cx below does this to c_x)
+hipError_t launch_spread_max(unsigned short* c, int n, hipStream_t st);
 // row constants + codes + gathered columns fed by the lists; also writes idx, count, status
 hipError_t launch_quantize_rows_lists(const void* X, int s, int h, OutlierLists L, int32_t* idx, int32_t* count,
                                       int32_t* status, int cap, int8_t* Xq, unsigned short* cx, unsigned short* Xo,
-                                      hipStream_t st);
+                                      int shared_cx, hipStream_t st);
 // whole pre-pass of a short X (s <= 32): outlier scan, row constants, codes, gathered columns
 hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
                                 int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,
-                                hipStream_t st);
+                                int shared_cx, hipStream_t st);
 hipError_t launch_colmax_final(const unsigned short* part, int nslab, int cols, unsigned short* out,
                                hipStream_t st);
 hipError_t launch_quantize_weight(const void* W, int h, int o, const unsigned short* cw, int8_t* Wq,
                                   hipStream_t st);
 hipError_t launch_quantize_rows(const void* X, int s, int h, const int32_t* idx, const int32_t* count, int cap,
-                                int8_t* Xq, unsigned short* cx, unsigned short* Xo, hipStream_t st);
+                                int8_t* Xq, unsigned short* cx, unsigned short* Xo, int shared_cx, hipStream_t st);
 hipError_t launch_export_tiled(const int8_t* T, int rows, int h, int8_t* out, int ld_rows_major,
                                hipStream_t st);
 // Wf: the original fp16 weights [h x o] (rows_are_slots = 0: outlier slot t uses row idx[t]), or the

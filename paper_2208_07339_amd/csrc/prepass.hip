@@ -234,6 +234,52 @@ hipError_t launch_merge_lists(OutlierLists L, int h, int32_t* idx, int cap, int3
     return hipGetLastError();
 }
 
+// no outlier columns at all (alpha = +inf is known on the host): empty lists without a scan of X
+__global__ void __launch_bounds__(256) clear_lists_kernel(int* __restrict__ count, int nl)
+{
+    const int l = blockIdx.x * 256 + threadIdx.x;
+    if (l < nl) count[l] = 0;
+}
+
+hipError_t launch_clear_lists(OutlierLists L, int h, hipStream_t st)
+{
+    const int nl = (h + 255) / 256;
+    clear_lists_kernel<<<(nl + 255) / 256, 256, 0, st>>>(L.count, nl);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// One constant for a whole tensor (absmax quantization as Section 2.1 defines
+// it; the row-wise and tensor-wise baselines of Table 1): every entry of
+// c[0 .. n) is replaced by the largest of them.  One workgroup; n is s or o.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024) spread_max_kernel(unsigned short* __restrict__ c, int n)
+{
+    __shared__ unsigned red[16];
+    const int tid = threadIdx.x;
+    unsigned m = 0;
+    for (int q = tid; q < n; q += 1024) {
+        const unsigned v = c[q];
+        m = v > m ? v : m;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const unsigned t = (unsigned)__shfl_xor((int)m, d);
+        m = t > m ? t : m;
+    }
+    if ((tid & 63) == 0) red[tid >> 6] = m;
+    __syncthreads();  // every read of c is done before the first write below
+#pragma unroll
+    for (int q = 0; q < 16; q++) m = red[q] > m ? red[q] : m;
+    for (int q = tid; q < n; q += 1024) c[q] = (unsigned short)m;
+}
+
+hipError_t launch_spread_max(unsigned short* c, int n, hipStream_t st)
+{
+    spread_max_kernel<<<1, 1024, 0, st>>>(c, n);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // Short X (s <= 32 tokens), two kernels for the whole pre-pass.
 //
@@ -324,7 +370,7 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
                                                              int32_t* __restrict__ status,
                                                              unsigned short* __restrict__ cx,
                                                              unsigned short* __restrict__ Xo,
-                                                             int8_t* __restrict__ Xq, int KT)
+                                                             int8_t* __restrict__ Xq, int KT, int shared_cx)
 {
     extern __shared__ unsigned fullmap[];  // ceil(h / 32) words, used only when |O| > cap
     __shared__ __attribute__((aligned(16))) int8_t stage[8 * TILE_BYTES];
@@ -423,6 +469,14 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
             }
     }
     __syncthreads();
+    if (shared_cx) {  // tensor-wise baseline: one constant, the largest of the row maxima (rows >= s hold 0)
+        unsigned t = 0;
+#pragma unroll
+        for (int q = 0; q < 32; q++) t = s_cxb[q] > t ? s_cxb[q] : t;
+        __syncthreads();
+        if (tid < 32) s_cxb[tid] = t;
+        __syncthreads();
+    }
 
     // ---- workgroup 0: the outputs of the outlier scan, c_x, Xo
     if (blockIdx.x == 0) {
@@ -471,7 +525,7 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
 
 hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
                                 int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,
-                                hipStream_t st)
+                                int shared_cx, hipStream_t st)
 {
     const int capc = list_capacity(cap);
     const int vec_ok = (h % 8 == 0) && aligned16(X);
@@ -481,7 +535,8 @@ hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, Outli
     if (e != hipSuccess) return e;
     const size_t shm = ((size_t)(h + 31) / 32) * sizeof(unsigned);
     quantize_small_kernel<<<(KT * 32 + 255) / 256, 256, shm, st>>>((const unsigned short*)X, s, h, L, capc, vec_ok, idx,
-                                                                   cap, opad_of(cap), count, status, cx, Xo, Xq, KT);
+                                                                   cap, opad_of(cap), count, status, cx, Xo, Xq, KT,
+                                                                   shared_cx);
     return hipGetLastError();
 }
 
@@ -743,7 +798,7 @@ __global__ void __launch_bounds__(256) quantize_rows_kernel(const unsigned short
 }
 
 hipError_t launch_quantize_rows(const void* X, int s, int h, const int32_t* idx, const int32_t* count, int cap,
-                                int8_t* Xq, unsigned short* cx, unsigned short* Xo, hipStream_t st)
+                                int8_t* Xq, unsigned short* cx, unsigned short* Xo, int shared_cx, hipStream_t st)
 {
     const int KT = k_tiles(h), RT = row_tiles(s);
     const int opad = opad_of(cap);
@@ -753,6 +808,7 @@ hipError_t launch_quantize_rows(const void* X, int s, int h, const int32_t* idx,
     row_absmax_kernel<false><<<s, 256, shm, st>>>((const unsigned short*)X, s, h, (int32_t*)idx, (int32_t*)count,
                                                   nullptr, none, 0, cap, opad, cx, Xo, vec_ok);
     hipError_t e = hipGetLastError();
+    if (e == hipSuccess && shared_cx) e = launch_spread_max(cx, s, st);
     if (e != hipSuccess) return e;
     dim3 grid(RT, (KT * 32 + 255) / 256);
     quantize_rows_kernel<false><<<grid, 256, 0, st>>>((const unsigned short*)X, s, h, idx, count, none, 0, cap, cx, Xq,
@@ -763,7 +819,7 @@ hipError_t launch_quantize_rows(const void* X, int s, int h, const int32_t* idx,
 // the same two steps fed by the column lists of the scan; also writes idx, count, status
 hipError_t launch_quantize_rows_lists(const void* X, int s, int h, OutlierLists L, int32_t* idx, int32_t* count,
                                       int32_t* status, int cap, int8_t* Xq, unsigned short* cx, unsigned short* Xo,
-                                      hipStream_t st)
+                                      int shared_cx, hipStream_t st)
 {
     const int KT = k_tiles(h), RT = row_tiles(s);
     const int opad = opad_of(cap), capc = list_capacity(cap);
@@ -772,6 +828,7 @@ hipError_t launch_quantize_rows_lists(const void* X, int s, int h, OutlierLists 
     row_absmax_kernel<true><<<s, 256, shm, st>>>((const unsigned short*)X, s, h, idx, count, status, L, capc, cap, opad,
                                                  cx, Xo, vec_ok);
     hipError_t e = hipGetLastError();
+    if (e == hipSuccess && shared_cx) e = launch_spread_max(cx, s, st);
     if (e != hipSuccess) return e;
     dim3 grid(RT, (KT * 32 + 255) / 256);
     quantize_rows_kernel<true><<<grid, 256, 0, st>>>((const unsigned short*)X, s, h, idx, count, L, capc, cap, cx, Xq, KT,
