@@ -129,8 +129,8 @@ int llmint8_linear(const void *X_f16, int s, int h, float alpha, const int8_t *W
 
 /* Baselines of Table 1: the same calls with coarser absmax constants.
  *   LLMINT8_VECTORWISE  one constant per row of X and per column of W (Section 3.1; the calls above)
- *   LLMINT8_ROWWISE     one constant per row of X, ONE for all of W (Section 3 reads row-wise
- *                       quantization as the finer constants on the hidden-state side only)
+ *   LLMINT8_ROWWISE     one constant per row of X, ONE for all of W (Section 4.3: row-wise and
+ *                       vector-wise treat the hidden states alike and differ on the weight side)
  *   LLMINT8_TENSORWISE  ONE constant for X and one for W (absmax quantization of Section 2.1)
  * A shared constant is written into every entry of cx_f16 / cw_f16, so Eq. 7 and Eq. 8 and therefore
  * llmint8_matmul are unchanged.  With alpha < inf the constants of X are taken over the non-outlier
