@@ -61,6 +61,24 @@ def lib():
         L.oracle_sampled_granular.restype = None
         L.oracle_sampled_granular.argtypes = [u16p, u16p, C.c_int, C.c_int, C.c_int, i32p, C.c_int,
                                               C.c_int, i32p, i32p, C.c_int, i32p, u16p]
+        i64p = C.POINTER(C.c_int64)
+        L.oracle_zp_u.restype = C.c_longlong
+        L.oracle_zp_u.argtypes = [C.c_double, C.c_double]
+        L.oracle_zp_quantize_weight.restype = None
+        L.oracle_zp_quantize_weight.argtypes = [u16p, C.c_int, C.c_int, i8p, u16p, u16p, i32p, i32p]
+        L.oracle_zp_quantize_rows.restype = None
+        L.oracle_zp_quantize_rows.argtypes = [u16p, C.c_int, C.c_int, i32p, C.c_int, i8p, u16p, u16p, i32p, i32p]
+        L.oracle_zp_gemm.restype = None
+        L.oracle_zp_gemm.argtypes = [i8p, i32p, i8p, i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_int, i64p]
+        L.oracle_zp_output.restype = None
+        L.oracle_zp_output.argtypes = [i64p, u16p, u16p, u16p, u16p, u16p, u16p, i32p, C.c_int, C.c_int,
+                                       C.c_int, C.c_int, u16p]
+        L.oracle_zp_linear.restype = C.c_int
+        L.oracle_zp_linear.argtypes = [u16p, u16p, C.c_int, C.c_int, C.c_int, C.c_double, i32p, i8p, u16p,
+                                       u16p, i32p, i32p, i8p, u16p, u16p, i32p, i32p, i32p, i64p, u16p]
+        L.oracle_zp_sampled.restype = None
+        L.oracle_zp_sampled.argtypes = [u16p, u16p, C.c_int, C.c_int, C.c_int, i32p, C.c_int, i32p, i32p,
+                                        C.c_int, i32p, u16p]
         L.oracle_num_threads.restype = C.c_int
         L.oracle_set_num_threads.argtypes = [C.c_int]
         _lib = L
@@ -292,6 +310,81 @@ def sampled_granular(X, W, idx, rows, cols, granularity):
     lib().oracle_sampled_granular(_p(Xb, C.c_uint16), _p(Wb, C.c_uint16), s, h, o, _p(idx, C.c_int32),
                                   len(idx), GRANULARITY[granularity], _p(rows, C.c_int32),
                                   _p(cols, C.c_int32), n, _p(Cs, C.c_int32), _p(Os, C.c_uint16))
+    return Cs, Os.view(np.float16)
+
+
+def zp_u(x, D):
+    """Eq. 3 with the exact nd = 254 / D of Eq. 1: nearest integer to 254 x / D, ties to even."""
+    return lib().oracle_zp_u(float(x), float(D))
+
+
+def zp_quantize_weight(W):
+    """Zeropoint quantization of every column of W: codes, lo, hi (fp16), zp, column sums of the codes."""
+    Wb = _bits(W)
+    h, o = Wb.shape
+    Wq = np.zeros((h, o), dtype=np.int8)
+    lo, hi = np.zeros(o, dtype=np.uint16), np.zeros(o, dtype=np.uint16)
+    zp, cs = np.zeros(o, dtype=np.int32), np.zeros(o, dtype=np.int32)
+    lib().oracle_zp_quantize_weight(_p(Wb, C.c_uint16), h, o, _p(Wq, C.c_int8), _p(lo, C.c_uint16),
+                                    _p(hi, C.c_uint16), _p(zp, C.c_int32), _p(cs, C.c_int32))
+    return dict(Wq=Wq, lo=lo.view(np.float16), hi=hi.view(np.float16), zp=zp, colsum=cs)
+
+
+def zp_quantize_rows(X, idx):
+    """Zeropoint quantization of every row of X over its non-outlier columns (code 0 in the others)."""
+    Xb = _bits(X)
+    s, h = Xb.shape
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    Xq = np.zeros((s, h), dtype=np.int8)
+    lo, hi = np.zeros(s, dtype=np.uint16), np.zeros(s, dtype=np.uint16)
+    zp, rs = np.zeros(s, dtype=np.int32), np.zeros(s, dtype=np.int32)
+    lib().oracle_zp_quantize_rows(_p(Xb, C.c_uint16), s, h, _p(idx, C.c_int32), len(idx), _p(Xq, C.c_int8),
+                                  _p(lo, C.c_uint16), _p(hi, C.c_uint16), _p(zp, C.c_int32), _p(rs, C.c_int32))
+    return dict(Xq=Xq, lo=lo.view(np.float16), hi=hi.view(np.float16), zp=zp, rowsum=rs)
+
+
+def zp_linear(X, W, alpha):
+    """The whole call with zeropoint quantization (Eq. 1-5) in place of absmax.  Dict of every stage."""
+    Xb, Wb = _bits(X), _bits(W)
+    s, h = Xb.shape
+    h2, o = Wb.shape
+    assert h == h2
+    idx = np.zeros(max(h, 1), dtype=np.int32)
+    Xq, Wq = np.zeros((s, h), dtype=np.int8), np.zeros((h, o), dtype=np.int8)
+    loa, hia, za, rs = (np.zeros(s, np.uint16), np.zeros(s, np.uint16), np.zeros(s, np.int32),
+                        np.zeros(s, np.int32))
+    lob, hib, zb, cs = (np.zeros(o, np.uint16), np.zeros(o, np.uint16), np.zeros(o, np.int32),
+                        np.zeros(o, np.int32))
+    Cm = np.zeros((s, o), dtype=np.int32)
+    T = np.zeros((s, o), dtype=np.int64)
+    Out = np.zeros((s, o), dtype=np.uint16)
+    n = lib().oracle_zp_linear(_p(Xb, C.c_uint16), _p(Wb, C.c_uint16), s, h, o, float(alpha), _p(idx, C.c_int32),
+                               _p(Xq, C.c_int8), _p(loa, C.c_uint16), _p(hia, C.c_uint16), _p(za, C.c_int32),
+                               _p(rs, C.c_int32), _p(Wq, C.c_int8), _p(lob, C.c_uint16), _p(hib, C.c_uint16),
+                               _p(zb, C.c_int32), _p(cs, C.c_int32), _p(Cm, C.c_int32), _p(T, C.c_int64),
+                               _p(Out, C.c_uint16))
+    if n == -1:
+        raise OverflowError("int32 accumulator overflow")
+    if n == -2:
+        raise ValueError("inputs must be finite")
+    return {"idx": idx[:n].copy(), "Xq": Xq, "lo_x": loa.view(np.float16), "hi_x": hia.view(np.float16),
+            "zp_x": za, "rowsum": rs, "Wq": Wq, "lo_w": lob.view(np.float16), "hi_w": hib.view(np.float16),
+            "zp_w": zb, "colsum": cs, "C": Cm, "T": T, "Out": Out.view(np.float16)}
+
+
+def zp_sampled(X, W, idx, rows, cols):
+    """Plain int8 product C[i,j] and Out[i,j] of the zeropoint variant for listed pairs, from the definition."""
+    Xb, Wb = _bits(X), _bits(W)
+    s, h = Xb.shape
+    o = Wb.shape[1]
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    cols = np.ascontiguousarray(cols, dtype=np.int32)
+    n = len(rows)
+    Cs = np.zeros(n, dtype=np.int32)
+    Os = np.zeros(n, dtype=np.uint16)
+    lib().oracle_zp_sampled(_p(Xb, C.c_uint16), _p(Wb, C.c_uint16), s, h, o, _p(idx, C.c_int32), len(idx),
+                            _p(rows, C.c_int32), _p(cols, C.c_int32), n, _p(Cs, C.c_int32), _p(Os, C.c_uint16))
     return Cs, Os.view(np.float16)
 
 

@@ -27,7 +27,9 @@
  * half-step bound and a float64 library matmul of the dequantized weights;
  * the row-wise and tensor-wise baselines against exact rational arithmetic,
  * closed forms on integer-valued inputs and the vector-wise functions on inputs
- * whose rows / columns share one maximum.  Numbers printed by the paper: none exist for this path, so
+ * whose rows / columns share one maximum; the zeropoint variant against exact
+ * rational arithmetic, the identity of Eq. 4 and Eq. 5, integer-grid inputs and
+ * the absmax functions on ranges symmetric about zero.  Numbers printed by the paper: none exist for this path, so
  * end-to-end agreement with the authors' own runs is unpinned.
  */
 #include <fenv.h>
@@ -483,6 +485,213 @@ void oracle_sampled_granular(const uint16_t *X, const uint16_t *W, int s, int h,
         }
         C_out[p] = (int32_t)acc;
         Out_out[p] = oracle_double_to_f16((double)acc * mx * mw / 16129.0 + hi);
+    }
+    free(is_out);
+}
+
+/* ---- zeropoint quantization (Section 2.1, Eq. 1-5), vector-wise ------------ */
+
+/* Asymmetric quantization of one vector v (a row of X without its outlier
+ * columns, or a column of W) with lo = min v, hi = max v, D = hi - lo:
+ *   Eq. 1  nd = 2 * 127 / D             (kept exact: the quotient is never rounded on its own)
+ *   Eq. 3  u(x) = nearest integer to nd * x, ties to even
+ *   Eq. 2  zp = u(lo) + 127             (the paper prints "X * min" where nd * min is meant; the
+ *                                        127 recentres the stored byte into [-127, 127], the range
+ *                                        the text names, instead of [0, 254])
+ *   stored code = u(x) - zp in [-127, 127]; Eq. 4 adds zp back: code + zp = u(x).
+ * D == 0 (a constant vector): codes 0, zp 0, and the vector counts as all zero.
+ * lo and hi are exact fp16 values and travel as bit patterns (a zero as +0).
+ *
+ * 254 * x is exact in double, D = hi - lo is exact in double (at most 41
+ * significant bits), the division is correctly rounded, and a quotient that is
+ * not a tie lies at least 2^-50 (relative) from the nearest half-integer, so
+ * nearbyint() of the double quotient is the exact answer.                     */
+long long oracle_zp_u(double x, double D)
+{
+    if (D == 0.0)
+        return 0;
+    return llrint(254.0 * x / D);
+}
+
+static void zp_range(const uint16_t *v, size_t stride, int n, const uint8_t *skip, uint16_t *lo, uint16_t *hi)
+{
+    double mn = 0.0, mx = 0.0;
+    uint16_t mnb = 0, mxb = 0;
+    int first = 1;
+    for (int q = 0; q < n; q++) {
+        if (skip && skip[q])
+            continue;
+        uint16_t b = v[(size_t)q * stride];
+        double x = oracle_f16_to_double(b);
+        if (x == 0.0)
+            b = 0;
+        if (first || x < mn) {
+            mn = x;
+            mnb = b;
+        }
+        if (first || x > mx) {
+            mx = x;
+            mxb = b;
+        }
+        first = 0;
+    }
+    *lo = mnb;
+    *hi = mxb;
+}
+
+/* columns of W: codes, range, zeropoint and the column sums of the codes over all h rows */
+void oracle_zp_quantize_weight(const uint16_t *W, int h, int o, int8_t *Wq, uint16_t *lo, uint16_t *hi,
+                               int32_t *zp, int32_t *colsum)
+{
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < o; j++) {
+        zp_range(W + j, (size_t)o, h, NULL, &lo[j], &hi[j]);
+        double l = oracle_f16_to_double(lo[j]), D = oracle_f16_to_double(hi[j]) - l;
+        long long z = D == 0.0 ? 0 : oracle_zp_u(l, D) + 127;
+        long long sum = 0;
+        for (int k = 0; k < h; k++) {
+            long long c = D == 0.0 ? 0 : oracle_zp_u(oracle_f16_to_double(W[(size_t)k * o + j]), D) - z;
+            Wq[(size_t)k * o + j] = (int8_t)c;
+            sum += c;
+        }
+        zp[j] = (int32_t)z;
+        colsum[j] = (int32_t)sum;
+    }
+}
+
+/* rows of X over the non-outlier columns; code 0 in the outlier columns; row sums of the codes */
+void oracle_zp_quantize_rows(const uint16_t *X, int s, int h, const int32_t *idx, int count, int8_t *Xq,
+                             uint16_t *lo, uint16_t *hi, int32_t *zp, int32_t *rowsum)
+{
+    uint8_t *is_out = (uint8_t *)calloc((size_t)h, 1);
+    for (int t = 0; t < count; t++)
+        is_out[idx[t]] = 1;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < s; i++) {
+        zp_range(X + (size_t)i * h, 1, h, is_out, &lo[i], &hi[i]);
+        double l = oracle_f16_to_double(lo[i]), D = oracle_f16_to_double(hi[i]) - l;
+        long long z = D == 0.0 ? 0 : oracle_zp_u(l, D) + 127;
+        long long sum = 0;
+        for (int j = 0; j < h; j++) {
+            long long c = 0;
+            if (!is_out[j] && D != 0.0)
+                c = oracle_zp_u(oracle_f16_to_double(X[(size_t)i * h + j]), D) - z;
+            Xq[(size_t)i * h + j] = (int8_t)c;
+            sum += c;
+        }
+        zp[i] = (int32_t)z;
+        rowsum[i] = (int32_t)sum;
+    }
+    free(is_out);
+}
+
+/* Eq. 4 over the non-outlier features: T[i][j] = sum_{k not in O} (A[i][k] + za[i]) (B[k][j] + zb[j]).
+ * 64-bit sums: with zeropoints far from 0 the terms do not fit 32 bits.       */
+void oracle_zp_gemm(const int8_t *Xq, const int32_t *za, const int8_t *Wq, const int32_t *zb, const int32_t *idx,
+                    int count, int s, int h, int o, int64_t *T)
+{
+    uint8_t *is_out = (uint8_t *)calloc((size_t)h, 1);
+    for (int t = 0; t < count; t++)
+        is_out[idx[t]] = 1;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < s; i++) {
+        int64_t *acc = (int64_t *)calloc((size_t)o, sizeof(int64_t));
+        for (int k = 0; k < h; k++) {
+            if (is_out[k])
+                continue;
+            int64_t a = (int64_t)Xq[(size_t)i * h + k] + za[i];
+            for (int j = 0; j < o; j++)
+                acc[j] += a * ((int64_t)Wq[(size_t)k * o + j] + zb[j]);
+        }
+        memcpy(T + (size_t)i * o, acc, (size_t)o * sizeof(int64_t));
+        free(acc);
+    }
+    free(is_out);
+}
+
+/* Dequantization (division by nd_a nd_b, i.e. multiplication by D_a D_b / 254^2) plus the 16-bit
+ * outlier product of Eq. 8                                                    */
+void oracle_zp_output(const int64_t *T, const uint16_t *loa, const uint16_t *hia, const uint16_t *lob,
+                      const uint16_t *hib, const uint16_t *X, const uint16_t *W, const int32_t *idx, int count,
+                      int s, int h, int o, uint16_t *Out)
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < s; i++) {
+        double *acc = (double *)calloc((size_t)o, sizeof(double));
+        for (int t = 0; t < count; t++) {
+            int k = idx[t];
+            double x = oracle_f16_to_double(X[(size_t)i * h + k]);
+            for (int j = 0; j < o; j++)
+                acc[j] += x * oracle_f16_to_double(W[(size_t)k * o + j]);
+        }
+        double Da = oracle_f16_to_double(hia[i]) - oracle_f16_to_double(loa[i]);
+        for (int j = 0; j < o; j++) {
+            double Db = oracle_f16_to_double(hib[j]) - oracle_f16_to_double(lob[j]);
+            double d = (double)T[(size_t)i * o + j] * Da * Db / 64516.0;
+            Out[(size_t)i * o + j] = oracle_double_to_f16(d + acc[j]);
+        }
+        free(acc);
+    }
+}
+
+/* The whole call with zeropoint quantization in place of absmax.  C receives the plain int8
+ * product sum_k A B of Eq. 5 (what the matrix unit computes), T the full sum of Eq. 4.
+ * Returns |O|, -1 if C leaves int32, -2 for non-finite input.                 */
+int oracle_zp_linear(const uint16_t *X, const uint16_t *W, int s, int h, int o, double alpha, int32_t *idx,
+                     int8_t *Xq, uint16_t *loa, uint16_t *hia, int32_t *za, int32_t *rowsum, int8_t *Wq,
+                     uint16_t *lob, uint16_t *hib, int32_t *zb, int32_t *colsum, int32_t *C, int64_t *T,
+                     uint16_t *Out)
+{
+    for (size_t n = 0; n < (size_t)s * h; n++)
+        if ((X[n] & 0x7c00u) == 0x7c00u)
+            return -2;
+    for (size_t n = 0; n < (size_t)h * o; n++)
+        if ((W[n] & 0x7c00u) == 0x7c00u)
+            return -2;
+    int count = oracle_find_outliers(X, s, h, alpha, idx, h);
+    oracle_zp_quantize_weight(W, h, o, Wq, lob, hib, zb, colsum);
+    oracle_zp_quantize_rows(X, s, h, idx, count, Xq, loa, hia, za, rowsum);
+    if (oracle_igemm(Xq, Wq, s, h, o, C))
+        return -1;
+    oracle_zp_gemm(Xq, za, Wq, zb, idx, count, s, h, o, T);
+    oracle_zp_output(T, loa, hia, lob, hib, X, W, idx, count, s, h, o, Out);
+    return count;
+}
+
+/* single outputs of a large problem, each from the definition (as oracle_sampled) */
+void oracle_zp_sampled(const uint16_t *X, const uint16_t *W, int s, int h, int o, const int32_t *idx, int count,
+                       const int32_t *rows, const int32_t *cols, int n, int32_t *C_out, uint16_t *Out_out)
+{
+    (void)s;
+    uint8_t *is_out = (uint8_t *)calloc((size_t)h, 1);
+    for (int t = 0; t < count; t++)
+        is_out[idx[t]] = 1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int p = 0; p < n; p++) {
+        int i = rows[p], j = cols[p];
+        uint16_t la, ha, lb, hb;
+        zp_range(X + (size_t)i * h, 1, h, is_out, &la, &ha);
+        zp_range(W + j, (size_t)o, h, NULL, &lb, &hb);
+        double l_a = oracle_f16_to_double(la), Da = oracle_f16_to_double(ha) - l_a;
+        double l_b = oracle_f16_to_double(lb), Db = oracle_f16_to_double(hb) - l_b;
+        long long za = Da == 0.0 ? 0 : oracle_zp_u(l_a, Da) + 127;
+        long long zb = Db == 0.0 ? 0 : oracle_zp_u(l_b, Db) + 127;
+        int64_t acc = 0, T = 0;
+        double hi = 0.0;
+        for (int k = 0; k < h; k++) {
+            double x = oracle_f16_to_double(X[(size_t)i * h + k]);
+            double w = oracle_f16_to_double(W[(size_t)k * o + j]);
+            if (is_out[k]) {
+                hi += x * w;
+                continue;
+            }
+            long long a = Da == 0.0 ? 0 : oracle_zp_u(x, Da) - za;
+            long long b = Db == 0.0 ? 0 : oracle_zp_u(w, Db) - zb;
+            acc += a * b;
+            T += (a + za) * (b + zb);
+        }
+        C_out[p] = (int32_t)acc;
+        Out_out[p] = oracle_double_to_f16((double)T * Da * Db / 64516.0 + hi);
     }
     free(is_out);
 }
