@@ -155,6 +155,36 @@ int llmint8_linear_events(const void *X_f16, int s, int h, float alpha, int gran
                           int8_t *Xq, void *cx_f16, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
                           llmint8_stream_t stream, void *ev_before_matmul, void *ev_after_matmul);
 
+/* Zeropoint variant (Section 2.1, Eq. 1-5; Table 1 "zeropoint vector-wise" and, with alpha < inf,
+ * "Zeropoint LLM.int8()"): asymmetric quantization with one set of constants per row of X (over its
+ * non-outlier columns) and per column of W, in place of absmax.  For a vector with lo = min, hi = max,
+ * D = hi - lo:  nd = 254 / D exactly (Eq. 1);  u(x) = round-half-even(254 x / D) (Eq. 3);
+ * zp = u(lo) + 127 (Eq. 2: the printed "X min" read as nd min; the 127 recentres the stored byte
+ * into the signed range [-127, 127] the text names);  stored code = u(x) - zp.  A constant vector
+ * (D = 0) gets codes 0 and zp 0 and counts as all zero.  Eq. 4: T[i][j] = sum over k not in O of
+ * (A[i][k] + zp_x[i]) (B[k][j] + zp_w[j]), computed in the unrolled form of Eq. 5 (int8 MFMA product
+ * plus three correction terms, added in double);  Out = fp16(T D_x[i] D_w[j] / 254^2 + Xo W_f16[O,:]).
+ *
+ * Constants travel as records of four int32 per vector (16-byte aligned arrays zc_x [s][4], zc_w [o][4]):
+ *   word 0  fp16 bit patterns of lo (low half) and hi (high half), a zero as +0
+ *   word 1  zp
+ *   word 2  sum of the vector's codes (row sum of X_i8 / column sum of W_i8 over all h)
+ *   word 3  0
+ * Xq, Wq, Xo, idx, count, status, ws as in the calls above; W_f16 is required.                  */
+int llmint8_zp_quantize_weight(const void *W_f16, int h, int o, int8_t *Wq, int32_t *zc_w, void *ws,
+                               size_t ws_bytes, llmint8_stream_t stream);
+int llmint8_zp_quantize_rows(const void *X_f16, int s, int h, const int32_t *idx, const int32_t *count, int cap,
+                             int8_t *Xq, int32_t *zc_x, void *Xo_f16, llmint8_stream_t stream);
+/* C_i32_debug receives the plain int8 product sum_k A[i][k] B[k][j] (the first term of Eq. 5). */
+int llmint8_zp_matmul(const int8_t *Xq, const int32_t *zc_x, const void *Xo_f16, const int32_t *idx,
+                      const int32_t *count, int cap, const int8_t *Wq, const int32_t *zc_w, const void *W_f16,
+                      int s, int h, int o, void *Out_f16, int32_t *C_i32_debug, void *ws, size_t ws_bytes,
+                      llmint8_stream_t stream);
+int llmint8_zp_linear(const void *X_f16, int s, int h, float alpha, const int8_t *Wq, const int32_t *zc_w,
+                      const void *W_f16, int o, int32_t *idx, int cap, int32_t *count, int32_t *status,
+                      int8_t *Xq, int32_t *zc_x, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
+                      llmint8_stream_t stream);
+
 /* Test/support: force the workgroup tile of the prefill GEMM (output columns x tokens):
  * 0 = 256 x 256, 1 = 192 x 256, 2 = 128 x 256, 3 = 128 x 128; -1 = choose from the shape (default).
  * Process-wide; results do not depend on it.                                  */

@@ -11,6 +11,7 @@ SYMBOLS = [
     "llmint8_workspace_bytes", "llmint8_quantize_weight", "llmint8_find_outliers",
     "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_linear_events", "llmint8_dequantize_rows",
     "llmint8_quantize_weight_granular", "llmint8_quantize_rows_granular", "llmint8_linear_granular",
+    "llmint8_zp_quantize_weight", "llmint8_zp_quantize_rows", "llmint8_zp_matmul", "llmint8_zp_linear",
     "llmint8_export_weight",
     "llmint8_export_rows", "llmint8_debug_prefill_tile",
     "llmint8_debug_decode_shape",
@@ -69,6 +70,14 @@ def lib():
                                           vp, sz, vp]
     L.llmint8_linear_events.restype = i32
     L.llmint8_linear_events.argtypes = L.llmint8_linear_granular.argtypes + [vp, vp]
+    L.llmint8_zp_quantize_weight.restype = i32
+    L.llmint8_zp_quantize_weight.argtypes = [vp, i32, i32, vp, vp, vp, sz, vp]
+    L.llmint8_zp_quantize_rows.restype = i32
+    L.llmint8_zp_quantize_rows.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
+    L.llmint8_zp_matmul.restype = i32
+    L.llmint8_zp_matmul.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    L.llmint8_zp_linear.restype = i32
+    L.llmint8_zp_linear.argtypes = [vp, i32, i32, f32, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.llmint8_export_weight.restype = i32
     L.llmint8_export_weight.argtypes = [vp, i32, i32, vp, vp]
     L.llmint8_export_rows.restype = i32
@@ -263,6 +272,79 @@ def dequantize_rows(qw, outl):
     out = torch.empty((opad(outl.cap), qw.o), dtype=torch.float16, device=qw.Wq.device)
     _check(lib().llmint8_dequantize_rows(_ptr(qw.Wq), _ptr(qw.cw), qw.h, qw.o, _ptr(outl.idx), _ptr(outl.count),
                                          outl.cap, _ptr(out), _stream()))
+    return out
+
+
+# ---- zeropoint variant (Eq. 1-5) -------------------------------------------------
+
+@dataclass
+class ZpWeight:
+    Wq: object     # int8 device tensor, private tiled layout
+    zc: object     # [o, 4] int32 records: lo | hi << 16 (fp16 bits), zp, column sum of the codes, 0
+    W: object      # [h, o] fp16 original (rows O are read by zp_matmul)
+    h: int
+    o: int
+
+
+@dataclass
+class ZpRows:
+    Xq: object     # int8 device tensor, private tiled layout
+    zc: object     # [s, 4] int32 records: lo | hi << 16, zp, row sum of the codes, 0
+    Xo: object     # [s, opad] fp16
+    s: int
+    h: int
+
+
+def zp_quantize_weight(W, ws=None):
+    """llmint8_zp_quantize_weight: W [h, o] fp16 (device, contiguous) -> ZpWeight."""
+    torch = _torch()
+    assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous() and W.dim() == 2
+    h, o = W.shape
+    Wq = torch.empty(wq_bytes(h, o), dtype=torch.int8, device=W.device)
+    zc = torch.empty((o, 4), dtype=torch.int32, device=W.device)
+    if ws is None:
+        ws = Workspace.allocate(1, h, o, 1, W.device)
+    _check(lib().llmint8_zp_quantize_weight(_ptr(W), h, o, _ptr(Wq), _ptr(zc), _ptr(ws.buf), ws.nbytes, _stream()))
+    return ZpWeight(Wq, zc, W, h, o)
+
+
+def zp_quantize_rows(X, outl, out=None):
+    """llmint8_zp_quantize_rows: X [s, h] fp16 + Outliers -> ZpRows."""
+    torch = _torch()
+    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.dim() == 2
+    s, h = X.shape
+    if out is None:
+        out = ZpRows(torch.empty(xq_bytes(s, h), dtype=torch.int8, device=X.device),
+                     torch.empty((s, 4), dtype=torch.int32, device=X.device),
+                     torch.empty((s, opad(outl.cap)), dtype=torch.float16, device=X.device), s, h)
+    _check(lib().llmint8_zp_quantize_rows(_ptr(X), s, h, _ptr(outl.idx), _ptr(outl.count), outl.cap, _ptr(out.Xq),
+                                          _ptr(out.zc), _ptr(out.Xo), _stream()))
+    return out
+
+
+def zp_matmul(rows, outl, qw, ws, out=None, want_c_i32=False):
+    """llmint8_zp_matmul -> Out [s, o] fp16 (and the plain int8 product if asked)."""
+    torch = _torch()
+    s, h, o = rows.s, rows.h, qw.o
+    assert h == qw.h
+    if out is None:
+        out = torch.empty((s, o), dtype=torch.float16, device=rows.Xq.device)
+    Cd = torch.empty((s, o), dtype=torch.int32, device=rows.Xq.device) if want_c_i32 else None
+    _check(lib().llmint8_zp_matmul(_ptr(rows.Xq), _ptr(rows.zc), _ptr(rows.Xo), _ptr(outl.idx), _ptr(outl.count),
+                                   outl.cap, _ptr(qw.Wq), _ptr(qw.zc), _ptr(qw.W), s, h, o, _ptr(out), _ptr(Cd),
+                                   _ptr(ws.buf), ws.nbytes, _stream()))
+    return (out, Cd) if want_c_i32 else out
+
+
+def zp_linear(X, qw, alpha, outl, rows, ws, out=None):
+    """llmint8_zp_linear: outlier scan, zeropoint quantization of X and the matmul in one C call."""
+    torch = _torch()
+    s, h = X.shape
+    if out is None:
+        out = torch.empty((s, qw.o), dtype=torch.float16, device=X.device)
+    _check(lib().llmint8_zp_linear(_ptr(X), s, h, float(alpha), _ptr(qw.Wq), _ptr(qw.zc), _ptr(qw.W), qw.o,
+                                   _ptr(outl.idx), outl.cap, _ptr(outl.count), _ptr(outl.status), _ptr(rows.Xq),
+                                   _ptr(rows.zc), _ptr(rows.Xo), _ptr(out), _ptr(ws.buf), ws.nbytes, _stream()))
     return out
 
 

@@ -22,10 +22,14 @@ inline size_t outlier_ws(int s, int h, int cap)
 inline size_t weight_ws(int h, int o) { return align_up((size_t)colmax_slabs(h, o) * o * 2, 256); }
 // rebuilt outlier rows of W (used when no fp16 weights are given): [opad x o] fp16, behind everything else
 inline size_t rows_ws(int o, int cap) { return align_up((size_t)opad_of(cap) * o * 2, 256); }
+// zeropoint variant: column minima and maxima of the weight scan; per call the column factors K [o] doubles
+inline size_t zp_weight_ws(int h, int o) { return align_up((size_t)2 * zp_colrange_slabs(h, o) * o * 2, 256); }
+inline size_t kcol_ws(int o) { return align_up((size_t)o * 8, 256); }
 inline size_t scan_ws(int s, int h, int o, int cap)
 {
-    const size_t a = outlier_ws(s, h, cap), b = weight_ws(h, o);
-    return a > b ? a : b;
+    const size_t a = outlier_ws(s, h, cap), b = weight_ws(h, o), c = zp_weight_ws(h, o);
+    const size_t m = a > b ? a : b;
+    return m > c ? m : c;
 }
 
 thread_local hipError_t g_last_hip = hipSuccess;  // reported by llmint8_last_hip_error()
@@ -72,7 +76,7 @@ size_t llmint8_xq_bytes(int s, int h)
 size_t llmint8_workspace_bytes(int s, int h, int o, int cap)
 {
     if (s < 1 || h < 1 || o < 1 || cap < 1) return 0;
-    return scan_ws(s, h, o, cap) + rows_ws(o, cap) + 256;  // slack to align the caller's pointer
+    return scan_ws(s, h, o, cap) + rows_ws(o, cap) + kcol_ws(o) + 256;  // slack to align the caller's pointer
 }
 
 static inline bool bad_granularity(int g) { return g < LLMINT8_VECTORWISE || g > LLMINT8_TENSORWISE; }
@@ -265,6 +269,82 @@ int llmint8_linear_events(const void* X_f16, int s, int h, float alpha, int gran
     return linear_impl(X_f16, s, h, alpha, granularity, Wq, cw_f16, W_f16, o, idx, cap, count, status, Xq, cx_f16,
                        Xo_f16, Out_f16, ws, ws_bytes, stream, (hipEvent_t)ev_before_matmul,
                        (hipEvent_t)ev_after_matmul);
+}
+
+// ---- zeropoint variant ------------------------------------------------------
+
+int llmint8_zp_quantize_weight(const void* W_f16, int h, int o, int8_t* Wq, int32_t* zc_w, void* ws, size_t ws_bytes,
+                               llmint8_stream_t stream)
+{
+    if (!W_f16 || !Wq || !zc_w || !ws || h < 1 || o < 1) return LLMINT8_INVALID_ARG;
+    if (misaligned(W_f16, 2) || misaligned(Wq, 16) || misaligned(zc_w, 16)) return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
+    if (ws_bytes < zp_weight_ws(h, o) + 256) return LLMINT8_WORKSPACE;
+    return hip_status(launch_zp_quantize_weight(W_f16, h, o, Wq, (int4*)zc_w, (unsigned short*)ws_base(ws),
+                                                (hipStream_t)stream));
+}
+
+int llmint8_zp_quantize_rows(const void* X_f16, int s, int h, const int32_t* idx, const int32_t* count, int cap,
+                             int8_t* Xq, int32_t* zc_x, void* Xo_f16, llmint8_stream_t stream)
+{
+    if (!X_f16 || !idx || !count || !Xq || !zc_x || !Xo_f16 || s < 1 || h < 1 || cap < 1) return LLMINT8_INVALID_ARG;
+    if (misaligned(X_f16, 2) || misaligned(idx, 4) || misaligned(count, 4) || misaligned(Xq, 16) ||
+        misaligned(zc_x, 16) || misaligned(Xo_f16, 16))
+        return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
+    return hip_status(launch_zp_quantize_rows(X_f16, s, h, idx, count, cap, Xq, (int4*)zc_x, (unsigned short*)Xo_f16,
+                                              (hipStream_t)stream));
+}
+
+int llmint8_zp_matmul(const int8_t* Xq, const int32_t* zc_x, const void* Xo_f16, const int32_t* idx,
+                      const int32_t* count, int cap, const int8_t* Wq, const int32_t* zc_w, const void* W_f16, int s,
+                      int h, int o, void* Out_f16, int32_t* C_i32_debug, void* ws, size_t ws_bytes,
+                      llmint8_stream_t stream)
+{
+    if (!Xq || !zc_x || !Xo_f16 || !idx || !count || !Wq || !zc_w || !W_f16 || !Out_f16 || !ws || s < 1 || h < 1 ||
+        o < 1 || cap < 1)
+        return LLMINT8_INVALID_ARG;
+    if (misaligned(Xq, 16) || misaligned(Wq, 16) || misaligned(Xo_f16, 16) || misaligned(zc_x, 16) ||
+        misaligned(zc_w, 16) || misaligned(W_f16, 2) || misaligned(Out_f16, 8) || misaligned(idx, 4) ||
+        misaligned(count, 4) || misaligned(C_i32_debug, 4))
+        return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
+    if (ws_bytes < llmint8_workspace_bytes(s, h, o, cap)) return LLMINT8_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    double* kcol = (double*)((char*)ws_base(ws) + scan_ws(s, h, o, cap) + rows_ws(o, cap));
+    hipError_t e = launch_zp_kcol(Wq, (const int4*)zc_w, h, o, idx, count, cap, kcol, st);
+    if (e != hipSuccess) return hip_status(e);
+    const ZpArgs zp = {(const int4*)zc_x, (const int4*)zc_w, kcol};
+    if (s <= 32)
+        e = launch_gemm_decode(Xq, nullptr, (const unsigned short*)Xo_f16, count, cap, Wq, nullptr,
+                               (const unsigned short*)W_f16, 0, idx, s, h, o, (unsigned short*)Out_f16, C_i32_debug,
+                               st, &zp);
+    else
+        e = launch_gemm_prefill(Xq, nullptr, (const unsigned short*)Xo_f16, count, cap, Wq, nullptr,
+                                (const unsigned short*)W_f16, 0, idx, s, h, o, (unsigned short*)Out_f16, C_i32_debug,
+                                st, &zp);
+    return hip_status(e);
+}
+
+int llmint8_zp_linear(const void* X_f16, int s, int h, float alpha, const int8_t* Wq, const int32_t* zc_w,
+                      const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status, int8_t* Xq,
+                      int32_t* zc_x, void* Xo_f16, void* Out_f16, void* ws, size_t ws_bytes, llmint8_stream_t stream)
+{
+    if (!X_f16 || !idx || !count || !ws || !Xq || !zc_x || !Xo_f16 || !Wq || !zc_w || !W_f16 || !Out_f16 || s < 1 ||
+        h < 1 || o < 1 || cap < 1)
+        return LLMINT8_INVALID_ARG;
+    if (misaligned(X_f16, 2) || misaligned(idx, 4) || misaligned(count, 4) || misaligned(status, 4) ||
+        misaligned(Xq, 16) || misaligned(Wq, 16) || misaligned(Xo_f16, 16) || misaligned(zc_x, 16) ||
+        misaligned(zc_w, 16) || misaligned(W_f16, 2) || misaligned(Out_f16, 8))
+        return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
+    if (ws_bytes < llmint8_workspace_bytes(s, h, o, cap)) return LLMINT8_WORKSPACE;
+    int r = llmint8_find_outliers(X_f16, s, h, alpha, idx, cap, count, status, ws, ws_bytes, stream);
+    if (r == LLMINT8_OK) r = llmint8_zp_quantize_rows(X_f16, s, h, idx, count, cap, Xq, zc_x, Xo_f16, stream);
+    if (r == LLMINT8_OK)
+        r = llmint8_zp_matmul(Xq, zc_x, Xo_f16, idx, count, cap, Wq, zc_w, W_f16, s, h, o, Out_f16, nullptr, ws,
+                              ws_bytes, stream);
+    return r;
 }
 
 int llmint8_debug_prefill_tile(int cfg)

@@ -31,6 +31,13 @@ __device__ inline float f16_bits_to_float(unsigned short b)
     return (float)__builtin_bit_cast(_Float16, b);  // exact widening
 }
 
+// hi - lo of a zeropoint record's first word (fp16 bits of lo in the low half, of hi in the high half): exact
+__device__ inline double zp_range(unsigned lohi)
+{
+    return (double)f16_bits_to_float((unsigned short)(lohi >> 16)) -
+           (double)f16_bits_to_float((unsigned short)(lohi & 0xffffu));
+}
+
 // Smallest magnitude bit pattern whose value is >= alpha (0 if alpha <= 0,
 // 0x7c00 if no finite fp16 reaches alpha).
 __host__ inline unsigned threshold_bits(float alpha)
@@ -103,16 +110,34 @@ hipError_t launch_quantize_rows(const void* X, int s, int h, const int32_t* idx,
                                 int8_t* Xq, unsigned short* cx, unsigned short* Xo, int shared_cx, hipStream_t st);
 hipError_t launch_export_tiled(const int8_t* T, int rows, int h, int8_t* out, int ld_rows_major,
                                hipStream_t st);
+// ---- zeropoint variant (Eq. 1-5; zeropoint.hip) ----
+// Constants of one row of X / one column of W: {lo | hi << 16 (fp16 bits), zp, sum of the codes, 0}.
+// part: scratch for 2 * zp_colrange_slabs(h, o) * o fp16 keys.
+int zp_colrange_slabs(int h, int o);
+hipError_t launch_zp_quantize_weight(const void* W, int h, int o, int8_t* Wq, int4* zc, unsigned short* part,
+                                     hipStream_t st);
+hipError_t launch_zp_quantize_rows(const void* X, int s, int h, const int32_t* idx, const int32_t* count, int cap,
+                                   int8_t* Xq, int4* zc, unsigned short* Xo, hipStream_t st);
+hipError_t launch_zp_kcol(const int8_t* Wq, const int4* zcw, int h, int o, const int32_t* idx, const int32_t* count,
+                          int cap, double* kcol, hipStream_t st);
+// What the GEMM epilogues need in place of c_x / c_w: T = C + zp_w[j] rowsum[i] + zp_x[i] K[j] (Eq. 5),
+// Out = T D_x[i] D_w[j] / 254^2 + outlier product.  All NULL: absmax constants.
+struct ZpArgs {
+    const int4* zcx;     // [s]
+    const int4* zcw;     // [o]
+    const double* kcol;  // [o] from launch_zp_kcol
+};
+
 // Wf: the original fp16 weights [h x o] (rows_are_slots = 0: outlier slot t uses row idx[t]), or the
 // rebuilt rows [opad x o] of launch_dequant_rows (rows_are_slots = 1: slot t uses row t)
 hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                                const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
                                const unsigned short* Wf, int rows_are_slots, const int32_t* idx, int s, int h, int o,
-                               unsigned short* Out, int32_t* Cdbg, hipStream_t st);
+                               unsigned short* Out, int32_t* Cdbg, hipStream_t st, const ZpArgs* zp = nullptr);
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
                               const unsigned short* Wf, int rows_are_slots, const int32_t* idx, int s, int h, int o,
-                              unsigned short* Out, int32_t* Cdbg, hipStream_t st);
+                              unsigned short* Out, int32_t* Cdbg, hipStream_t st, const ZpArgs* zp = nullptr);
 hipError_t launch_dequant_rows(const int8_t* Wq, const unsigned short* cw, int h, int o, const int32_t* idx,
                                const int32_t* count, int cap, unsigned short* Wo, hipStream_t st);
 

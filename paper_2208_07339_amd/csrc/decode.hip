@@ -22,14 +22,18 @@ constexpr int DSLOTS = 16;  // outlier slots whose operands are fetched before t
 // any order.  What the epilogue needs (c_w, c_x, the outlier columns of X and
 // the matching rows of the fp16 weights) is requested before the stream starts,
 // so that no workgroup ends with a chain of dependent loads.
-template <int NJ, int U>
+//
+// ZP: zeropoint constants (Eq. 1-5) in place of c_x / c_w: the epilogue adds the three correction
+// terms of the unrolled product of Eq. 5 to the accumulator (in double: with zeropoints far from 0
+// they are large and cancel) and divides by nd_x nd_w.
+template <int NJ, int U, bool ZP>
 __global__ void __launch_bounds__(256)
 gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq, int KT, int JT,
                    const unsigned short* __restrict__ cw, const unsigned short* __restrict__ cx,
                    const unsigned short* __restrict__ Wf, int rows_are_slots, int wrows,
                    const int32_t* __restrict__ idx, const unsigned short* __restrict__ Xo,
                    const int32_t* __restrict__ count, int cap, int opad,
-                   _Float16* __restrict__ Out, int32_t* __restrict__ Cdbg, int s, int h, int o)
+                   _Float16* __restrict__ Out, int32_t* __restrict__ Cdbg, int s, int h, int o, const ZpArgs zp)
 {
     __shared__ int red[4][NJ][16][64];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -44,15 +48,31 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     float cwj[NJ], sxi[4];
     unsigned wo[NJ][DSLOTS / 2];  // fp16 pairs: slots 2q (low half) and 2q+1 of this thread's columns
     uint4 xo[4][DSLOTS / 8];      // slots 0..15 of this thread's tokens (Xo holds zeros past |O|)
+    double zsb[ZP ? NJ : 1], zK[ZP ? NJ : 1], zsa[ZP ? 4 : 1];  // D_w / 254, K, D_x / 254
+    int zzb[ZP ? NJ : 1], zza[ZP ? 4 : 1], zrs[ZP ? 4 : 1];       // zp_w, zp_x, row sums of the codes
 #pragma unroll
     for (int n = 0; n < NJ; n++) {
         const int j = (jt0 + n) * 32 + jj;
-        cwj[n] = (j < o) ? f16_bits_to_float(cw[j]) : 0.0f;
+        if constexpr (ZP) {
+            const int4 r = (j < o) ? zp.zcw[j] : make_int4(0, 0, 0, 0);
+            zsb[n] = zp_range((unsigned)r.x) * (1.0 / 254.0);
+            zzb[n] = r.y;
+            zK[n] = (j < o) ? zp.kcol[j] : 0.0;
+        } else {
+            cwj[n] = (j < o) ? f16_bits_to_float(cw[j]) : 0.0f;
+        }
     }
 #pragma unroll
     for (int m = 0; m < 4; m++) {
         const int i = ig + 8 * m;
-        sxi[m] = (i < s) ? f16_bits_to_float(cx[i]) * (1.0f / 16129.0f) : 0.0f;
+        if constexpr (ZP) {
+            const int4 r = (i < s) ? zp.zcx[i] : make_int4(0, 0, 0, 0);
+            zsa[m] = zp_range((unsigned)r.x) * (1.0 / 254.0);
+            zza[m] = r.y;
+            zrs[m] = r.z;
+        } else {
+            sxi[m] = (i < s) ? f16_bits_to_float(cx[i]) * (1.0f / 16129.0f) : 0.0f;
+        }
     }
 #pragma unroll
     for (int m = 0; m < 4; m++) {
@@ -161,7 +181,13 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
             const int c = red[0][n][r][l] + red[1][n][r][l] + red[2][n][r][l] + red[3][n][r][l];
             if (Cdbg) Cdbg[(size_t)i * o + j] = c;
             // Eq. 7 dequantization, then the outlier product of Eq. 8 accumulated in fp32
-            float d = (float)c * sxi[m] * cwj[n];
+            float d;
+            if constexpr (ZP) {
+                const double T = (double)c + (double)zzb[n] * (double)zrs[m] + (double)zza[m] * zK[n];  // Eq. 5
+                d = (float)(T * zsa[m] * zsb[n]);
+            } else {
+                d = (float)c * sxi[m] * cwj[n];
+            }
 #pragma unroll
             for (int t = 0; t < DSLOTS; t++)
                 if (t < cnt) {
@@ -186,13 +212,20 @@ int g_decode_cfg = -1;  // test hook, as g_force_cfg
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
                               const unsigned short* Wf, int rows_are_slots, const int32_t* idx, int s, int h, int o,
-                              unsigned short* Out, int32_t* Cdbg, hipStream_t st)
+                              unsigned short* Out, int32_t* Cdbg, hipStream_t st, const ZpArgs* zp)
 {
     const int KT = k_tiles(h), JT = row_tiles(o);
     const int wrows = rows_are_slots ? opad_of(cap) : h;
+    const ZpArgs none = {nullptr, nullptr, nullptr};
+    if (zp) {
+        gemm_decode_kernel<2, 4, true><<<(JT + 1) / 2, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows,
+                                                                    idx, Xo, count, cap, opad_of(cap), (_Float16*)Out,
+                                                                    Cdbg, s, h, o, *zp);
+        return hipGetLastError();
+    }
 #define LAUNCH_DECODE(NJ, U)                                                                                     \
-    gemm_decode_kernel<NJ, U><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo, count, cap, \
-                                                                 opad_of(cap), (_Float16*)Out, Cdbg, s, h, o)
+    gemm_decode_kernel<NJ, U, false><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo, count, cap, \
+                                                                 opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, none)
     switch (g_decode_cfg) {
         case 1: LAUNCH_DECODE(1, 8); break;
         case 2: LAUNCH_DECODE(2, 4); break;

@@ -48,6 +48,7 @@ struct GemmArgs {
     int32_t* Cdbg;               // NULL or [s x o]
     int s, h, o;
     int fast_ok;                 // o % 8 == 0 and every epilogue operand 16-byte aligned
+    ZpArgs zp;                   // zeropoint constants (ZP kernels only)
 };
 
 // ---------------------------------------------------------------------------
@@ -83,7 +84,12 @@ struct GemmArgs {
 constexpr int NB = 4;
 constexpr int OSLOTS = 32;  // outlier slots staged through LDS; more are read from memory directly
 
-template <int WA, int WB>
+//
+// ZP: zeropoint constants (Eq. 1-5) in place of c_x / c_w.  Every tile then takes the guarded
+// epilogue, which reads its operands from memory, adds the correction terms of the unrolled
+// product of Eq. 5 to the accumulators (in double: with zeropoints far from 0 they are large and
+// cancel) and divides by nd_x nd_w.
+template <int WA, int WB, bool ZP>
 __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
 {
     constexpr int TW = 2 * WA, TX = 2 * WB;
@@ -145,7 +151,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         const int qi = q0 + inband - pj * bh;
         J0w = pj * 64 * WA;
         I0w = qi * 64 * WB;
-        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 64 * WB <= s);
+        interior = !ZP && g.fast_ok && !g.Cdbg && opad <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 64 * WB <= s);
 #pragma unroll
         for (int k = 0; k < PIECES; k++) {
             const int p = w * PIECES + k;
@@ -371,6 +377,8 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                     }
             }
             float sx[WB];      // c_x / 127^2 of this lane's tokens (Eq. 7: S = c_x (x) c_w / 127^2)
+            double zsa[ZP ? WB : 1];             // zeropoint: D_x / 254,
+            int zza[ZP ? WB : 1], zrs[ZP ? WB : 1];  // zp_x and the row sum of the codes
             v8h xb[WB][2];     // MFMA "B" operand of the outlier product: slots 8*gl .. +7 (+16) of this lane's tokens
 #pragma unroll
             for (int b = 0; b < WB; b++) {
@@ -382,7 +390,14 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                     xb[b][1] = (v8h)(0);
                     if (cnt > 16) xb[b][1] = *(const v8h*)(EX + il * (2 * opad) + (2 + gl) * 16);  // then opad == 32
                 } else {
-                    sx[b] = (i < s) ? f16_bits_to_float(g.cx[i]) * (1.0f / 16129.0f) : 0.0f;
+                    if constexpr (ZP) {
+                        const int4 rec = (i < s) ? g.zp.zcx[i] : make_int4(0, 0, 0, 0);
+                        zsa[b] = zp_range((unsigned)rec.x) * (1.0 / 254.0);
+                        zza[b] = rec.y;
+                        zrs[b] = rec.z;
+                    } else {
+                        sx[b] = (i < s) ? f16_bits_to_float(g.cx[i]) * (1.0f / 16129.0f) : 0.0f;
+                    }
                     xb[b][0] = cnt > 0 ? load_x_mem(i, 0) : (v8h)(0);
                     xb[b][1] = cnt > 16 ? load_x_mem(i, 16) : (v8h)(0);
                 }
@@ -414,10 +429,12 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                                 wa[aa][ks][e] =
                                     __builtin_bit_cast(_Float16, EW[(16 * ks + 8 * gl + e) * 256 + jl + ll]);
                     } else {
+                        if constexpr (!ZP) {
 #pragma unroll
-                        for (int r = 0; r < 16; r++) {
-                            const int j = cJ0w + jl + 8 * (r >> 2) + 4 * gl + (r & 3);
-                            cwv[aa][r] = (j < o) ? f16_bits_to_float(g.cw[j]) : 0.0f;
+                            for (int r = 0; r < 16; r++) {
+                                const int j = cJ0w + jl + 8 * (r >> 2) + 4 * gl + (r & 3);
+                                cwv[aa][r] = (j < o) ? f16_bits_to_float(g.cw[j]) : 0.0f;
+                            }
                         }
                         wa[aa][0] = cnt > 0 ? load_w_mem(cJ0w + jl + ll, 0) : (v8h)(0);
                         wa[aa][1] = cnt > 16 ? load_w_mem(cJ0w + jl + ll, 16) : (v8h)(0);
@@ -448,12 +465,30 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                                         const v8h xm = load_x_mem(I0 + b * 32 + ll, t0);
                                         t = __builtin_amdgcn_mfma_f32_32x32x16_f16(wm, xm, t, 0, 0, 0);
                                     }
+                                if constexpr (!ZP) {
 #pragma unroll
-                                for (int r = 0; r < 16; r++)
-                                    d[r] = __builtin_fmaf((float)acc[a][b][r] * sx[b], cwv[aa][r], t[r]);
+                                    for (int r = 0; r < 16; r++)
+                                        d[r] = __builtin_fmaf((float)acc[a][b][r] * sx[b], cwv[aa][r], t[r]);
+                                } else {
+                                    d = t;
+                                }
                             } else {
 #pragma unroll
-                                for (int r = 0; r < 16; r++) d[r] = (float)acc[a][b][r] * sx[b] * cwv[aa][r];
+                                for (int r = 0; r < 16; r++)
+                                    d[r] = ZP ? 0.0f : (float)acc[a][b][r] * sx[b] * cwv[aa][r];
+                            }
+                            if constexpr (ZP) {
+                                // Eq. 5: T = C + zp_w rowsum + zp_x K, then the division by nd_x nd_w; the
+                                // column constants are fetched here, one MFMA tile at a time
+#pragma unroll
+                                for (int r = 0; r < 16; r++) {
+                                    const int j = J0 + a * 32 + 8 * (r >> 2) + 4 * gl + (r & 3);
+                                    const int4 rec = (j < o) ? g.zp.zcw[j] : make_int4(0, 0, 0, 0);
+                                    const double K = (j < o) ? g.zp.kcol[j] : 0.0;
+                                    const double T = (double)acc[a][b][r] + (double)rec.y * (double)zrs[b] +
+                                                     (double)zza[b] * K;
+                                    d[r] += (float)(T * zsa[b] * (zp_range((unsigned)rec.x) * (1.0 / 254.0)));
+                                }
                             }
                             // staging row of token tl (0..63): 128 bytes = 8 chunks of 16, chunk q stored at
                             // q ^ ((tl >> 1) & 7) to spread the banks
@@ -490,10 +525,14 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                 }
             }
         };
-        if (cinterior)
-            epilogue(std::true_type{});
-        else
+        if constexpr (ZP) {
             epilogue(std::false_type{});
+        } else {
+            if (cinterior)
+                epilogue(std::true_type{});
+            else
+                epilogue(std::false_type{});
+        }
 
         if (!has_next) break;
         sbase = (eslot + 2) % NB;
@@ -515,7 +554,7 @@ static int compute_units()
     return cached[dev];
 }
 
-template <int WA, int WB>
+template <int WA, int WB, bool ZP>
 static hipError_t launch_cfg(GemmArgs& g, hipStream_t st)
 {
     constexpr int STAGE = (2 * WA + 2 * WB) * 2 * TILE_BYTES;
@@ -524,13 +563,13 @@ static hipError_t launch_cfg(GemmArgs& g, hipStream_t st)
     g.nQ = (g.RT + 2 * WB - 1) / (2 * WB);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB>,
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, ZP>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, shm);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int total = g.nP * g.nQ, ncu = compute_units();
-    gemm_prefill_kernel<WA, WB><<<total < ncu ? total : ncu, 256, shm, st>>>(g);
+    gemm_prefill_kernel<WA, WB, ZP><<<total < ncu ? total : ncu, 256, shm, st>>>(g);
     return hipGetLastError();
 }
 
@@ -558,9 +597,10 @@ int g_force_cfg = -1;  // test hook: tile shape override (-1 = automatic)
 hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                                const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
                                const unsigned short* Wf, int rows_are_slots, const int32_t* idx, int s, int h, int o,
-                               unsigned short* Out, int32_t* Cdbg, hipStream_t st)
+                               unsigned short* Out, int32_t* Cdbg, hipStream_t st, const ZpArgs* zp)
 {
     GemmArgs g;
+    g.zp = zp ? *zp : ZpArgs{nullptr, nullptr, nullptr};
     g.rows_are_slots = rows_are_slots;
     g.wrows = rows_are_slots ? opad_of(cap) : h;
     g.Wq = Wq; g.Xq = Xq;
@@ -572,11 +612,19 @@ hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const
     g.s = s; g.h = h; g.o = o;
     g.fast_ok = (o % 8 == 0) && al16(cw) && al16(cx) && al16(Wf) && al16(Xo) && al16(Out);
     const int c = g_force_cfg >= 0 ? g_force_cfg : pick_cfg(s, o);
+    if (zp) {
+        switch (c) {
+            case 1: return launch_cfg<3, 4, true>(g, st);
+            case 2: return launch_cfg<2, 4, true>(g, st);
+            case 3: return launch_cfg<2, 2, true>(g, st);
+            default: return launch_cfg<4, 4, true>(g, st);
+        }
+    }
     switch (c) {
-        case 1: return launch_cfg<3, 4>(g, st);
-        case 2: return launch_cfg<2, 4>(g, st);
-        case 3: return launch_cfg<2, 2>(g, st);
-        default: return launch_cfg<4, 4>(g, st);
+        case 1: return launch_cfg<3, 4, false>(g, st);
+        case 2: return launch_cfg<2, 4, false>(g, st);
+        case 3: return launch_cfg<2, 2, false>(g, st);
+        default: return launch_cfg<4, 4, false>(g, st);
     }
 }
 

@@ -1,0 +1,342 @@
+// Zeropoint (asymmetric) quantization, Section 2.1 Eq. 1-5, one set of constants
+// per row of X and per column of W (the "zeropoint vector-wise" rows of Table 1),
+// for the variant of the matmul that uses it in place of absmax quantization.
+//
+// For a vector with lo = min, hi = max, D = hi - lo:
+//   Eq. 1  nd = 254 / D, never rounded on its own
+//   Eq. 3  u(x) = round-half-even(nd x) = round-half-even(254 x / D)
+//   Eq. 2  zp = u(lo) + 127 (the printed "X min" read as nd min; the 127 recentres the stored
+//          byte into [-127, 127]); stored code = u(x) - zp, and Eq. 4's code + zp gives u(x) back
+// D = 0 (a constant vector): codes 0, zp 0.
+//
+// The constants of a vector travel as one 16-byte record (ZpConst): the fp16 bit patterns of lo
+// and hi, zp, and the sum of the vector's codes (the row / column sums that the unrolled product
+// of Eq. 5 needs).
+#include "common.h"
+
+namespace llmint8 {
+
+typedef unsigned short us8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+
+// Order-preserving key of a finite fp16 bit pattern: keys compare as unsigned integers the way
+// the values compare as numbers (-0 directly below +0).
+__device__ inline unsigned f16_key(unsigned b) { return (b & 0x8000u) ? (~b & 0xffffu) : (b | 0x8000u); }
+__device__ inline unsigned key_f16(unsigned k)
+{
+    const unsigned b = (k & 0x8000u) ? (k & 0x7fffu) : (~k & 0xffffu);
+    return (b & 0x7fffu) ? b : 0u;  // a zero is reported as +0
+}
+
+// u(x) for D > 0.  254 x and D are exact in double, the division is correctly rounded, and a
+// quotient that is not a tie lies at least 2^-50 (relative) from the nearest half-integer, so
+// rint() of the double quotient is the exact answer.  |u| <= 254 * 2^11.
+__device__ __forceinline__ int zp_u(unsigned short xb, double D)
+{
+    return (int)__builtin_rint(254.0 * (double)f16_bits_to_float(xb) / D);
+}
+
+__device__ inline int4 make_const(unsigned kmin, unsigned kmax)
+{
+    const unsigned lo = key_f16(kmin), hi = key_f16(kmax);
+    const double D = zp_range(lo | (hi << 16));
+    int4 r;
+    r.x = (int)(lo | (hi << 16));
+    r.y = D > 0.0 ? zp_u((unsigned short)lo, D) + 127 : 0;
+    r.z = 0;  // the sum of the codes is accumulated by the quantizer
+    r.w = 0;
+    return r;
+}
+
+// ---------------------------------------------------------------------------
+// Weights: column ranges over slabs of rows, constants, codes + column sums.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) zp_colrange_partial_kernel(const unsigned short* __restrict__ W, int h, int o,
+                                                                  unsigned short* __restrict__ pmin,
+                                                                  unsigned short* __restrict__ pmax, int rows_per_slab)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= o) return;
+    const int r0 = blockIdx.y * rows_per_slab, r1 = min(h, r0 + rows_per_slab);
+    unsigned kmin = 0xffffu, kmax = 0u;
+    for (int r = r0; r < r1; r++) {
+        const unsigned k = f16_key(W[(size_t)r * o + j]);
+        kmin = k < kmin ? k : kmin;
+        kmax = k > kmax ? k : kmax;
+    }
+    pmin[(size_t)blockIdx.y * o + j] = (unsigned short)kmin;
+    pmax[(size_t)blockIdx.y * o + j] = (unsigned short)kmax;
+}
+
+__global__ void __launch_bounds__(256) zp_colrange_final_kernel(const unsigned short* __restrict__ pmin,
+                                                                const unsigned short* __restrict__ pmax, int nslab,
+                                                                int o, int4* __restrict__ zc)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= o) return;
+    unsigned kmin = 0xffffu, kmax = 0u;
+    for (int sl = 0; sl < nslab; sl++) {
+        const unsigned a = pmin[(size_t)sl * o + j], b = pmax[(size_t)sl * o + j];
+        kmin = a < kmin ? a : kmin;
+        kmax = b > kmax ? b : kmax;
+    }
+    zc[j] = make_const(kmin, kmax);
+}
+
+// W_i8 in the tiled layout, as quantize_weight_kernel: one workgroup = 32 features x 256 output
+// columns, staged through LDS.  Also adds this slab's part of every column sum into the records.
+__global__ void __launch_bounds__(256) zp_quantize_weight_kernel(const unsigned short* __restrict__ W, int h, int o,
+                                                                 int4* __restrict__ zc, int8_t* __restrict__ Wq,
+                                                                 int KT, int JT)
+{
+    __shared__ __attribute__((aligned(16))) int8_t stage[8 * TILE_BYTES];
+    __shared__ int csum[256];
+    const int tid = threadIdx.x;
+    const int kt = blockIdx.y;
+    const int jt0 = blockIdx.x * 8;
+    const int cg = tid & 31, sub = tid >> 5;
+    const int j0 = jt0 * 32 + cg * 8;
+    csum[tid] = 0;
+    double D[8];
+    int z[8], part[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        D[e] = 0.0;
+        z[e] = 0;
+        part[e] = 0;
+        if (j0 + e < o) {
+            const int4 r = zc[j0 + e];
+            D[e] = zp_range((unsigned)r.x);
+            z[e] = r.y;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int kk = q * 8 + sub;
+        const int k = kt * 32 + kk;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            int qv = 0;  // padding rows and columns of the tiles stay zero
+            if (k < h && D[e] > 0.0) qv = zp_u(W[(size_t)k * o + j0 + e], D[e]) - z[e];
+            part[e] += qv;
+            const int jj = cg * 8 + e;
+            stage[(jj >> 5) * TILE_BYTES + tile_byte(jj & 31, kk)] = (int8_t)qv;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++)
+        if (part[e]) atomicAdd(&csum[cg * 8 + e], part[e]);
+    __syncthreads();
+    const int tile = tid >> 5;
+    if (jt0 + tile < JT) {
+        const u4* src = (const u4*)(stage + tid * 32);
+        u4* dst = (u4*)(Wq + ((size_t)(jt0 + tile) * KT + kt) * TILE_BYTES + (tid & 31) * 32);
+        dst[0] = src[0];
+        dst[1] = src[1];
+    }
+    const int j = jt0 * 32 + tid;
+    if (j < o && csum[tid]) atomicAdd(&zc[j].z, csum[tid]);
+}
+
+int zp_colrange_slabs(int h, int o)
+{
+    const int colblocks = (o + 255) / 256;
+    int n = (2048 + colblocks - 1) / colblocks;
+    const int maxslab = (h + 31) / 32;
+    if (n > maxslab) n = maxslab;
+    if (n > 64) n = 64;
+    return n < 1 ? 1 : n;
+}
+
+hipError_t launch_zp_quantize_weight(const void* W, int h, int o, int8_t* Wq, int4* zc, unsigned short* part,
+                                     hipStream_t st)
+{
+    const int nslab = zp_colrange_slabs(h, o);
+    const int rps = (h + nslab - 1) / nslab;
+    unsigned short* pmin = part;
+    unsigned short* pmax = part + (size_t)nslab * o;
+    zp_colrange_partial_kernel<<<dim3((o + 255) / 256, nslab), 256, 0, st>>>((const unsigned short*)W, h, o, pmin, pmax,
+                                                                            rps);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    zp_colrange_final_kernel<<<(o + 255) / 256, 256, 0, st>>>(pmin, pmax, nslab, o, zc);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int KT = k_tiles(h), JT = row_tiles(o);
+    zp_quantize_weight_kernel<<<dim3((JT + 7) / 8, KT), 256, 0, st>>>((const unsigned short*)W, h, o, zc, Wq, KT, JT);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Hidden states.  One workgroup per row: range over the non-outlier columns,
+// constants, and the gathered outlier columns Xo (as row_absmax_kernel).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) zp_row_range_kernel(const unsigned short* __restrict__ X, int s, int h,
+                                                           const int32_t* __restrict__ idx,
+                                                           const int32_t* __restrict__ count, int cap, int opad,
+                                                           int4* __restrict__ zc, unsigned short* __restrict__ Xo)
+{
+    extern __shared__ unsigned bitmap[];  // ceil(h / 32) words, then 8 words of reduction space
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int nw = (h + 31) / 32;
+    unsigned* red = bitmap + nw;
+    const int i = blockIdx.x;
+    const unsigned short* row = X + (size_t)i * h;
+    for (int q = tid; q < nw; q += 256) bitmap[q] = 0;
+    int cnt = *count;
+    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
+    __syncthreads();
+    for (int t = tid; t < cnt; t += 256) {
+        const unsigned j = (unsigned)idx[t];
+        if (j < (unsigned)h) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+    }
+    for (int t = tid; t < opad; t += 256) {
+        unsigned short v = 0;
+        if (t < cnt) {
+            const unsigned j = (unsigned)idx[t];
+            if (j < (unsigned)h) v = row[j];
+        }
+        Xo[(size_t)i * opad + t] = v;
+    }
+    __syncthreads();
+    unsigned kmin = 0xffffu, kmax = 0u;
+    for (int c = tid; c < h; c += 256)
+        if (!((bitmap[c >> 5] >> (c & 31)) & 1u)) {
+            const unsigned k = f16_key(row[c]);
+            kmin = k < kmin ? k : kmin;
+            kmax = k > kmax ? k : kmax;
+        }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const unsigned a = (unsigned)__shfl_xor((int)kmin, d), b = (unsigned)__shfl_xor((int)kmax, d);
+        kmin = a < kmin ? a : kmin;
+        kmax = b > kmax ? b : kmax;
+    }
+    if (lane == 0) {
+        red[w] = kmin;
+        red[4 + w] = kmax;
+    }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int q = 1; q < 4; q++) {
+            kmin = red[q] < kmin ? red[q] : kmin;
+            kmax = red[4 + q] > kmax ? red[4 + q] : kmax;
+        }
+        int4 r = {0, 0, 0, 0};       // no non-outlier column at all: an empty, all-zero vector
+        if (kmin <= kmax) r = make_const(kmin, kmax);
+        zc[i] = r;
+    }
+}
+
+// X_i8 in the tiled layout, as quantize_rows_kernel: one workgroup = 32 rows x 256 features.
+// Also adds this block's part of every row sum into the records.
+__global__ void __launch_bounds__(256) zp_quantize_rows_kernel(const unsigned short* __restrict__ X, int s, int h,
+                                                               const int32_t* __restrict__ idx,
+                                                               const int32_t* __restrict__ count, int cap,
+                                                               int4* __restrict__ zc, int8_t* __restrict__ Xq, int KT)
+{
+    __shared__ __attribute__((aligned(16))) int8_t stage[8 * TILE_BYTES];
+    __shared__ unsigned bitmap[8];
+    const int tid = threadIdx.x;
+    const int rt = blockIdx.x;
+    const int k0 = blockIdx.y * 256;
+    if (tid < 8) bitmap[tid] = 0;
+    int cnt = *count;
+    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
+    __syncthreads();
+    for (int t = tid; t < cnt; t += 256) {
+        const unsigned j = (unsigned)idx[t] - (unsigned)k0;
+        if (j < 256u) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+    }
+    __syncthreads();
+    const int kseg = (tid & 31) * 8;
+    const int k = k0 + kseg;
+    const unsigned bits = (bitmap[kseg >> 5] >> (kseg & 31)) & 0xffu;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int r = q * 8 + (tid >> 5);
+        const int i = rt * 32 + r;
+        double D = 0.0;
+        int z = 0;
+        if (i < s) {
+            const int4 rec = zc[i];
+            D = zp_range((unsigned)rec.x);
+            z = rec.y;
+        }
+        unsigned lo = 0, hi = 0;
+        int part = 0;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            int qv = 0;
+            if (D > 0.0 && k + e < h && !((bits >> e) & 1u)) qv = zp_u(X[(size_t)i * h + k + e], D) - z;
+            part += qv;
+            const unsigned byte = (unsigned)qv & 0xffu;
+            if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
+        }
+        u2 pk = {lo, hi};
+        *(u2*)(stage + (kseg >> 5) * TILE_BYTES + tile_byte(r, kseg & 31)) = pk;
+        // the 32 lanes that share row r (one half of a wave) add up their parts
+#pragma unroll
+        for (int d = 16; d >= 1; d >>= 1) part += __shfl_xor(part, d);
+        if ((tid & 31) == 0 && i < s && part) atomicAdd(&zc[i].z, part);
+    }
+    __syncthreads();
+    const int kt0 = k0 >> 5;
+#pragma unroll
+    for (int half = 0; half < 2; half++) {
+        const int off = half * 4096 + tid * 16;
+        if (kt0 + (off >> 10) < KT)
+            *(u4*)(Xq + ((size_t)rt * KT + kt0) * TILE_BYTES + off) = *(const u4*)(stage + off);
+    }
+}
+
+hipError_t launch_zp_quantize_rows(const void* X, int s, int h, const int32_t* idx, const int32_t* count, int cap,
+                                   int8_t* Xq, int4* zc, unsigned short* Xo, hipStream_t st)
+{
+    const int KT = k_tiles(h), RT = row_tiles(s);
+    const size_t shm = ((size_t)(h + 31) / 32 + 8) * sizeof(unsigned);
+    zp_row_range_kernel<<<s, 256, shm, st>>>((const unsigned short*)X, s, h, idx, count, cap, opad_of(cap), zc, Xo);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    zp_quantize_rows_kernel<<<dim3(RT, (KT * 32 + 255) / 256), 256, 0, st>>>((const unsigned short*)X, s, h, idx, count,
+                                                                            cap, zc, Xq, KT);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Per call, per output column: K[j] = sum_{k not in O} W_i8[k][j] + (h - |O|) zp_w[j], the factor of
+// zp_x[i] in the unrolled product of Eq. 5 (its last two terms), as a double.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) zp_kcol_kernel(const int8_t* __restrict__ Wq, const int4* __restrict__ zcw, int h,
+                                                      int o, int KT, const int32_t* __restrict__ idx,
+                                                      const int32_t* __restrict__ count, int cap,
+                                                      double* __restrict__ kcol)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= o) return;
+    int cnt = *count;
+    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
+    const int4 rec = zcw[j];
+    long long sum = rec.z;
+    int used = 0;
+    for (int t = 0; t < cnt; t++) {
+        const unsigned k = (unsigned)idx[t];
+        if (k < (unsigned)h) {
+            sum -= Wq[((size_t)(j >> 5) * KT + (k >> 5)) * TILE_BYTES + tile_byte(j & 31, (int)(k & 31))];
+            used++;
+        }
+    }
+    kcol[j] = (double)(sum + (long long)(h - used) * rec.y);
+}
+
+hipError_t launch_zp_kcol(const int8_t* Wq, const int4* zcw, int h, int o, const int32_t* idx, const int32_t* count,
+                          int cap, double* kcol, hipStream_t st)
+{
+    zp_kcol_kernel<<<(o + 255) / 256, 256, 0, st>>>(Wq, zcw, h, o, k_tiles(h), idx, count, cap, kcol);
+    return hipGetLastError();
+}
+
+}  // namespace llmint8

@@ -1,0 +1,157 @@
+"""HIP path vs CPU oracle for the zeropoint variant (Section 2.1, Eq. 1-5, per row of X and per
+column of W, with and without the decomposition of Section 3.2).  Ranges, zeropoints, codes, row and
+column sums and the plain int8 product bit for bit; outputs within 1e-3 of the largest output."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2208_07339_amd import workloads as wl
+from gpu_util import assert_out_close, bits
+
+pytestmark = pytest.mark.gpu
+
+INF = float("inf")
+
+
+def upload(X, W):
+    import torch
+    Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
+    Wd = torch.from_numpy(W.view(np.int16)).cuda().view(torch.float16)
+    return Xd, Wd
+
+
+def unpack(zc):
+    """[n, 4] int32 records -> lo bits, hi bits, zp, sum."""
+    zc = zc.cpu().numpy()
+    w0 = zc[:, 0].astype(np.int64) & 0xffffffff
+    assert not zc[:, 3].any()
+    return (w0 & 0xffff).astype(np.uint16), (w0 >> 16).astype(np.uint16), zc[:, 1], zc[:, 2]
+
+
+def zp_compare(X, W, alpha, cap=32):
+    import torch
+
+    import paper_2208_07339_amd as L
+    s, h = X.shape
+    o = W.shape[1]
+    ref = oracle.zp_linear(X, W, alpha)
+    assert len(ref["idx"]) <= cap
+    Xd, Wd = upload(X, W)
+    ws = L.Workspace.allocate(s, h, o, cap)
+    qw = L.zp_quantize_weight(Wd, ws)
+    lo, hi, zp, cs = unpack(qw.zc)
+    assert np.array_equal(lo, bits(ref["lo_w"])) and np.array_equal(hi, bits(ref["hi_w"]))
+    assert np.array_equal(zp, ref["zp_w"]) and np.array_equal(cs, ref["colsum"])
+    wq_host = L.export_weight(L.QuantizedWeight(qw.Wq, None, None, h, o)).cpu().numpy()
+    assert np.array_equal(wq_host, ref["Wq"])
+    # staged calls
+    outl = L.find_outliers(Xd, alpha, cap, ws)
+    rows = L.zp_quantize_rows(Xd, outl)
+    out, Cd = L.zp_matmul(rows, outl, qw, ws, want_c_i32=True)
+    torch.cuda.synchronize()
+    n = int(outl.count.item())
+    assert outl.idx[:n].cpu().numpy().tolist() == ref["idx"].tolist()
+    lo, hi, zp, rs = unpack(rows.zc)
+    assert np.array_equal(lo, bits(ref["lo_x"])) and np.array_equal(hi, bits(ref["hi_x"]))
+    assert np.array_equal(zp, ref["zp_x"]) and np.array_equal(rs, ref["rowsum"])
+    xq_host = L.export_rows(L.QuantizedRows(rows.Xq, None, None, s, h)).cpu().numpy()
+    assert np.array_equal(xq_host, ref["Xq"])
+    Xo = rows.Xo.cpu().numpy()
+    assert np.array_equal(bits(Xo[:, :n]), bits(X[:, ref["idx"]])) and not bits(Xo[:, n:]).any()
+    assert np.array_equal(Cd.cpu().numpy(), ref["C"])
+    assert_out_close(out.cpu().numpy(), ref["Out"])
+    # one call, into buffers holding junk, twice
+    outl2 = L.Outliers(torch.full((cap,), -7, dtype=torch.int32, device="cuda"),
+                       torch.full((1,), -7, dtype=torch.int32, device="cuda"),
+                       torch.full((1,), -7, dtype=torch.int32, device="cuda"), cap)
+    rows2 = L.ZpRows(torch.full((L.xq_bytes(s, h),), 99, dtype=torch.int8, device="cuda"),
+                     torch.full((s, 4), 12345, dtype=torch.int32, device="cuda"),
+                     torch.full((s, L.opad(cap)), 7.0, dtype=torch.float16, device="cuda"), s, h)
+    for _ in range(2):
+        out2 = L.zp_linear(Xd, qw, alpha, outl2, rows2, ws)
+    torch.cuda.synchronize()
+    assert int(outl2.count.item()) == n and int(outl2.status.item()) == 0
+    assert torch.equal(rows2.zc, rows.zc) and torch.equal(rows2.Xq, rows.Xq)
+    assert_out_close(out2.cpu().numpy(), ref["Out"])
+    return ref
+
+
+def one_sided(d, shift=0.0):
+    """The recipe's inputs made asymmetric: non-outlier entries clipped at -0.25 (a leaky ReLU-like
+    cut), optionally shifted; the planted outlier columns are kept."""
+    X = np.maximum(d["X"], np.float16(-0.25)) + np.float16(shift)
+    X[:, d["planted"]] = d["X"][:, d["planted"]]
+    return np.ascontiguousarray(X.astype(np.float16))
+
+
+SHAPES = [(8, 256, 512, 2), (16, 1024, 2048, 5), (13, 200, 61, 2), (32, 4160, 96, 6),   # weight-streaming path
+          (33, 64, 32, 1), (100, 300, 200, 3), (256, 1024, 512, 4), (333, 520, 260, 5)]  # tiled path
+
+
+@pytest.mark.parametrize("alpha", [6.0, INF])
+@pytest.mark.parametrize("s,h,o,ncol", SHAPES)
+def test_zeropoint_on_one_sided_inputs(s, h, o, ncol, alpha):
+    d = wl.make_custom(s, h, o, ncol, seed=5 * s + h)
+    ref = zp_compare(one_sided(d), d["W"], alpha)
+    if alpha == 6.0:
+        assert (ref["zp_x"] != 0).all()  # these rows are far from symmetric
+
+
+@pytest.mark.parametrize("s,h,o", [(16, 512, 256), (150, 384, 320)])
+def test_zeropoint_on_the_symmetric_recipe_and_a_shifted_one(s, h, o):
+    d = wl.make_custom(s, h, o, 3, seed=77)
+    zp_compare(d["X"], d["W"], 6.0)
+    zp_compare(one_sided(d, shift=2.5), np.ascontiguousarray(d["W"] + np.float16(0.03)), 6.0)  # large zeropoints
+
+
+def test_constant_and_zero_vectors():
+    d = wl.make_custom(40, 128, 64, 2, seed=3)
+    X, W = d["X"].copy(), d["W"].copy()
+    X[3] = 0
+    X[7] = np.float16(1.5)
+    W[:, 5] = 0
+    W[:, 9] = np.float16(-0.25)
+    ref = zp_compare(X, W, 6.0)
+    assert ref["zp_x"][3] == 0 and not ref["Xq"][7].any() and not ref["Wq"][:, 9].any()
+    zp_compare(np.zeros((5, 64), np.float16), np.zeros((64, 32), np.float16), 6.0)
+
+
+def test_prefill_13b_ffn_up_full_size():
+    """Full benchmark size: ranges, zeropoints, sums and both int8 tensors in full; accumulators and
+    outputs on random samples the oracle computes one by one."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    d = wl.make("ffn13b")
+    X, W = one_sided(d), d["W"]
+    s, h, o, cap = d["s"], d["h"], d["o"], 32
+    Xd, Wd = upload(X, W)
+    ws = L.Workspace.allocate(s, h, o, cap)
+    qw = L.zp_quantize_weight(Wd, ws)
+    outl = L.Outliers(torch.empty(cap, dtype=torch.int32, device="cuda"),
+                      torch.empty(1, dtype=torch.int32, device="cuda"),
+                      torch.empty(1, dtype=torch.int32, device="cuda"), cap)
+    rows = L.ZpRows(torch.empty(L.xq_bytes(s, h), dtype=torch.int8, device="cuda"),
+                    torch.empty((s, 4), dtype=torch.int32, device="cuda"),
+                    torch.empty((s, L.opad(cap)), dtype=torch.float16, device="cuda"), s, h)
+    out = L.zp_linear(Xd, qw, 6.0, outl, rows, ws)
+    _, Cd = L.zp_matmul(rows, outl, qw, ws, want_c_i32=True)
+    torch.cuda.synchronize()
+    idx = oracle.find_outliers(X, 6.0)
+    n = int(outl.count.item())
+    assert outl.idx[:n].cpu().numpy().tolist() == idx.tolist()
+    w = oracle.zp_quantize_weight(W)
+    lo, hi, zp, cs = unpack(qw.zc)
+    assert np.array_equal(lo, bits(w["lo"])) and np.array_equal(hi, bits(w["hi"]))
+    assert np.array_equal(zp, w["zp"]) and np.array_equal(cs, w["colsum"])
+    assert np.array_equal(L.export_weight(L.QuantizedWeight(qw.Wq, None, None, h, o)).cpu().numpy(), w["Wq"])
+    x = oracle.zp_quantize_rows(X, idx)
+    lo, hi, zp, rs = unpack(rows.zc)
+    assert np.array_equal(lo, bits(x["lo"])) and np.array_equal(hi, bits(x["hi"]))
+    assert np.array_equal(zp, x["zp"]) and np.array_equal(rs, x["rowsum"])
+    assert np.array_equal(L.export_rows(L.QuantizedRows(rows.Xq, None, None, s, h)).cpu().numpy(), x["Xq"])
+    rng = np.random.default_rng(78)
+    ri, ci = rng.integers(0, s, 1200), rng.integers(0, o, 1200)
+    Cs, Os = oracle.zp_sampled(X, W, idx, ri, ci)
+    assert np.array_equal(Cd.cpu().numpy()[ri, ci], Cs)
+    assert_out_close(out.cpu().numpy()[ri, ci], Os, float(np.abs(Os.astype(np.float64)).max()))
