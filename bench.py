@@ -107,6 +107,39 @@ def run_workload(name, steps, warmup, copies=1, int8_rows=False, granularity="ve
                 ms_prepass=ms_pre, ms_matmul=ms_mm, weight_quantize_ms=t_wq * 1e3, inputs=d)
 
 
+def run_zeropoint(name, steps, warmup, alpha):
+    """The zeropoint variant (Eq. 1-5) on the same inputs: whole call, and its matmul part alone."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    from paper_2208_07339_amd import workloads as wl
+
+    d = wl.make(name)
+    s, h, o = d["s"], d["h"], d["o"]
+    Xd, Wd = to_dev(d["X"]), to_dev(d["W"])
+    ws = L.Workspace.allocate(s, h, o, CAP)
+    t0 = time.perf_counter()
+    qw = L.zp_quantize_weight(Wd, ws)
+    torch.cuda.synchronize()
+    t_wq = time.perf_counter() - t0
+    outl = L.find_outliers(Xd, alpha, CAP, ws)
+    rows = L.zp_quantize_rows(Xd, outl)
+    out = torch.empty((s, o), dtype=torch.float16, device="cuda")
+    torch.cuda.synchronize()
+    times = []
+    for fn in (lambda: L.zp_linear(Xd, qw, alpha, outl, rows, ws, out), lambda: L.zp_matmul(rows, outl, qw, ws, out)):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        times.append((time.perf_counter() - t0) * 1e3 / steps)
+    return dict(name=name, s=s, h=h, o=o, n_out=int(outl.count.item()), planted=len(d["planted"]), ms_step=times[0],
+                ms_matmul_calls=times[1], weight_quantize_ms=t_wq * 1e3)
+
+
 def cpu_baseline(res, target_seconds=12.0):
     """The CPU oracle, as it stands, on a bounded sample: the per-call steps (outlier scan, row
     quantization, integer product, dequantization + outlier product) on the first r rows of X
@@ -159,6 +192,9 @@ def main():
                          "baselines of Table 1 (measured separately, not the headline)")
     ap.add_argument("--alpha", type=float, default=6.0,
                     help="outlier threshold; inf switches the decomposition off (the baselines without it)")
+    ap.add_argument("--quantizer", default="absmax", choices=["absmax", "zeropoint"],
+                    help="zeropoint: the asymmetric quantization of Eq. 1-5 per row of X / column of W (Table 1's "
+                         "zeropoint rows; measured separately, not the headline)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three device-to-device copies of 256 MiB first: under rocprofv3 --pmc their "
                          "FETCH_SIZE / WRITE_SIZE readings calibrate the counters (paper_2208_07339_amd/pmc_summary.py)")
@@ -178,6 +214,23 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if a.quantizer == "zeropoint":
+        r = run_zeropoint(a.workload, a.steps, a.warmup, a.alpha)
+        ops = 2.0 * r["s"] * r["h"] * r["o"]
+        nbytes = algorithmic_bytes_decode(r["s"], r["h"], r["o"], r["n_out"])
+        dec = a.workload == "decode"
+        print(json.dumps({
+            "metric": "zeropoint variant of the matmul per call (outlier scan + zeropoint row quantize + int8 GEMM "
+                      "with the Eq. 5 corrections in the epilogue), 1 MI355X",
+            "value": nbytes / (r["ms_step"] * 1e-3) / 1e9 if dec else ops / (r["ms_step"] * 1e-3) / 1e12,
+            "unit": "GB/s" if dec else "TOPS", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+            "ms_per_step": r["ms_step"], "ms_matmul_calls": r["ms_matmul_calls"],
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+            "config": {"workload": a.workload, "s": r["s"], "h": r["h"], "o": r["o"],
+                       "alpha": a.alpha if np.isfinite(a.alpha) else "inf", "quantizer": "zeropoint",
+                       "outlier_columns_found": r["n_out"]},
+            "weight_quantize_ms_once": r["weight_quantize_ms"]}))
+        return
     i8 = a.outlier_rows == "int8"
     res = run_workload(a.workload, a.steps, a.warmup, copies=2 if a.workload == "decode" else 1, int8_rows=i8,
                        granularity=a.granularity, alpha=a.alpha)

@@ -24,7 +24,7 @@ inline size_t weight_ws(int h, int o) { return align_up((size_t)colmax_slabs(h, 
 inline size_t rows_ws(int o, int cap) { return align_up((size_t)opad_of(cap) * o * 2, 256); }
 // zeropoint variant: column minima and maxima of the weight scan; per call the column factors K [o] doubles
 inline size_t zp_weight_ws(int h, int o) { return align_up((size_t)2 * zp_colrange_slabs(h, o) * o * 2, 256); }
-inline size_t kcol_ws(int o) { return align_up((size_t)o * 8, 256); }
+inline size_t kcol_ws(int o) { return (size_t)3 * zp_col_pitch(o) * 8; }
 inline size_t scan_ws(int s, int h, int o, int cap)
 {
     const size_t a = outlier_ws(s, h, cap), b = weight_ws(h, o), c = zp_weight_ws(h, o);
@@ -314,7 +314,7 @@ int llmint8_zp_matmul(const int8_t* Xq, const int32_t* zc_x, const void* Xo_f16,
     double* kcol = (double*)((char*)ws_base(ws) + scan_ws(s, h, o, cap) + rows_ws(o, cap));
     hipError_t e = launch_zp_kcol(Wq, (const int4*)zc_w, h, o, idx, count, cap, kcol, st);
     if (e != hipSuccess) return hip_status(e);
-    const ZpArgs zp = {(const int4*)zc_x, (const int4*)zc_w, kcol};
+    const ZpArgs zp = {(const int4*)zc_x, kcol, zp_col_pitch(o)};
     if (s <= 32)
         e = launch_gemm_decode(Xq, nullptr, (const unsigned short*)Xo_f16, count, cap, Wq, nullptr,
                                (const unsigned short*)W_f16, 0, idx, s, h, o, (unsigned short*)Out_f16, C_i32_debug,

@@ -118,14 +118,17 @@ hipError_t launch_zp_quantize_weight(const void* W, int h, int o, int8_t* Wq, in
                                      hipStream_t st);
 hipError_t launch_zp_quantize_rows(const void* X, int s, int h, const int32_t* idx, const int32_t* count, int cap,
                                    int8_t* Xq, int4* zc, unsigned short* Xo, hipStream_t st);
+// colc: three planes of zp_col_pitch(o) doubles (see zp_kcol_kernel).  The pitch covers every column a
+// tile grid can touch (tiles are at most 256 columns wide), so the epilogues read it unguarded.
+__host__ __device__ inline int zp_col_pitch(int o) { return ((o + 255) & ~255) + 256; }
 hipError_t launch_zp_kcol(const int8_t* Wq, const int4* zcw, int h, int o, const int32_t* idx, const int32_t* count,
-                          int cap, double* kcol, hipStream_t st);
+                          int cap, double* colc, hipStream_t st);
 // What the GEMM epilogues need in place of c_x / c_w: T = C + zp_w[j] rowsum[i] + zp_x[i] K[j] (Eq. 5),
-// Out = T D_x[i] D_w[j] / 254^2 + outlier product.  All NULL: absmax constants.
+// Out = T D_x[i] D_w[j] / 254^2 + outlier product.  zcx NULL: absmax constants.
 struct ZpArgs {
-    const int4* zcx;     // [s]
-    const int4* zcw;     // [o]
-    const double* kcol;  // [o] from launch_zp_kcol
+    const int4* zcx;     // [s] records of the rows of X
+    const double* colc;  // per-column factors from launch_zp_kcol
+    int pitch;           // zp_col_pitch(o)
 };
 
 // Wf: the original fp16 weights [h x o] (rows_are_slots = 0: outlier slot t uses row idx[t]), or the

@@ -48,16 +48,15 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     float cwj[NJ], sxi[4];
     unsigned wo[NJ][DSLOTS / 2];  // fp16 pairs: slots 2q (low half) and 2q+1 of this thread's columns
     uint4 xo[4][DSLOTS / 8];      // slots 0..15 of this thread's tokens (Xo holds zeros past |O|)
-    double zsb[ZP ? NJ : 1], zK[ZP ? NJ : 1], zsa[ZP ? 4 : 1];  // D_w / 254, K, D_x / 254
-    int zzb[ZP ? NJ : 1], zza[ZP ? 4 : 1], zrs[ZP ? 4 : 1];       // zp_w, zp_x, row sums of the codes
+    double zp_[ZP ? NJ : 1], zq_[ZP ? NJ : 1], zr_[ZP ? NJ : 1];  // column factors p, q, r of zp_kcol_kernel
+    double zsa[ZP ? 4 : 1], zza[ZP ? 4 : 1], zrs[ZP ? 4 : 1];     // D_x / 254, zp_x, row sums of the codes
 #pragma unroll
     for (int n = 0; n < NJ; n++) {
         const int j = (jt0 + n) * 32 + jj;
         if constexpr (ZP) {
-            const int4 r = (j < o) ? zp.zcw[j] : make_int4(0, 0, 0, 0);
-            zsb[n] = zp_range((unsigned)r.x) * (1.0 / 254.0);
-            zzb[n] = r.y;
-            zK[n] = (j < o) ? zp.kcol[j] : 0.0;
+            zp_[n] = zp.colc[j];  // planes are padded to a multiple of 256 columns
+            zq_[n] = zp.colc[(size_t)zp.pitch + j];
+            zr_[n] = zp.colc[2 * (size_t)zp.pitch + j];
         } else {
             cwj[n] = (j < o) ? f16_bits_to_float(cw[j]) : 0.0f;
         }
@@ -68,8 +67,8 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
         if constexpr (ZP) {
             const int4 r = (i < s) ? zp.zcx[i] : make_int4(0, 0, 0, 0);
             zsa[m] = zp_range((unsigned)r.x) * (1.0 / 254.0);
-            zza[m] = r.y;
-            zrs[m] = r.z;
+            zza[m] = (double)r.y;
+            zrs[m] = (double)r.z;
         } else {
             sxi[m] = (i < s) ? f16_bits_to_float(cx[i]) * (1.0f / 16129.0f) : 0.0f;
         }
@@ -183,8 +182,8 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
             // Eq. 7 dequantization, then the outlier product of Eq. 8 accumulated in fp32
             float d;
             if constexpr (ZP) {
-                const double T = (double)c + (double)zzb[n] * (double)zrs[m] + (double)zza[m] * zK[n];  // Eq. 5
-                d = (float)(T * zsa[m] * zsb[n]);
+                // Eq. 5 over nd_w: C p + rowsum q + zp_x r, then the division by nd_x
+                d = (float)(zsa[m] * __builtin_fma((double)c, zp_[n], __builtin_fma(zrs[m], zq_[n], zza[m] * zr_[n])));
             } else {
                 d = (float)c * sxi[m] * cwj[n];
             }
@@ -216,7 +215,7 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
 {
     const int KT = k_tiles(h), JT = row_tiles(o);
     const int wrows = rows_are_slots ? opad_of(cap) : h;
-    const ZpArgs none = {nullptr, nullptr, nullptr};
+    const ZpArgs none = {nullptr, nullptr, 0};
     if (zp) {
         gemm_decode_kernel<2, 4, true><<<(JT + 1) / 2, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows,
                                                                     idx, Xo, count, cap, opad_of(cap), (_Float16*)Out,

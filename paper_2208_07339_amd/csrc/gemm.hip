@@ -377,8 +377,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                     }
             }
             float sx[WB];      // c_x / 127^2 of this lane's tokens (Eq. 7: S = c_x (x) c_w / 127^2)
-            double zsa[ZP ? WB : 1];             // zeropoint: D_x / 254,
-            int zza[ZP ? WB : 1], zrs[ZP ? WB : 1];  // zp_x and the row sum of the codes
+            double zsa[ZP ? WB : 1], zza[ZP ? WB : 1], zrs[ZP ? WB : 1];  // zeropoint: D_x / 254, zp_x, row sum of the codes
             v8h xb[WB][2];     // MFMA "B" operand of the outlier product: slots 8*gl .. +7 (+16) of this lane's tokens
 #pragma unroll
             for (int b = 0; b < WB; b++) {
@@ -393,8 +392,8 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                     if constexpr (ZP) {
                         const int4 rec = (i < s) ? g.zp.zcx[i] : make_int4(0, 0, 0, 0);
                         zsa[b] = zp_range((unsigned)rec.x) * (1.0 / 254.0);
-                        zza[b] = rec.y;
-                        zrs[b] = rec.z;
+                        zza[b] = (double)rec.y;
+                        zrs[b] = (double)rec.z;
                     } else {
                         sx[b] = (i < s) ? f16_bits_to_float(g.cx[i]) * (1.0f / 16129.0f) : 0.0f;
                     }
@@ -478,16 +477,15 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                                     d[r] = ZP ? 0.0f : (float)acc[a][b][r] * sx[b] * cwv[aa][r];
                             }
                             if constexpr (ZP) {
-                                // Eq. 5: T = C + zp_w rowsum + zp_x K, then the division by nd_x nd_w; the
-                                // column constants are fetched here, one MFMA tile at a time
+                                // Eq. 5 over nd_w: C p + rowsum q + zp_x r with the column factors of
+                                // zp_kcol_kernel (planes padded with zeros: no guards), then the division by nd_x
 #pragma unroll
                                 for (int r = 0; r < 16; r++) {
                                     const int j = J0 + a * 32 + 8 * (r >> 2) + 4 * gl + (r & 3);
-                                    const int4 rec = (j < o) ? g.zp.zcw[j] : make_int4(0, 0, 0, 0);
-                                    const double K = (j < o) ? g.zp.kcol[j] : 0.0;
-                                    const double T = (double)acc[a][b][r] + (double)rec.y * (double)zrs[b] +
-                                                     (double)zza[b] * K;
-                                    d[r] += (float)(T * zsa[b] * (zp_range((unsigned)rec.x) * (1.0 / 254.0)));
+                                    const double cp = g.zp.colc[j], cq = g.zp.colc[(size_t)g.zp.pitch + j],
+                                                 cr = g.zp.colc[2 * (size_t)g.zp.pitch + j];
+                                    d[r] += (float)(zsa[b] * __builtin_fma((double)acc[a][b][r], cp,
+                                                                           __builtin_fma(zrs[b], cq, zza[b] * cr)));
                                 }
                             }
                             // staging row of token tl (0..63): 128 bytes = 8 chunks of 16, chunk q stored at
@@ -600,7 +598,7 @@ hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const
                                unsigned short* Out, int32_t* Cdbg, hipStream_t st, const ZpArgs* zp)
 {
     GemmArgs g;
-    g.zp = zp ? *zp : ZpArgs{nullptr, nullptr, nullptr};
+    g.zp = zp ? *zp : ZpArgs{nullptr, nullptr, 0};
     g.rows_are_slots = rows_are_slots;
     g.wrows = rows_are_slots ? opad_of(cap) : h;
     g.Wq = Wq; g.Xq = Xq;

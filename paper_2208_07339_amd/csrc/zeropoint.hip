@@ -307,35 +307,48 @@ hipError_t launch_zp_quantize_rows(const void* X, int s, int h, const int32_t* i
 }
 
 // ---------------------------------------------------------------------------
-// Per call, per output column: K[j] = sum_{k not in O} W_i8[k][j] + (h - |O|) zp_w[j], the factor of
-// zp_x[i] in the unrolled product of Eq. 5 (its last two terms), as a double.
+// Per call, per output column, what the GEMM epilogues multiply with (three planes of `pitch` doubles,
+// zero for j >= o so that the epilogues need no guards):
+//   plane 0  p[j] = D_w[j] / 254                       (1 / nd_w)
+//   plane 1  q[j] = zp_w[j] * p[j]
+//   plane 2  r[j] = K[j] * p[j],  K[j] = sum_{k not in O} W_i8[k][j] + (h - |O|) zp_w[j]
+// so that T / nd_w of Eq. 5 is  C p + rowsum q + zp_x r.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) zp_kcol_kernel(const int8_t* __restrict__ Wq, const int4* __restrict__ zcw, int h,
                                                       int o, int KT, const int32_t* __restrict__ idx,
-                                                      const int32_t* __restrict__ count, int cap,
-                                                      double* __restrict__ kcol)
+                                                      const int32_t* __restrict__ count, int cap, int pitch,
+                                                      double* __restrict__ colc)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= o) return;
-    int cnt = *count;
-    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
-    const int4 rec = zcw[j];
-    long long sum = rec.z;
-    int used = 0;
-    for (int t = 0; t < cnt; t++) {
-        const unsigned k = (unsigned)idx[t];
-        if (k < (unsigned)h) {
-            sum -= Wq[((size_t)(j >> 5) * KT + (k >> 5)) * TILE_BYTES + tile_byte(j & 31, (int)(k & 31))];
-            used++;
+    if (j >= pitch) return;
+    double p = 0.0, q = 0.0, r = 0.0;
+    if (j < o) {
+        int cnt = *count;
+        cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
+        const int4 rec = zcw[j];
+        long long sum = rec.z;
+        int used = 0;
+        for (int t = 0; t < cnt; t++) {
+            const unsigned k = (unsigned)idx[t];
+            if (k < (unsigned)h) {
+                sum -= Wq[((size_t)(j >> 5) * KT + (k >> 5)) * TILE_BYTES + tile_byte(j & 31, (int)(k & 31))];
+                used++;
+            }
         }
+        p = zp_range((unsigned)rec.x) * (1.0 / 254.0);
+        q = (double)rec.y * p;
+        r = (double)(sum + (long long)(h - used) * rec.y) * p;
     }
-    kcol[j] = (double)(sum + (long long)(h - used) * rec.y);
+    colc[j] = p;
+    colc[(size_t)pitch + j] = q;
+    colc[2 * (size_t)pitch + j] = r;
 }
 
 hipError_t launch_zp_kcol(const int8_t* Wq, const int4* zcw, int h, int o, const int32_t* idx, const int32_t* count,
-                          int cap, double* kcol, hipStream_t st)
+                          int cap, double* colc, hipStream_t st)
 {
-    zp_kcol_kernel<<<(o + 255) / 256, 256, 0, st>>>(Wq, zcw, h, o, k_tiles(h), idx, count, cap, kcol);
+    const int pitch = zp_col_pitch(o);
+    zp_kcol_kernel<<<pitch / 256, 256, 0, st>>>(Wq, zcw, h, o, k_tiles(h), idx, count, cap, pitch, colc);
     return hipGetLastError();
 }
 
