@@ -401,6 +401,20 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                     xb[b][1] = cnt > 16 ? load_x_mem(i, 16) : (v8h)(0);
                 }
             }
+            // zeropoint: this wave's 32*WA columns of the three factor planes, copied once per tile into a
+            // wave-private piece of the epilogue-stage slots (they hold nothing such tiles need, and are
+            // not refilled before every wave has passed the barrier at the top of the next tile)
+            double* ZC = (double*)(lds + eslot * STAGE) + w * (3 * 32 * WA);
+            if constexpr (ZP) {
+#pragma unroll
+                for (int q = 0; q < 3; q++)
+                    for (int c = lane_e; c < 32 * WA; c += 64)
+                        ZC[q * 32 * WA + c] = g.zp.colc[(size_t)q * g.zp.pitch + J0 + c];
+                // read back by other lanes of the same wave only: LDS serves a wave's requests in order,
+                // the compiler just must not move the reads up
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_wave_barrier();
+            }
             int unit = 0;
 #pragma unroll
             for (int a0 = 0; a0 < WA; a0 += 2) {
@@ -481,9 +495,8 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                                 // zp_kcol_kernel (planes padded with zeros: no guards), then the division by nd_x
 #pragma unroll
                                 for (int r = 0; r < 16; r++) {
-                                    const int j = J0 + a * 32 + 8 * (r >> 2) + 4 * gl + (r & 3);
-                                    const double cp = g.zp.colc[j], cq = g.zp.colc[(size_t)g.zp.pitch + j],
-                                                 cr = g.zp.colc[2 * (size_t)g.zp.pitch + j];
+                                    const int c = a * 32 + 8 * (r >> 2) + 4 * gl + (r & 3);
+                                    const double cp = ZC[c], cq = ZC[32 * WA + c], cr = ZC[2 * 32 * WA + c];
                                     d[r] += (float)(zsa[b] * __builtin_fma((double)acc[a][b][r], cp,
                                                                            __builtin_fma(zrs[b], cq, zza[b] * cr)));
                                 }
