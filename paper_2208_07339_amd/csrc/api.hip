@@ -15,10 +15,10 @@ inline void* ws_base(void* ws) { return (void*)align_up((uintptr_t)ws, 256); }
 
 // outlier scan: list scratch first, then the slab maxima
 inline size_t scratch_ws(int h, int cap) { return align_up(outlier_lists_bytes(h, cap), 256); }
-inline size_t outlier_ws(int s, int h, int cap)
-{
-    return scratch_ws(h, cap) + align_up((size_t)colmax_slabs(s, h) * h * 2, 256);
-}
+inline size_t slab_ws(int s, int h) { return align_up((size_t)colmax_slabs(s, h) * h * 2, 256); }
+// partial row maxima of the fused column / row scan: [ceil(h / 512)][s] fp16 bits
+inline size_t rowpart_ws(int s, int h) { return align_up((size_t)((h + 511) / 512) * s * 2, 256); }
+inline size_t outlier_ws(int s, int h, int cap) { return scratch_ws(h, cap) + slab_ws(s, h) + rowpart_ws(s, h); }
 inline size_t weight_ws(int h, int o) { return align_up((size_t)colmax_slabs(h, o) * o * 2, 256); }
 // rebuilt outlier rows of W (used when no fp16 weights are given): [opad x o] fp16, behind everything else
 inline size_t rows_ws(int o, int cap) { return align_up((size_t)opad_of(cap) * o * 2, 256); }
@@ -226,15 +226,30 @@ static int linear_impl(const void* X_f16, int s, int h, float alpha, int granula
         if (std::isinf(alpha) && alpha > 0.0f) {
             // no decomposition (the baselines of Table 1 without it): O is empty, X need not be scanned
             e = launch_clear_lists(L, h, st);
+            if (e == hipSuccess)
+                e = launch_quantize_rows_lists(X_f16, s, h, L, idx, count, status, cap, Xq, (unsigned short*)cx_f16,
+                                               (unsigned short*)Xo_f16, shared_cx, st);
         } else {
             unsigned short* part = (unsigned short*)(base + scratch_ws(h, cap));
             const int nslab = colmax_slabs(s, h);
-            e = launch_colmax_partial(X_f16, s, h, part, nslab, st);
-            if (e == hipSuccess) e = launch_outlier_lists(part, nslab, h, threshold_bits(alpha), L, cap, st);
+            const unsigned thr = threshold_bits(alpha);
+            if (!shared_cx && h % 8 == 0 && !misaligned(X_f16, 16)) {
+                // X is read twice instead of three times: the column scan leaves partial row maxima, from which
+                // a small kernel gets the row constants once the outlier columns are known
+                unsigned short* rowpart = (unsigned short*)(base + scratch_ws(h, cap) + slab_ws(s, h));
+                e = launch_colmax_rowmax(X_f16, s, h, part, nslab, rowpart, thr, st);
+                if (e == hipSuccess) e = launch_outlier_lists(part, nslab, h, thr, L, cap, st);
+                if (e == hipSuccess)
+                    e = launch_quantize_rows_rowpart(X_f16, s, h, L, thr, rowpart, idx, count, status, cap, Xq,
+                                                     (unsigned short*)cx_f16, (unsigned short*)Xo_f16, st);
+            } else {
+                e = launch_colmax_partial(X_f16, s, h, part, nslab, st);
+                if (e == hipSuccess) e = launch_outlier_lists(part, nslab, h, thr, L, cap, st);
+                if (e == hipSuccess)
+                    e = launch_quantize_rows_lists(X_f16, s, h, L, idx, count, status, cap, Xq,
+                                                   (unsigned short*)cx_f16, (unsigned short*)Xo_f16, shared_cx, st);
+            }
         }
-        if (e == hipSuccess)
-            e = launch_quantize_rows_lists(X_f16, s, h, L, idx, count, status, cap, Xq, (unsigned short*)cx_f16,
-                                           (unsigned short*)Xo_f16, shared_cx, st);
     }
     if (e == hipSuccess && ev_before) e = hipEventRecord(ev_before, st);
     if (e != hipSuccess) return hip_status(e);

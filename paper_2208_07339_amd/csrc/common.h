@@ -98,6 +98,13 @@ hipError_t launch_spread_max(unsigned short* c, int n, hipStream_t st);
 hipError_t launch_quantize_rows_lists(const void* X, int s, int h, OutlierLists L, int32_t* idx, int32_t* count,
                                       int32_t* status, int cap, int8_t* Xq, unsigned short* cx, unsigned short* Xo,
                                       int shared_cx, hipStream_t st);
+// column scan of X that also leaves rowpart[ceil(h / 512)][s], the partial row maxima below the threshold
+// (needs h % 8 == 0 and 16-byte aligned X, part), and the row constants + codes + gathered columns from them
+hipError_t launch_colmax_rowmax(const void* X, int s, int h, unsigned short* part, int nslab, unsigned short* rowpart,
+                                unsigned thr, hipStream_t st);
+hipError_t launch_quantize_rows_rowpart(const void* X, int s, int h, OutlierLists L, unsigned thr,
+                                        const unsigned short* rowpart, int32_t* idx, int32_t* count, int32_t* status,
+                                        int cap, int8_t* Xq, unsigned short* cx, unsigned short* Xo, hipStream_t st);
 // whole pre-pass of a short X (s <= 32): outlier scan, row constants, codes, gathered columns
 hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
                                 int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,

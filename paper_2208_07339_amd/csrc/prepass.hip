@@ -102,6 +102,86 @@ hipError_t launch_colmax_partial(const void* M, int rows, int cols, unsigned sho
 }
 
 // ---------------------------------------------------------------------------
+// The same column scan for X (vector path only) that also prepares the row
+// constants: rowpart[colblock][row] = largest magnitude BELOW the threshold
+// among the row's entries in this workgroup's 512 columns.  Entries of
+// non-outlier columns are all below the threshold, so the maximum of a row's
+// partials is its constant c_x unless that maximum sits in an outlier column
+// (row_const_kernel checks this once the outlier columns are known).
+// ---------------------------------------------------------------------------
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ unsigned short hmax8(us8 v)
+{
+    us2 a = __builtin_elementwise_max(__builtin_elementwise_max(v.s01, v.s23), __builtin_elementwise_max(v.s45, v.s67));
+    return a.x > a.y ? a.x : a.y;
+}
+
+__global__ void __launch_bounds__(256) colmax_rowmax_kernel(const unsigned short* __restrict__ M, int rows, int cols,
+                                                            unsigned short* __restrict__ part,
+                                                            unsigned short* __restrict__ rowpart, int rows_per_slab,
+                                                            unsigned thr)
+{
+    __shared__ us8 red[4][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int c0 = blockIdx.x * 512 + lane * 8;
+    const int r0 = blockIdx.y * rows_per_slab;
+    const int r1 = min(rows, r0 + rows_per_slab);
+    const bool in = c0 < cols;
+    const unsigned short* p = M + (size_t)(in ? c0 : 0);
+    const us8 thrv = (us8)((unsigned short)thr);
+    us8 m = (us8)(0);
+    for (int r = r0 + w; r < r1; r += 16) {
+        us8 v[4];
+        unsigned short x[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            v[u] = (us8)(0);
+            if (in && r + 4 * u < r1) v[u] = *(const us8*)(p + (size_t)(r + 4 * u) * cols);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            v[u] &= (unsigned short)0x7fff;
+            m = __builtin_elementwise_max(m, v[u]);
+            const us8 below = v[u] & __builtin_convertvector(v[u] < thrv, us8);  // lanes that reach the threshold drop out
+            x[u] = hmax8(below);
+        }
+        // two rows per register through the cross-lane reduction
+        us2 a = {x[0], x[1]}, b = {x[2], x[3]};
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const us2 ta = __builtin_bit_cast(us2, __shfl_xor(__builtin_bit_cast(int, a), d));
+            const us2 tb = __builtin_bit_cast(us2, __shfl_xor(__builtin_bit_cast(int, b), d));
+            a = __builtin_elementwise_max(a, ta);
+            b = __builtin_elementwise_max(b, tb);
+        }
+        if (lane == 0) {
+            unsigned short* o = rowpart + (size_t)blockIdx.x * rows;
+            if (r < r1) o[r] = a.x;
+            if (r + 4 < r1) o[r + 4] = a.y;
+            if (r + 8 < r1) o[r + 8] = b.x;
+            if (r + 12 < r1) o[r + 12] = b.y;
+        }
+    }
+    red[w][lane] = m;
+    __syncthreads();
+    if (w == 0 && in) {
+        m = __builtin_elementwise_max(__builtin_elementwise_max(red[0][lane], red[1][lane]),
+                                      __builtin_elementwise_max(red[2][lane], red[3][lane]));
+        *(us8*)(part + (size_t)blockIdx.y * cols + c0) = m;
+    }
+}
+
+hipError_t launch_colmax_rowmax(const void* X, int s, int h, unsigned short* part, int nslab, unsigned short* rowpart,
+                                unsigned thr, hipStream_t st)
+{
+    const int rps = (s + nslab - 1) / nslab;
+    dim3 grid((h + 511) / 512, nslab);
+    colmax_rowmax_kernel<<<grid, 256, 0, st>>>((const unsigned short*)X, s, h, part, rowpart, rps, thr);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Outlier column lists.  The scan kernels cut the h columns into runs of 256;
 // run l gets the list cand[l][0 .. capc) of its columns whose maximum reaches
 // the threshold, ascending, and count[l] = how many there are (capc =
@@ -711,6 +791,147 @@ __global__ void __launch_bounds__(256) row_absmax_kernel(const unsigned short* _
 }
 
 // ---------------------------------------------------------------------------
+// Row constants from the partial row maxima of colmax_rowmax_kernel, one wave
+// per row; also the gathered outlier columns Xo and (workgroup 0) idx, count,
+// status, as row_absmax_kernel<true>.  With m1 = the largest below-threshold
+// magnitude of the row and mo = the largest such magnitude inside the outlier
+// columns: mo < m1 means m1 sits in a non-outlier column, so c_x = m1.
+// Otherwise (rare), and whenever more columns qualify than cap allows (then
+// the columns beyond cap count as ordinary ones and their large entries
+// belong to c_x), the workgroup scans that row again without the outlier
+// columns.  Needs h % 8 == 0 and a 16-byte aligned X.
+// ---------------------------------------------------------------------------
+constexpr int RC_SLOTS = 256;  // outlier columns kept in LDS; more: every row takes the slow path
+
+__global__ void __launch_bounds__(256) row_const_kernel(const unsigned short* __restrict__ X, int s, int h,
+                                                        OutlierLists L, int capc, int cap, int opad, unsigned thr,
+                                                        const unsigned short* __restrict__ rowpart, int ncb,
+                                                        int32_t* __restrict__ idx, int32_t* __restrict__ count,
+                                                        int32_t* __restrict__ status, unsigned short* __restrict__ cx,
+                                                        unsigned short* __restrict__ Xo)
+{
+    extern __shared__ unsigned fullmap[];  // ceil(h / 32) words, filled only when some row needs the slow path
+    __shared__ int s_cnt[MAXLISTS], s_base[MAXLISTS];
+    __shared__ int s_idx[RC_SLOTS];
+    __shared__ int s_slow, s_again[4];
+    __shared__ unsigned s_red[4];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int nl = (h + 255) / 256, nw = (h + 31) / 32;
+    const int total = scan_lists(L.count, nl, s_cnt, s_base);
+    const int cnt = total < cap ? total : cap;
+    const bool all_slow = total > cap || cnt > RC_SLOTS;
+    if (tid == 0) s_slow = all_slow ? 1 : 0;
+    for (int b = tid; b < nl; b += 256) {
+        const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+        const int base = s_base[b];
+        for (int e = 0; e < n && base + e < cap; e++) {
+            const int j = L.cand[(size_t)b * capc + e];
+            if (base + e < RC_SLOTS) s_idx[base + e] = j;
+            if (blockIdx.x == 0) idx[base + e] = j;
+        }
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        *count = cnt;
+        if (status) *status = total > cap ? 1 : 0;
+    }
+    __syncthreads();
+    const int i = blockIdx.x * 4 + w;  // this wave's row
+    const unsigned short* row = X + (size_t)(i < s ? i : 0) * h;
+    unsigned m1 = 0, mo = 0;
+    bool need = false;
+    if (i < s && !all_slow) {
+        for (int cb = lane; cb < ncb; cb += 64) {
+            const unsigned v = rowpart[(size_t)cb * s + i];
+            m1 = v > m1 ? v : m1;
+        }
+        for (int t = lane; t < opad; t += 64) {
+            unsigned short v = 0;
+            if (t < cnt) {
+                v = row[s_idx[t]];
+                const unsigned a = v & 0x7fffu;
+                if (a < thr) mo = a > mo ? a : mo;
+            }
+            Xo[(size_t)i * opad + t] = v;
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const unsigned t1 = (unsigned)__shfl_xor((int)m1, d), t2 = (unsigned)__shfl_xor((int)mo, d);
+            m1 = t1 > m1 ? t1 : m1;
+            mo = t2 > mo ? t2 : mo;
+        }
+        need = mo >= m1 && m1 > 0;
+    }
+    if (lane == 0) {
+        s_again[w] = (i < s && (all_slow || need)) ? 1 : 0;
+        if (need) s_slow = 1;
+    }
+    __syncthreads();
+    if (s_slow) {  // uniform: the bitmap of all outlier columns, then the whole workgroup scans each such row again
+        for (int q = tid; q < nw; q += 256) fullmap[q] = 0;
+        __syncthreads();
+        for (int b = tid; b < nl; b += 256) {
+            const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+            const int base = s_base[b];
+            for (int e = 0; e < n && base + e < cap; e++) {
+                const int j = L.cand[(size_t)b * capc + e];
+                atomicOr(&fullmap[j >> 5], 1u << (j & 31));
+            }
+        }
+        __syncthreads();
+        for (int r4 = 0; r4 < 4; r4++) {
+            if (!s_again[r4]) continue;  // uniform
+            const int i2 = blockIdx.x * 4 + r4;
+            const unsigned short* row2 = X + (size_t)i2 * h;
+            unsigned m = 0;
+            for (int c0 = tid * 8; c0 < h; c0 += 4 * 2048) {  // h is a multiple of 8 here; four 16-byte loads in flight
+                us8 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const int c = c0 + u * 2048;
+                    v[u] = (us8)(0);
+                    if (c < h) v[u] = *(const us8*)(row2 + c) & (unsigned short)0x7fff;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const int c = c0 + u * 2048;
+                    if (c < h) {
+                        const unsigned bits = (fullmap[c >> 5] >> (c & 31)) & 0xffu;
+#pragma unroll
+                        for (int e = 0; e < 8; e++) {
+                            const unsigned x = ((bits >> e) & 1u) ? 0u : (unsigned)v[u][e];
+                            m = x > m ? x : m;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const unsigned t = (unsigned)__shfl_xor((int)m, d);
+                m = t > m ? t : m;
+            }
+            if (lane == 0) s_red[w] = m;
+            __syncthreads();
+            if (tid == 0) {
+                const unsigned a = s_red[0] > s_red[1] ? s_red[0] : s_red[1];
+                const unsigned b = s_red[2] > s_red[3] ? s_red[2] : s_red[3];
+                cx[i2] = (unsigned short)(a > b ? a : b);
+            }
+            if (all_slow) {  // gather straight from the lists: the LDS copy may not hold them all
+                for (int b = tid; b < nl; b += 256) {
+                    const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+                    const int base = s_base[b];
+                    for (int e = 0; e < n && base + e < cap; e++)
+                        Xo[(size_t)i2 * opad + base + e] = row2[L.cand[(size_t)b * capc + e]];
+                }
+                for (int t = cnt + tid; t < opad; t += 256) Xo[(size_t)i2 * opad + t] = 0;
+            }
+            __syncthreads();  // s_red is reused by the next row
+        }
+    }
+    if (i < s && lane == 0 && !(all_slow || need)) cx[i] = (unsigned short)m1;
+}
+
+// ---------------------------------------------------------------------------
 // X_i8 in the tiled layout.  One workgroup: 32 rows (one row tile) x 256
 // features (8 tiles, contiguous in the output).  Rows are read as 512-byte
 // pieces, coded, scattered into LDS at their tile position and written out as
@@ -833,6 +1054,25 @@ hipError_t launch_quantize_rows_lists(const void* X, int s, int h, OutlierLists 
     dim3 grid(RT, (KT * 32 + 255) / 256);
     quantize_rows_kernel<true><<<grid, 256, 0, st>>>((const unsigned short*)X, s, h, idx, count, L, capc, cap, cx, Xq, KT,
                                                      vec_ok);
+    return hipGetLastError();
+}
+
+// the per-call pre-pass for s > 32 when X allows 16-byte loads: row constants from the partial row maxima
+// of the column scan instead of another full pass over X
+hipError_t launch_quantize_rows_rowpart(const void* X, int s, int h, OutlierLists L, unsigned thr,
+                                        const unsigned short* rowpart, int32_t* idx, int32_t* count, int32_t* status,
+                                        int cap, int8_t* Xq, unsigned short* cx, unsigned short* Xo, hipStream_t st)
+{
+    const int KT = k_tiles(h), RT = row_tiles(s);
+    const int opad = opad_of(cap), capc = list_capacity(cap);
+    const size_t shm = ((size_t)(h + 31) / 32) * sizeof(unsigned);
+    row_const_kernel<<<(s + 3) / 4, 256, shm, st>>>((const unsigned short*)X, s, h, L, capc, cap, opad, thr, rowpart,
+                                                    (h + 511) / 512, idx, count, status, cx, Xo);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    dim3 grid(RT, (KT * 32 + 255) / 256);
+    quantize_rows_kernel<true><<<grid, 256, 0, st>>>((const unsigned short*)X, s, h, idx, count, L, capc, cap, cx, Xq, KT,
+                                                     1);
     return hipGetLastError();
 }
 

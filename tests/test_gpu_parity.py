@@ -250,6 +250,25 @@ def test_linear_prefill_sizes():
     linear_compare(wl.make_custom(48, 256, 64, 0, seed=47), alpha=float("inf"))
 
 
+def test_linear_row_maximum_inside_an_outlier_column():
+    """Rows whose largest magnitude below alpha sits in an outlier column (alone, or tied with a regular
+    column): the row constant must come from the regular columns only."""
+    d = wl.make_custom(200, 1024, 128, 4, seed=51)
+    X = d["X"]
+    j0, j1 = int(d["planted"][0]), int(d["planted"][-1])
+    free = [j for j in range(1024) if j not in set(d["planted"].tolist())]
+    quiet = np.nonzero(np.abs(X[:, j0].astype(np.float32)) < 6.0)[0]
+    assert len(quiet) >= 20
+    X[quiet[:10], j0] = np.float16(5.5)            # alone at the top of the row
+    X[quiet[10:15], j0] = np.float16(-5.75)
+    X[quiet[10:15], free[3]] = np.float16(5.75)    # tied with a regular column
+    X[quiet[15:20], j1] = np.float16(5.9)
+    X[quiet[15:20], j0] = np.float16(5.9)          # two outlier columns share it
+    linear_compare(d)
+    linear_compare(d, cap=2)                        # ... and with the columns beyond cap counted as regular
+    linear_compare(wl.make_custom(64, 333, 64, 3, seed=52))   # h not a multiple of 8: the three-pass pre-pass
+
+
 def test_linear_short_x_degenerate_cases():
     linear_compare(wl.make("tiny"))
     linear_compare(wl.make("tiny"), alpha=0.0, cap=256)           # every column an outlier
