@@ -9,14 +9,20 @@ typedef unsigned short us8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 
-// round-half-even of the exact quotient 127 x / c for fp16 x, c with |x| <= c,
-// c > 0: 127 x is exact in fp32, the IEEE fp32 division is correctly rounded
-// and a non-tie quotient lies further from a half-integer than half an fp32 ulp,
-// so rint() of the fp32 quotient is the exact answer.  Do not replace the
-// division by a multiplication with a reciprocal.
-__device__ __forceinline__ int q8(float x, float c)
+// round-half-even of the exact quotient 127 x / c for fp16 x, c with |x| <= c, c > 0.
+// a = 127 x is exact in fp32; a non-tie quotient a / c lies further from a half-integer than half an
+// fp32 ulp, so rint() of the correctly rounded fp32 quotient is the exact answer.  The correctly
+// rounded quotient comes without a division per element: with rc = the correctly rounded reciprocal of
+// c (one IEEE division per row / column, by the caller), q = a rc is within an ulp of a / c, the fused
+// multiply-add gives the remainder r = a - q c exactly, and q + r rc rounds to the correctly rounded
+// quotient (Markstein's correction step).  Checked against integer arithmetic for every pair of fp16
+// values |x| <= c.  Do not drop the correction step, and do not let rc be an approximate reciprocal.
+__device__ __forceinline__ int q8(float x, float c, float rc)
 {
-    return (int)__builtin_rintf((x * 127.0f) / c);
+    const float a = x * 127.0f;
+    const float q = a * rc;
+    const float r = __builtin_fmaf(-q, c, a);
+    return (int)__builtin_rintf(__builtin_fmaf(r, rc, q));
 }
 
 // ---------------------------------------------------------------------------
@@ -584,10 +590,11 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
         const int r = q * 8 + (tid >> 5);
         const us8 v = xv[q];
         const float c = (r < s) ? f16_bits_to_float((unsigned short)s_cxb[r]) : 0.0f;
+        const float rc = c > 0.0f ? 1.0f / c : 0.0f;
         unsigned lo = 0, hi = 0;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-            const int qv = (c > 0.0f && !((bits >> e) & 1u)) ? q8(f16_bits_to_float(v[e]), c) : 0;
+            const int qv = (c > 0.0f && !((bits >> e) & 1u)) ? q8(f16_bits_to_float(v[e]), c, rc) : 0;
             const unsigned byte = (unsigned)qv & 0xffu;
             if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
         }
@@ -656,9 +663,12 @@ __global__ void __launch_bounds__(256) quantize_weight_kernel(const unsigned sho
     const int jt0 = blockIdx.x * 8;
     const int cg = tid & 31, sub = tid >> 5;
     const int j0 = jt0 * 32 + cg * 8;
-    float c[8];
+    float c[8], rc[8];
 #pragma unroll
-    for (int e = 0; e < 8; e++) c[e] = (j0 + e < o) ? f16_bits_to_float(cw[j0 + e]) : 0.0f;
+    for (int e = 0; e < 8; e++) {
+        c[e] = (j0 + e < o) ? f16_bits_to_float(cw[j0 + e]) : 0.0f;
+        rc[e] = c[e] > 0.0f ? 1.0f / c[e] : 0.0f;
+    }
 #pragma unroll
     for (int q = 0; q < 4; q++) {
         const int kk = q * 8 + sub;
@@ -675,7 +685,7 @@ __global__ void __launch_bounds__(256) quantize_weight_kernel(const unsigned sho
         }
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-            int qv = (c[e] > 0.0f) ? q8(f16_bits_to_float(v[e]), c[e]) : 0;
+            int qv = (c[e] > 0.0f) ? q8(f16_bits_to_float(v[e]), c[e], rc[e]) : 0;
             const int jj = cg * 8 + e;
             stage[(jj >> 5) * TILE_BYTES + tile_byte(jj & 31, kk)] = (int8_t)qv;
         }
@@ -998,10 +1008,11 @@ __global__ void __launch_bounds__(256) quantize_rows_kernel(const unsigned short
                     if (k + e < h) v[e] = row[k + e];
             }
         }
+        const float rc = c > 0.0f ? 1.0f / c : 0.0f;
         unsigned lo = 0, hi = 0;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-            int qv = (c > 0.0f && !((bits >> e) & 1u)) ? q8(f16_bits_to_float(v[e]), c) : 0;
+            int qv = (c > 0.0f && !((bits >> e) & 1u)) ? q8(f16_bits_to_float(v[e]), c, rc) : 0;
             unsigned byte = (unsigned)qv & 0xffu;
             if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
         }

@@ -148,30 +148,59 @@ def test_threshold_boundary_values():
     assert g["idx"].tolist() == [5, 9]
 
 
-def test_quantizer_sweep_matches_oracle_bit_for_bit():
-    # every mantissa of the row constant in one binade against every smaller magnitude, and
-    # constants in the range real rows have; includes hundreds of exact ties
-    for lo, hi, xmax, neg in [(0x3C00, 0x4000, 0x3FFF, False), (0x4400, 0x4800, 0x47FF, True),
-                              (0x0001, 0x0400, 0x03FF, False), (0x7800, 0x7C00, 0x7BFF, True)]:
-        c = np.arange(lo, hi, dtype=np.int64)
-        cols = np.arange(xmax + 1, dtype=np.int64)
-        X = np.zeros((len(c), xmax + 2), np.uint16)
-        X[:, 0] = c
-        X[:, 1:] = np.where(cols[None, :] <= c[:, None], cols[None, :], 0).astype(np.uint16)
-        if neg:
-            X[:, 1:] |= 0x8000
-        Xf = X.view(np.float16)
-        want, cx = oracle.quantize_rows(Xf, np.zeros(0, np.int32))
-        import torch
+def quantizer_sweep(lo, hi, xmax, neg):
+    """Rows = the row constants lo .. hi-1 (fp16 bit patterns), columns = every magnitude 0 .. xmax that does
+    not exceed the row's constant: codes and constants against the oracle, bit for bit."""
+    import torch
 
-        import paper_2208_07339_amd as L
-        Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
-        ws = L.Workspace.allocate(Xd.shape[0], Xd.shape[1], 32, 16)
-        outl = L.find_outliers(Xd, float("inf"), 16, ws)
-        rows = L.quantize_rows(Xd, outl)
-        got = L.export_rows(rows).cpu().numpy()
-        assert np.array_equal(bits(rows.cx.cpu().numpy()), bits(cx))
-        assert np.array_equal(got, want)
+    import paper_2208_07339_amd as L
+    c = np.arange(lo, hi, dtype=np.int64)
+    cols = np.arange(xmax + 1, dtype=np.int64)
+    X = np.zeros((len(c), xmax + 2), np.uint16)
+    X[:, 0] = c
+    X[:, 1:] = np.where(cols[None, :] <= c[:, None], cols[None, :], 0).astype(np.uint16)
+    if neg:
+        X[:, 1:] |= 0x8000
+    Xf = X.view(np.float16)
+    want, cx = oracle.quantize_rows(Xf, np.zeros(0, np.int32))
+    Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
+    ws = L.Workspace.allocate(Xd.shape[0], Xd.shape[1], 32, 16)
+    outl = L.find_outliers(Xd, float("inf"), 16, ws)
+    rows = L.quantize_rows(Xd, outl)
+    got = L.export_rows(rows).cpu().numpy()
+    assert np.array_equal(bits(rows.cx.cpu().numpy()), bits(cx))
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("first", range(0, 31, 4))
+def test_quantizer_on_every_pair_of_fp16_values(first):
+    """Exhaustive: every finite row constant c > 0 (31 binades of 1024 patterns, the subnormal one included)
+    against every magnitude |x| <= c, the sign alternating by binade.  The quantizer divides through a
+    reciprocal and a correction step; this is the proof that it still rounds the exact quotient."""
+    for b in range(first, min(first + 4, 31)):
+        lo, hi = max(1, b * 1024), (b + 1) * 1024
+        quantizer_sweep(lo, hi, hi - 1, neg=bool(b & 1))
+
+
+def test_weight_quantizer_sweep():
+    """The same sweep through the column constants of llmint8_quantize_weight (one binade each of typical,
+    subnormal and maximal constants)."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    for lo, hi in [(0x2000, 0x2400), (0x0001, 0x0400), (0x7800, 0x7C00)]:
+        c = np.arange(lo, hi, dtype=np.int64)
+        rowsv = np.arange(hi, dtype=np.int64)
+        W = np.zeros((hi + 1, len(c)), np.uint16)
+        W[0, :] = c
+        W[1:, :] = np.where(rowsv[:, None] <= c[None, :], rowsv[:, None], 0).astype(np.uint16)
+        W[1::2, :] |= 0x8000
+        Wf = W.view(np.float16)
+        want, cw = oracle.quantize_weight(Wf)
+        Wd = torch.from_numpy(W.view(np.int16)).cuda().view(torch.float16)
+        qw = L.quantize_weight(Wd)
+        assert np.array_equal(bits(qw.cw.cpu().numpy()), bits(cw))
+        assert np.array_equal(hip_weight_i8(qw), want)
 
 
 def test_two_runs_are_bit_identical():
