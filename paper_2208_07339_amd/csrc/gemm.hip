@@ -521,7 +521,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                         const int i = I0 + b0 * 32 + tl;
                         const int j = J0 + a0 * 32 + q * 8;
                         if (FAST) {
-                            if (na == 2 || q < 4) *(u4*)(g.Out + (size_t)i * o + j) = v;
+                            if (na == 2 || q < 4) __builtin_nontemporal_store(v, (u4*)(g.Out + (size_t)i * o + j));
                         } else if ((tl < 32 || b0 + 1 < WB) && i < s && q < 4 * na) {
                             if (g.fast_ok && j + 8 <= o) {
                                 *(u4*)(g.Out + (size_t)i * o + j) = v;
