@@ -38,6 +38,9 @@ MEASURED_TRAFFIC = {
 }
 
 
+WARM_MS = 60.0  # least duration of the untimed warm-up (see run_workload)
+
+
 def algorithmic_bytes_decode(s, h, o, n_out):
     """W_i8 + c_w + Out + outlier rows of W_f16 + X_i8 tile + Xo, per launch of the decode kernel."""
     return h * o + 2 * o + 2 * s * o + n_out * o * 2 + 32 * h + s * 32 * 2
@@ -79,8 +82,16 @@ def run_workload(name, steps, warmup, copies=1, int8_rows=False, granularity="ve
     def step(i):
         L.linear(Xd, qws[i % len(qws)], d["alpha"], outl, rows, ws, out, granularity=granularity)
 
-    for i in range(warmup):
-        step(i)
+    # Warm-up: W steps, and more of them until WARM_MS of back-to-back work have passed.  From idle the chip
+    # needs some 30 ms of load to settle at its sustained clocks (measured: the first 10 ms run 15 % slow),
+    # which is more than W steps of a 0.1 ms call.
+    t0 = time.perf_counter()
+    n_warm = 0
+    while n_warm < warmup or (time.perf_counter() - t0) * 1e3 < WARM_MS:
+        step(n_warm)
+        n_warm += 1
+        if n_warm % 16 == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
@@ -96,15 +107,19 @@ def run_workload(name, steps, warmup, copies=1, int8_rows=False, granularity="ve
         for e in e3:
             e.record()  # creates the handles
     torch.cuda.synchronize()
+    t0 = time.perf_counter()
     for i in range(steps):
         evs[i][0].record()
         L.linear(Xd, qws[i % len(qws)], d["alpha"], outl, rows, ws, out, events=(evs[i][1], evs[i][2]),
                  granularity=granularity)
     torch.cuda.synchronize()
+    ms_step_events = (time.perf_counter() - t0) * 1e3 / steps
     ms_pre = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
     ms_mm = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
     return dict(name=name, s=s, h=h, o=o, n_out=n_out, planted=len(d["planted"]), ms_step=ms_step,
-                ms_prepass=ms_pre, ms_matmul=ms_mm, weight_quantize_ms=t_wq * 1e3, inputs=d)
+                ms_prepass=ms_pre, ms_matmul=ms_mm, ms_step_events=ms_step_events, warmup_steps_run=n_warm,
+                weight_quantize_ms=t_wq * 1e3,
+                inputs=d)
 
 
 def run_zeropoint(name, steps, warmup, alpha):
@@ -128,8 +143,12 @@ def run_zeropoint(name, steps, warmup, alpha):
     torch.cuda.synchronize()
     times = []
     for fn in (lambda: L.zp_linear(Xd, qw, alpha, outl, rows, ws, out), lambda: L.zp_matmul(rows, outl, qw, ws, out)):
-        for _ in range(warmup):
+        t0, n_warm = time.perf_counter(), 0
+        while n_warm < warmup or (time.perf_counter() - t0) * 1e3 < WARM_MS:  # as in run_workload
             fn()
+            n_warm += 1
+            if n_warm % 16 == 0:
+                torch.cuda.synchronize()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
@@ -179,8 +198,8 @@ def _cpu_rows(oracle, Xs, W, Wq, cw, alpha):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="ffn13b", choices=["ffn13b", "decode", "attn6p7b", "ffn175b_down"])
     ap.add_argument("--no-decode", action="store_true", help="skip the secondary decode measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -248,6 +267,7 @@ def main():
                    "outlier_columns_planted": res["planted"], "outlier_columns_found": res["n_out"],
                    "outlier_capacity": CAP, "outlier_rows": a.outlier_rows},
         "ms_prepass": res["ms_prepass"], "ms_matmul_kernel": res["ms_matmul"],
+        "ms_per_step_with_events": res["ms_step_events"], "warmup_steps_run": res["warmup_steps_run"],
         "weight_quantize_ms_once": res["weight_quantize_ms"],
     }
     if a.workload == "decode":
