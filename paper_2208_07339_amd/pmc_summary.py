@@ -7,7 +7,9 @@
 reported by rocprofv3 in KiB per dispatch; the device-to-device copies that `bench.py --copy-probe`
 runs first (256 MiB each: the first three dispatches of __amd_rocclr_copyBuffer) give the factor by
 which the counter over- or under-reads, and every other kernel's reading is divided by it.
-`trace`: per kernel, calls and mean / min / max duration.
+`trace`: per kernel, calls and mean / min / max duration, and the mean over the last `tail` dispatches
+(optional third argument, default the last third): bench.py's own kernel figure comes from its last,
+event-instrumented loop, after the warm-up and the timed loop, so that is the part to compare it with.
 """
 import collections
 import csv
@@ -46,14 +48,17 @@ def counters(paths):
             print(line)
 
 
-def trace(path):
+def trace(path, tail=None):
     agg = collections.defaultdict(list)
-    for r in csv.DictReader(open(path)):
+    for r in sorted(csv.DictReader(open(path)), key=lambda r: int(r["Start_Timestamp"])):
         agg[r["Kernel_Name"]].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
     total = sum(sum(v) for v in agg.values())
-    print(f"{'kernel':50s} {'calls':>6s} {'mean us':>10s} {'min us':>10s} {'max us':>10s} {'share':>7s}")
+    print(f"{'kernel':50s} {'calls':>6s} {'mean us':>10s} {'min us':>10s} {'max us':>10s} {'share':>7s} {'last-n mean':>14s}")
     for k, v in sorted(agg.items(), key=lambda kv: -sum(kv[1])):
-        print(f"{short(k):50s} {len(v):6d} {sum(v) / len(v):10.1f} {min(v):10.1f} {max(v):10.1f} {100 * sum(v) / total:6.1f}%")
+        n = min(len(v), tail) if tail else max(1, len(v) // 3)
+        last = v[-n:]
+        print(f"{short(k):50s} {len(v):6d} {sum(v) / len(v):10.1f} {min(v):10.1f} {max(v):10.1f} "
+              f"{100 * sum(v) / total:6.1f}% {sum(last) / len(last):9.1f} ({n})")
 
 
 if __name__ == "__main__":
@@ -62,4 +67,4 @@ if __name__ == "__main__":
     if sys.argv[1] == "counters":
         counters(sys.argv[2:])
     else:
-        trace(sys.argv[2])
+        trace(sys.argv[2], int(sys.argv[3]) if len(sys.argv) > 3 else None)
