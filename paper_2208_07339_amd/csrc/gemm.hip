@@ -513,6 +513,9 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                             }
                         }
                     }
+                    // The staged values are read back by other lanes of the same wave, through pointers of another
+                    // type: LDS serves a wave's requests in order, the compiler must not reorder them either.
+                    asm volatile("" ::: "memory");
                     // ---- write the staged block: a lane moves 16 bytes, 8 lanes cover a token's 128 bytes
 #pragma unroll
                     for (int p = 0; p < 8; p++) {
@@ -533,6 +536,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                             }
                         }
                     }
+                    asm volatile("" ::: "memory");  // the next block's staging writes stay behind these reads
                 }
             }
         };
