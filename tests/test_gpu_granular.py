@@ -159,3 +159,49 @@ def test_prefill_13b_ffn_up_full_size(mode, alpha):
     Cs, Os = oracle.sampled_granular(X, W, idx, ri, ci, mode)
     assert np.array_equal(Cd.cpu().numpy()[ri, ci], Cs)
     assert_out_close(out.cpu().numpy()[ri, ci], Os, float(np.abs(Os.astype(np.float64)).max()))
+
+
+def test_granular_with_rows_rebuilt_from_the_codes():
+    """The coarser constants combine with the variant that keeps no 16-bit weights (W_f16 = NULL): the
+    rebuilt rows use the shared constant."""
+    import dataclasses
+
+    import torch
+
+    import paper_2208_07339_amd as L
+    for (s, h, o), mode in (((16, 512, 256), "tensorwise"), ((120, 384, 192), "rowwise")):
+        d = wl.make_custom(s, h, o, 4, seed=s + 7)
+        X, W, cap = d["X"], d["W"], 32
+        ref = oracle.linear_granular(X, W, 6.0, mode)
+        want = oracle.output_dq(ref["C"], ref["cx"], ref["cw"], X, ref["Wq"], ref["idx"])
+        Xd, Wd = upload(X, W)
+        ws = L.Workspace.allocate(s, h, o, cap)
+        qw = dataclasses.replace(L.quantize_weight(Wd, ws, granularity=mode), W=None)
+        outl = L.Outliers(torch.empty(cap, dtype=torch.int32, device="cuda"),
+                          torch.empty(1, dtype=torch.int32, device="cuda"),
+                          torch.empty(1, dtype=torch.int32, device="cuda"), cap)
+        rows = L.QuantizedRows(torch.empty(L.xq_bytes(s, h), dtype=torch.int8, device="cuda"),
+                               torch.empty(s, dtype=torch.float16, device="cuda"),
+                               torch.empty((s, L.opad(cap)), dtype=torch.float16, device="cuda"), s, h)
+        out = L.linear(Xd, qw, 6.0, outl, rows, ws, granularity=mode)
+        torch.cuda.synchronize()
+        assert_out_close(out.cpu().numpy(), want)
+
+
+def test_granularity_argument_errors():
+    import ctypes as C
+
+    import torch
+
+    import paper_2208_07339_amd as L
+    lib = L.lib()
+    p = lambda t: C.c_void_p(t.data_ptr())
+    X = torch.zeros((4, 64), dtype=torch.float16, device="cuda")
+    Xq = torch.empty(L.xq_bytes(4, 64), dtype=torch.int8, device="cuda")
+    idx = torch.zeros(16, dtype=torch.int32, device="cuda")
+    cx = torch.zeros(4, dtype=torch.float16, device="cuda")
+    Xo = torch.zeros((4, 16), dtype=torch.float16, device="cuda")
+    for g in (-1, 3, 100):
+        assert lib.llmint8_quantize_rows_granular(p(X), 4, 64, p(idx), p(idx), 16, g, p(Xq), p(cx), p(Xo), None) == 1
+    assert lib.llmint8_quantize_rows_granular(p(X), 4, 64, p(idx), p(idx), 16, 2, p(Xq), p(cx), p(Xo), None) == 0
+    torch.cuda.synchronize()

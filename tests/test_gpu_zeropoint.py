@@ -155,3 +155,69 @@ def test_prefill_13b_ffn_up_full_size():
     Cs, Os = oracle.zp_sampled(X, W, idx, ri, ci)
     assert np.array_equal(Cd.cpu().numpy()[ri, ci], Cs)
     assert_out_close(out.cpu().numpy()[ri, ci], Os, float(np.abs(Os.astype(np.float64)).max()))
+
+
+def test_more_outlier_columns_than_cap():
+    """Only the first cap columns count as outliers; the rest are quantized like any other column (their
+    large entries then widen the row ranges).  The oracle is given exactly that set."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    d = wl.make_custom(90, 512, 128, 9, seed=61)
+    X, W, cap = one_sided(d), d["W"], 4
+    full = oracle.find_outliers(X, 6.0)
+    assert len(full) > cap
+    O = full[:cap]
+    Xd, Wd = upload(X, W)
+    ws = L.Workspace.allocate(90, 512, 128, cap)
+    qw = L.zp_quantize_weight(Wd, ws)
+    outl = L.find_outliers(Xd, 6.0, cap, ws)
+    rows = L.zp_quantize_rows(Xd, outl)
+    out, Cd = L.zp_matmul(rows, outl, qw, ws, want_c_i32=True)
+    torch.cuda.synchronize()
+    assert int(outl.status.item()) == 1 and outl.idx.cpu().numpy().tolist() == O.tolist()
+    x = oracle.zp_quantize_rows(X, O)
+    w = oracle.zp_quantize_weight(W)
+    lo, hi, zp, rs = unpack(rows.zc)
+    assert np.array_equal(lo, bits(x["lo"])) and np.array_equal(hi, bits(x["hi"]))
+    assert np.array_equal(zp, x["zp"]) and np.array_equal(rs, x["rowsum"])
+    assert np.array_equal(L.export_rows(L.QuantizedRows(rows.Xq, None, None, 90, 512)).cpu().numpy(), x["Xq"])
+    assert np.array_equal(Cd.cpu().numpy(), oracle.igemm(x["Xq"], w["Wq"]))
+    ri, ci = np.repeat(np.arange(90), 128), np.tile(np.arange(128), 90)
+    _, Os = oracle.zp_sampled(X, W, O, ri, ci)
+    assert_out_close(out.cpu().numpy().reshape(-1), Os)
+
+
+def test_argument_errors_are_reported_not_executed():
+    import ctypes as C
+
+    import torch
+
+    import paper_2208_07339_amd as L
+    lib = L.lib()
+    p = lambda t: C.c_void_p(t.data_ptr())
+    W = torch.zeros((64, 32), dtype=torch.float16, device="cuda")
+    X = torch.zeros((4, 64), dtype=torch.float16, device="cuda")
+    Wq = torch.empty(L.wq_bytes(64, 32), dtype=torch.int8, device="cuda")
+    Xq = torch.empty(L.xq_bytes(4, 64), dtype=torch.int8, device="cuda")
+    zw = torch.zeros((32, 4), dtype=torch.int32, device="cuda")
+    zx = torch.zeros((4, 4), dtype=torch.int32, device="cuda")
+    idx = torch.zeros(16, dtype=torch.int32, device="cuda")
+    Xo = torch.zeros((4, 16), dtype=torch.float16, device="cuda")
+    out = torch.zeros((4, 32), dtype=torch.float16, device="cuda")
+    ws = L.Workspace.allocate(4, 64, 32, 16)
+    INVALID, SHAPE, WORKSPACE = 1, 2, 3
+    assert lib.llmint8_zp_quantize_weight(None, 64, 32, p(Wq), p(zw), p(ws.buf), ws.nbytes, None) == INVALID
+    assert lib.llmint8_zp_quantize_weight(p(W), 64, 32, p(Wq), p(zw), p(ws.buf), 16, None) == WORKSPACE
+    assert lib.llmint8_zp_quantize_weight(p(W), 133145, 32, p(Wq), p(zw), p(ws.buf), ws.nbytes, None) == SHAPE
+    assert lib.llmint8_zp_quantize_rows(p(X), 4, 64, p(idx), p(idx), 0, p(Xq), p(zx), p(Xo), None) == INVALID
+    # the 16-bit weights are required by this variant
+    assert lib.llmint8_zp_matmul(p(Xq), p(zx), p(Xo), p(idx), p(idx), 16, p(Wq), p(zw), None, 4, 64, 32, p(out), None,
+                                 p(ws.buf), ws.nbytes, None) == INVALID
+    assert lib.llmint8_zp_matmul(p(Xq), p(zx), p(Xo), p(idx), p(idx), 16, p(Wq), p(zw), p(W), 4, 64, 32, p(out), None,
+                                 p(ws.buf), 64, None) == WORKSPACE
+    # records must be 16-byte aligned
+    off = torch.zeros(4 * 4 + 1, dtype=torch.int32, device="cuda")[1:]
+    assert lib.llmint8_zp_quantize_rows(p(X), 4, 64, p(idx), p(idx), 16, p(Xq), p(off), p(Xo), None) == INVALID
+    assert lib.llmint8_zp_linear(p(X), 4, 64, 6.0, p(Wq), p(zw), p(W), 32, p(idx), 16, p(idx), None, p(Xq), p(zx),
+                                 p(Xo), p(out), p(ws.buf), 64, None) == WORKSPACE
