@@ -71,8 +71,8 @@ size_t llmint8_xq_bytes(int s, int h);
 /* Bytes of scratch any of the calls below may need for these sizes. */
 size_t llmint8_workspace_bytes(int s, int h, int o, int cap);
 
-/* Section 3.1 / Section 2.1, done once per weight ("converted to Int8 and
- * used immediately"): c_w[j] = max_k |W[k][j]| over all h rows,
+/* Section 3.1 / Section 2.1, done once per weight (the weights are turned into
+ * int8 when they are loaded, before any X is seen): c_w[j] = max_k |W[k][j]| over all h rows,
  * W_i8[k][j] = round-half-even(127 W[k][j] / c_w[j]) (0 where c_w[j] = 0).
  *   W_f16  in   [h x o] fp16
  *   Wq     out  llmint8_wq_bytes(h, o) bytes, private layout

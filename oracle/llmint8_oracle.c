@@ -234,7 +234,7 @@ void oracle_output(const int32_t *C, const uint16_t *cx, const uint16_t *cw, con
 
 /* ---- variant: outlier rows of W rebuilt from the int8 codes ---------------- */
 
-/* Section 3.2 counts only "about 0.1% additional memory" for the decomposition,
+/* Section 3.2 puts the extra memory of the decomposition at roughly a tenth of a percent,
  * which keeping all of W in 16 bits would not give.  This variant stores no
  * 16-bit weights: the rows O of W are rebuilt from the codes by inverting the
  * absmax quantization of Section 2.1, W^[k][j] = fp16( W_i8[k][j] * c_w[j] / 127 )
