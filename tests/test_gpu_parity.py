@@ -392,3 +392,21 @@ def test_argument_errors_are_reported_not_executed():
     assert lib.llmint8_find_outliers(p(X), 4, 8, 6.0, p(idx), 0, p(idx), None, p(idx), 1 << 20, None) == 1
     with pytest.raises(L.Llmint8Error):
         L.binding._check(3)
+
+
+def test_random_shapes_through_the_one_call_path():
+    """Seeded random shapes on both sides of the 32-token split, aligned and ragged, with random outlier
+    counts, capacities (some too small) and thresholds: llmint8_linear against the oracle, stage by stage."""
+    rng = np.random.default_rng(20240607)
+    for case in range(24):
+        s = int(rng.choice([rng.integers(1, 33), rng.integers(33, 400)]))
+        h = int(rng.choice([8 * rng.integers(4, 260), rng.integers(20, 1500)]))
+        o = int(rng.choice([8 * rng.integers(2, 90), rng.integers(9, 600)]))
+        ncol = int(rng.integers(0, min(h, 40)))
+        cap = int(rng.choice([32, 16, 48, max(1, ncol // 2)]))
+        alpha = float(rng.choice([6.0, 6.0, 4.5, 9.0]))
+        d = wl.make_custom(s, h, o, ncol, seed=1000 + case)
+        try:
+            linear_compare(d, alpha=alpha, cap=cap)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: s={s} h={h} o={o} ncol={ncol} cap={cap} alpha={alpha}: {e}") from e
