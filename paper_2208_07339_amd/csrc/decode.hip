@@ -108,6 +108,8 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
         wp[n] = (const v4i*)(Wq + ((size_t)jt * KT + (size_t)w * kq) * TILE_BYTES) + lane;
     }
     const v4i* xp = (const v4i*)(Xq + (size_t)w * kq * TILE_BYTES) + lane;
+    // a lane holds token (lane % 32) of the X tile; tokens >= s are zero padding and need not be fetched
+    const bool xrow = (lane & 31) < s;
 
     v16i acc[NJ];
 #pragma unroll
@@ -122,7 +124,7 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
         for (int u = 0; u < U; u++) {
 #pragma unroll
             for (int n = 0; n < NJ; n++) wv[BB][n][u] = __builtin_nontemporal_load(wp[n] + (size_t)(kt + u) * 64);
-            xv[BB][u] = xp[(size_t)(kt + u) * 64];
+            xv[BB][u] = xrow ? xp[(size_t)(kt + u) * 64] : v4i{0, 0, 0, 0};
         }
     };
     auto mm = [&](auto B) {
@@ -151,7 +153,7 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     }
     if (b < nb) mm(B0{});  // odd number of batches: the last one is already in flight in buffer 0
     for (int kt = nb * U; kt < kq; kt++) {
-        const v4i x1 = xp[(size_t)kt * 64];
+        const v4i x1 = xrow ? xp[(size_t)kt * 64] : v4i{0, 0, 0, 0};
 #pragma unroll
         for (int n = 0; n < NJ; n++) {
             const v4i w1 = __builtin_nontemporal_load(wp[n] + (size_t)kt * 64);
