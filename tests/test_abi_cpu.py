@@ -55,3 +55,29 @@ def test_product_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 txt = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in txt and "from oracle" not in txt and "liboracle" not in txt, f
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    """No fallback: without the built HIP library the binding raises instead of computing anything."""
+    from paper_2208_07339_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libllmint8.so"))
+    with pytest.raises(binding.Llmint8Error, match="no fallback"):
+        binding.lib()
+
+
+def test_argument_checks_of_the_variants_need_no_gpu(lib):
+    assert lib.llmint8_zp_quantize_weight(None, 4, 4, None, None, None, 0, None) == 1
+    assert lib.llmint8_zp_linear(*([None] * 1), 4, 4, C.c_float(6.0), None, None, None, 4, None, 4, None, None,
+                                 None, None, None, None, None, 0, None) == 1
+    assert lib.llmint8_quantize_weight_granular(None, 4, 4, 0, None, None, None, 0, None) == 1
+    assert lib.llmint8_dequantize_rows(None, None, 4, 4, None, None, 4, None, None) == 1
+    assert lib.llmint8_debug_prefill_tile(99) == 1 and lib.llmint8_debug_prefill_tile(-1) == 0
+    assert lib.llmint8_debug_decode_shape(99) == 1 and lib.llmint8_debug_decode_shape(-1) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "single-GPU" in r.stderr
