@@ -47,10 +47,9 @@ def sample_rows(rng, s, wrap, n):
     return np.unique(np.r_[fixed, rng.integers(0, s, n)]).astype(np.int64)
 
 
-def test_more_than_2_31_elements_in_x():
-    import torch
-
-    import paper_2208_07339_amd as L
+@pytest.fixture(scope="module")
+def big_x():
+    """X with s * h > 2^31 (host and device), a small W, and the outlier columns of X."""
     s, h, o, block = 66000, 32768, 64, 2048
     assert s * h > 2 ** 31
     X = tiled_matrix(s, h, block, 1.0, 1)
@@ -63,8 +62,15 @@ def test_more_than_2_31_elements_in_x():
     decisive = np.r_[0:block, sorted({i for i, _ in planted})]
     idx = oracle.find_outliers(np.ascontiguousarray(X[decisive]), 6.0)
     assert {3, 777, 20001, h - 1} <= set(idx.tolist()) and len(idx) <= CAP
+    return X, W, idx, upload(X), upload(W)
 
-    Xd, Wd = upload(X), upload(W)
+
+def test_more_than_2_31_elements_in_x(big_x):
+    import torch
+
+    import paper_2208_07339_amd as L
+    X, W, idx, Xd, Wd = big_x
+    (s, h), o = X.shape, W.shape[1]
     ws = L.Workspace.allocate(s, h, o, CAP)
     qw = L.quantize_weight(Wd, ws)
     outl, rows = buffers(L, s, h)
@@ -93,6 +99,51 @@ def test_more_than_2_31_elements_in_x():
     torch.cuda.synchronize()
     assert outl2.idx[:n].cpu().numpy().tolist() == idx.tolist()
     assert torch.equal(rows2.cx, rows.cx) and torch.equal(rows2.Xq, rows.Xq)
+
+
+def zp_buffers(L, s, h):
+    import torch
+    outl, _ = buffers(L, 1, 32)
+    rows = L.ZpRows(torch.empty(L.xq_bytes(s, h), dtype=torch.int8, device="cuda"),
+                    torch.empty((s, 4), dtype=torch.int32, device="cuda"),
+                    torch.empty((s, L.opad(CAP)), dtype=torch.float16, device="cuda"), s, h)
+    return outl, rows
+
+
+def unpack(zc):
+    """[n, 4] int32 records -> lo bits, hi bits, zp, sum."""
+    zc = zc.cpu().numpy()
+    w0 = zc[:, 0].astype(np.int64) & 0xffffffff
+    return (w0 & 0xffff).astype(np.uint16), (w0 >> 16).astype(np.uint16), zc[:, 1], zc[:, 2]
+
+
+def test_zeropoint_more_than_2_31_elements_in_x(big_x):
+    import torch
+
+    import paper_2208_07339_amd as L
+    X, W, idx, Xd, Wd = big_x
+    (s, h), o = X.shape, W.shape[1]
+    ws = L.Workspace.allocate(s, h, o, CAP)
+    qw = L.zp_quantize_weight(Wd, ws)
+    outl, rows = zp_buffers(L, s, h)
+    out = L.zp_linear(Xd, qw, 6.0, outl, rows, ws)
+    torch.cuda.synchronize()
+    n = int(outl.count.item())
+    assert outl.idx[:n].cpu().numpy().tolist() == idx.tolist()
+    rng = np.random.default_rng(8)
+    rsel = sample_rows(rng, s, 2 ** 31 // h, 800)
+    ref = oracle.zp_quantize_rows(np.ascontiguousarray(X[rsel]), idx)
+    rsel_d = torch.from_numpy(rsel).cuda()
+    lo, hi, zp, rs = unpack(rows.zc[rsel_d])
+    assert np.array_equal(lo, bits(ref["lo"])) and np.array_equal(hi, bits(ref["hi"]))
+    assert np.array_equal(zp, ref["zp"]) and np.array_equal(rs, ref["rowsum"])
+    xq = L.export_rows(L.QuantizedRows(rows.Xq, None, None, s, h))[rsel_d].cpu().numpy()
+    assert np.array_equal(xq, ref["Xq"])
+    ri = np.repeat(rsel[::4], 4)
+    ci = rng.integers(0, o, len(ri))
+    _, Os = oracle.zp_sampled(X, W, idx, ri, ci)
+    got = out[torch.from_numpy(ri).cuda(), torch.from_numpy(ci).cuda()].cpu().numpy()
+    assert_out_close(got, Os, float(np.abs(Os.astype(np.float64)).max()))
 
 
 def test_more_than_2_31_elements_in_out():
@@ -137,14 +188,14 @@ def big_w():
     Wd = upload(W)
     qw = L.quantize_weight(Wd, L.Workspace.allocate(1, h, o, CAP))
     torch.cuda.synchronize()
-    return W, qw
+    return W, qw, Wd
 
 
 def test_more_than_2_31_elements_in_w_quantized(big_w):
     import torch
 
     import paper_2208_07339_amd as L
-    W, qw = big_w
+    W, qw, _ = big_w
     o = W.shape[1]
     rng = np.random.default_rng(6)
     csel = np.unique(np.r_[0:4, o - 40:o, rng.integers(0, o, 400)])
@@ -159,7 +210,7 @@ def test_more_than_2_31_elements_in_w(big_w, s):
     import torch
 
     import paper_2208_07339_amd as L
-    W, qw = big_w
+    W, qw, _ = big_w
     h, o = W.shape
     rng = np.random.default_rng(7 + s)
     X = rng.standard_normal((s, h), dtype=np.float32).astype(np.float16)
@@ -177,5 +228,41 @@ def test_more_than_2_31_elements_in_w(big_w, s):
     ri = rng.integers(0, s, 600)
     ci = np.r_[rng.integers(0, o, 560), np.arange(o - 40, o)]
     _, Os = oracle.sampled(X, W, idx, ri, ci)
+    got = out[torch.from_numpy(ri).cuda(), torch.from_numpy(ci).cuda()].cpu().numpy()
+    assert_out_close(got, Os, float(np.abs(Os.astype(np.float64)).max()))
+
+
+@pytest.mark.parametrize("s", [16, 40])
+def test_zeropoint_more_than_2_31_elements_in_w(big_w, s):
+    import torch
+
+    import paper_2208_07339_amd as L
+    W, _, Wd = big_w
+    h, o = W.shape
+    rng = np.random.default_rng(9 + s)
+    X = np.abs(rng.standard_normal((s, h), dtype=np.float32)).astype(np.float16)   # one-sided rows
+    for k in (5, 40000, h - 1):
+        X[k % s, k] = 30.0
+    idx = oracle.find_outliers(X, 6.0)
+    assert {5, 40000, h - 1} <= set(idx.tolist()) and len(idx) <= CAP
+    ws = L.Workspace.allocate(s, h, o, CAP)
+    qw = L.zp_quantize_weight(Wd, ws)
+    torch.cuda.synchronize()
+    csel = np.unique(np.r_[0:4, o - 40:o, rng.integers(0, o, 200)])
+    ref = oracle.zp_quantize_weight(np.ascontiguousarray(W[:, csel]))
+    csel_d = torch.from_numpy(csel).cuda()
+    lo, hi, zp, cs = unpack(qw.zc[csel_d])
+    assert np.array_equal(lo, bits(ref["lo"])) and np.array_equal(hi, bits(ref["hi"]))
+    assert np.array_equal(zp, ref["zp"]) and np.array_equal(cs, ref["colsum"])
+    wq = L.export_weight(L.QuantizedWeight(qw.Wq, None, None, h, o))[:, csel_d].cpu().numpy()
+    assert np.array_equal(wq, ref["Wq"])
+    outl, rows = zp_buffers(L, s, h)
+    out = L.zp_linear(upload(X), qw, 6.0, outl, rows, ws)
+    torch.cuda.synchronize()
+    n = int(outl.count.item())
+    assert outl.idx[:n].cpu().numpy().tolist() == idx.tolist()
+    ri = rng.integers(0, s, 400)
+    ci = np.r_[rng.integers(0, o, 360), np.arange(o - 40, o)]
+    _, Os = oracle.zp_sampled(X, W, idx, ri, ci)
     got = out[torch.from_numpy(ri).cuda(), torch.from_numpy(ci).cuda()].cpu().numpy()
     assert_out_close(got, Os, float(np.abs(Os.astype(np.float64)).max()))
