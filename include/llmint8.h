@@ -25,7 +25,10 @@
  *     them into plain row-major int8 matrices.
  *   - stream is a hipStream_t (NULL = the default stream).  Every call only
  *     enqueues kernels on it: no host synchronisation, no allocation, no
- *     global state (llmint8_debug_prefill_tile aside).  Calls that share a workspace must be ordered by stream.
+ *     global state (llmint8_debug_prefill_tile aside).  Calls that share a
+ *     workspace must be ordered by stream.  A call may therefore be recorded
+ *     into a HIP graph by stream capture and replayed; make the first call of
+ *     a process on each device outside a capture (it sets kernel attributes).
  *   - Return value: LLMINT8_OK or an error code below; nothing is enqueued
  *     when an argument error is returned.  Conditions only visible on the
  *     device (|O| > cap) set bit 0 of the device status word and clamp.

@@ -576,12 +576,15 @@ static hipError_t launch_cfg(GemmArgs& g, hipStream_t st)
     constexpr int shm = NB * STAGE + 4 * 8192;  // operand ring + output staging
     g.nP = (g.JT + 2 * WA - 1) / (2 * WA);
     g.nQ = (g.RT + 2 * WB - 1) / (2 * WB);
-    static bool attr_set = false;
-    if (!attr_set) {
+    // once per device: the attribute belongs to the kernel as loaded on that device
+    static bool attr_set[16] = {false};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = -1;
+    if (dev < 0 || !attr_set[dev]) {
         hipError_t e = hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, ZP>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, shm);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        if (dev >= 0) attr_set[dev] = true;
     }
     const int total = g.nP * g.nQ, ncu = compute_units();
     gemm_prefill_kernel<WA, WB, ZP><<<total < ncu ? total : ncu, 256, shm, st>>>(g);

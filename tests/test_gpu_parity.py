@@ -410,3 +410,47 @@ def test_random_shapes_through_the_one_call_path():
             linear_compare(d, alpha=alpha, cap=cap)
         except AssertionError as e:
             raise AssertionError(f"case {case}: s={s} h={h} o={o} ncol={ncol} cap={cap} alpha={alpha}: {e}") from e
+
+
+@pytest.mark.parametrize("s,h,o", [(16, 1024, 768), (200, 640, 384)])  # weight-streaming path, tiled path
+def test_linear_replayed_from_a_captured_graph(s, h, o):
+    """The one-call entry point allocates nothing and enqueues kernels only, so a caller may capture it
+    in a graph: every replay, on new contents of X (other outlier columns, other constants), must give
+    what the oracle gives, with the program's own eager work between the replays."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    cap = 32
+    inputs = [wl.make_custom(s, h, o, n, seed=50 + n) for n in (3, 0, 6)]
+    W = inputs[0]["W"]
+    Wd = torch.from_numpy(W.view(np.int16)).cuda().view(torch.float16)
+    ws = L.Workspace.allocate(s, h, o, cap)
+    qw = L.quantize_weight(Wd, ws)
+    Wq_ref, cw_ref = oracle.quantize_weight(W)
+    Xd = torch.zeros((s, h), dtype=torch.float16, device="cuda")
+    out = torch.zeros((s, o), dtype=torch.float16, device="cuda")
+    outl = L.Outliers(torch.zeros(cap, dtype=torch.int32, device="cuda"),
+                      torch.zeros(1, dtype=torch.int32, device="cuda"),
+                      torch.zeros(1, dtype=torch.int32, device="cuda"), cap)
+    rows = L.QuantizedRows(torch.zeros(L.xq_bytes(s, h), dtype=torch.int8, device="cuda"),
+                           torch.zeros(s, dtype=torch.float16, device="cuda"),
+                           torch.zeros((s, L.opad(cap)), dtype=torch.float16, device="cuda"), s, h)
+    L.linear(Xd, qw, 6.0, outl, rows, ws, out=out)   # once outside: one-time set-up (kernel attributes) is not captured
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        L.linear(Xd, qw, 6.0, outl, rows, ws, out=out)
+    for d in inputs + inputs[:1]:
+        X = d["X"]
+        Xd.copy_(torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16))   # eager work between replays
+        out.fill_(7.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        idx = oracle.find_outliers(X, 6.0)
+        n = int(outl.count.item())
+        assert outl.idx[:n].cpu().numpy().tolist() == idx.tolist()
+        Xq, cx = oracle.quantize_rows(X, idx)
+        assert np.array_equal(bits(rows.cx.cpu().numpy()), bits(cx))
+        assert np.array_equal(L.export_rows(rows).cpu().numpy(), Xq)
+        ref = oracle.output(oracle.igemm(Xq, Wq_ref), cx, cw_ref, X, W, idx)
+        assert_out_close(out.cpu().numpy(), ref)
