@@ -454,3 +454,27 @@ def test_linear_replayed_from_a_captured_graph(s, h, o):
         assert np.array_equal(L.export_rows(rows).cpu().numpy(), Xq)
         ref = oracle.output(oracle.igemm(Xq, Wq_ref), cx, cw_ref, X, W, idx)
         assert_out_close(out.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("s,h,o,ncol", [(1, 1, 1, 0), (1, 1, 1, 1), (1, 3, 7, 1), (2, 5, 5, 2), (3, 2, 1, 0), (31, 7, 9, 3),
+                                        (33, 1, 1, 0), (33, 1, 2, 1), (40, 7, 3, 2), (64, 3, 9, 1), (70, 9, 1, 4)])
+def test_smallest_dimensions(s, h, o, ncol):
+    """One feature, one output column, one token, on both sides of the 32-token split: everything is padding."""
+    linear_compare(wl.make_custom(s, h, o, ncol, seed=7 * s + h + o))
+    zp = oracle.zp_linear  # the zeropoint variant on the same inputs
+    import torch
+
+    import paper_2208_07339_amd as L
+    d = wl.make_custom(s, h, o, ncol, seed=7 * s + h + o)
+    X, W = d["X"], d["W"]
+    ref = zp(X, W, 6.0)
+    Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
+    Wd = torch.from_numpy(W.view(np.int16)).cuda().view(torch.float16)
+    ws = L.Workspace.allocate(s, h, o, 32)
+    qw = L.zp_quantize_weight(Wd, ws)
+    outl = L.find_outliers(Xd, 6.0, 32, ws)
+    rows = L.zp_quantize_rows(Xd, outl)
+    out, Cd = L.zp_matmul(rows, outl, qw, ws, want_c_i32=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(Cd.cpu().numpy(), ref["C"])
+    assert_out_close(out.cpu().numpy(), ref["Out"])
