@@ -98,6 +98,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     constexpr int NMFMA = 2 * WA * WB;
     constexpr int NRD = 2 * (WA + WB);
     constexpr int NOPS = PIECES + NRD;
+    constexpr int OPSPAN = NMFMA;                // MFMA slots of a stage that carry its requests and LDS reads
     constexpr int NEW = 16;                      // epilogue-stage pieces holding W rows: [32 slots][256 columns] fp16
     constexpr int NEX = 4 * WB;                  // pieces holding Xo: [64*WB tokens][opad <= 32 slots] fp16
     static_assert(NEW + NEX + 1 <= 8 * PIECES, "epilogue operands must fit two stages");
@@ -166,7 +167,10 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                 t = t < g.RT ? t : g.RT - 1;
                 base = g.Xq + (size_t)t * KT * TILE_BYTES;
             }
-            gpp[k] = base + (p & 1) * TILE_BYTES;
+            const unsigned long long b = (unsigned long long)(base + (p & 1) * TILE_BYTES);
+            const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b);
+            const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
+            gpp[k] = (const int8_t*)(((unsigned long long)hi << 32) | lo);  // uniform: lives in scalar registers
         }
     };
     set_loader(x0 + pos);
@@ -197,17 +201,23 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         const int c = (ln - 32) < 8 * WB ? (ln - 32) : 0;
         return g.cx + (I0w + c * 8);
     };
-    // request piece k of operand stage v / of epilogue stage e into ring slot `slot`
-    auto dma_k = [&](int v, int slot, int k) {
+    // Request piece k of an operand stage into ring slot `slot`.  vo = byte offset of this lane within the
+    // piece's row tile (stage * 2 KiB + lane * 16), the same for all pieces of a stage.  Uniform 64-bit base
+    // + 32-bit lane offset is the scalar-base form of the load: two instructions per request (LDS address
+    // into M0, the load), no address arithmetic in the K pipeline.
+    auto dma_k = [&](unsigned vo, int slot, int k) {
         int8_t* dst = lds + slot * STAGE + (w * PIECES + k) * TILE_BYTES;
-        // uniform 64-bit base (scalar registers) + 32-bit lane offset: the scalar-base form of the load,
-        // no vector address arithmetic in the K pipeline
-        const unsigned long long b = (unsigned long long)(gpp[k] + (size_t)v * (2 * TILE_BYTES));
-        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b);
-        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
-        const __attribute__((address_space(1))) int8_t* sb =
-            (const __attribute__((address_space(1))) int8_t*)(((unsigned long long)hi << 32) | lo);
-        __builtin_amdgcn_global_load_lds(sb + voff, LPTR(dst), 16, 0, 0);
+        const __attribute__((address_space(1))) int8_t* sb = (const __attribute__((address_space(1))) int8_t*)gpp[k];
+        __builtin_amdgcn_global_load_lds(sb + vo, LPTR(dst), 16, 0, 0);
+    };
+    // The lane offset of operand stage v.  Opaque to the compiler, so that its zero extension stays next to
+    // the loads that use it (hoisted out of the loop, it turns every request into a 64-bit vector add).
+    auto stage_off = [&](int v) {
+        unsigned vo = voff;
+        asm volatile("" : "+v"(vo));  // (nor is voff + constant worth a register of its own across the K loop)
+        vo += (unsigned)v * (2 * TILE_BYTES);
+        asm volatile("" : "+v"(vo));
+        return vo;
     };
     auto dma_e = [&](int e, int slot, int k) {
         int8_t* dst = lds + slot * STAGE + (w * PIECES + k) * TILE_BYTES;
@@ -231,8 +241,9 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     // request all pieces of stage v (operand stage, or epilogue stage v - nst) of the loader tile
     auto issue_stage = [&](int v, int slot) {
         if (v < nst) {
+            const unsigned vo = stage_off(v);
 #pragma unroll
-            for (int k = 0; k < PIECES; k++) dma_k(v, slot, k);
+            for (int k = 0; k < PIECES; k++) dma_k(vo, slot, k);
         } else {
 #pragma unroll
             for (int k = 0; k < PIECES; k++) dma_e(v - nst, slot, k);
@@ -250,16 +261,17 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         // are complete; after the barrier the same holds for every wave.
         STAGE_SYNC((NB - 2) * PIECES);
         FENCE();
-        const int slot = (sbase + st) % NB, nslot = (sbase + st + 1) % NB;
+        const int slot = (unsigned)(sbase + st) % NB, nslot = (unsigned)(sbase + st + 1) % NB;
+        const unsigned vo = MODE == 0 ? stage_off(st + NB) : 0u;
 #pragma unroll
         for (int i = 0; i < NMFMA; i++) {
             const int c = i / (WA * WB), a = (i / WB) % WA, b = i % WB;
             acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(RP[SS][c][a], RQ[SS][c][b], acc[a][b], 0, 0, 0);
             FENCE();
 #pragma unroll
-            for (int q = i * NOPS / NMFMA; q < (i + 1) * NOPS / NMFMA; q++) {
+            for (int q = (i < OPSPAN ? i : OPSPAN) * NOPS / OPSPAN; q < (i + 1 < OPSPAN ? i + 1 : OPSPAN) * NOPS / OPSPAN; q++) {
                 if (q < PIECES) {
-                    if (MODE == 0) dma_k(st + NB, slot, q);
+                    if (MODE == 0) dma_k(vo, slot, q);
                     if (MODE == 1 || MODE == 2) dma_e(MODE - 1, slot, q);
                 } else if (MODE != 4) {
                     rd(std::integral_constant<int, 1 - SS>{}, nslot, q - PIECES);
