@@ -205,3 +205,20 @@ def test_granularity_argument_errors():
         assert lib.llmint8_quantize_rows_granular(p(X), 4, 64, p(idx), p(idx), 16, g, p(Xq), p(cx), p(Xo), None) == 1
     assert lib.llmint8_quantize_rows_granular(p(X), 4, 64, p(idx), p(idx), 16, 2, p(Xq), p(cx), p(Xo), None) == 0
     torch.cuda.synchronize()
+
+
+def test_random_shapes():
+    """Seeded random shapes, granularities and thresholds on both GEMM paths against the oracle."""
+    rng = np.random.default_rng(20240612)
+    for case in range(16):
+        s = int(rng.choice([rng.integers(1, 33), rng.integers(33, 300)]))
+        h = int(rng.choice([8 * rng.integers(4, 200), rng.integers(20, 1200)]))
+        o = int(rng.choice([8 * rng.integers(2, 80), rng.integers(9, 500)]))
+        ncol = int(rng.integers(0, min(h, 20)))
+        mode = str(rng.choice(["rowwise", "tensorwise"]))
+        alpha = float(rng.choice([6.0, 6.0, INF]))
+        d = wl.make_custom(s, h, o, ncol, seed=3000 + case)
+        try:
+            granular_compare(d, mode, alpha)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: s={s} h={h} o={o} ncol={ncol} {mode} alpha={alpha}: {e}") from e

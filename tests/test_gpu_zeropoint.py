@@ -221,3 +221,24 @@ def test_argument_errors_are_reported_not_executed():
     assert lib.llmint8_zp_quantize_rows(p(X), 4, 64, p(idx), p(idx), 16, p(Xq), p(off), p(Xo), None) == INVALID
     assert lib.llmint8_zp_linear(p(X), 4, 64, 6.0, p(Wq), p(zw), p(W), 32, p(idx), 16, p(idx), None, p(Xq), p(zx),
                                  p(Xo), p(out), p(ws.buf), 64, None) == WORKSPACE
+
+
+def test_random_shapes():
+    """Seeded random shapes on both GEMM paths, aligned and ragged, random numbers of outlier columns,
+    one-sided and shifted inputs, with and without the decomposition: every stage against the oracle."""
+    rng = np.random.default_rng(20240611)
+    for case in range(16):
+        s = int(rng.choice([rng.integers(1, 33), rng.integers(33, 300)]))
+        h = int(rng.choice([8 * rng.integers(4, 200), rng.integers(20, 1200)]))
+        o = int(rng.choice([8 * rng.integers(2, 80), rng.integers(9, 500)]))
+        ncol = int(rng.integers(0, min(h, 20)))
+        alpha = float(rng.choice([6.0, 6.0, INF]))
+        shift = float(rng.choice([0.0, 0.0, 1.5, -0.75]))
+        d = wl.make_custom(s, h, o, ncol, seed=2000 + case)
+        X = one_sided(d, shift)
+        if len(oracle.find_outliers(X, alpha)) > 32:
+            continue
+        try:
+            zp_compare(X, d["W"], alpha)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: s={s} h={h} o={o} ncol={ncol} alpha={alpha} shift={shift}: {e}") from e
