@@ -81,3 +81,27 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "single-GPU" in r.stderr
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/llmint8.h is a C header: a C99 translation unit that includes it and links against the
+    library builds with no warning, and its size functions agree with the Python binding's."""
+    import subprocess
+
+    import paper_2208_07339_amd as L
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "llmint8.h"\n'
+        "int main(void) {\n"
+        '    printf("%d %zu %zu %zu %s\\n", llmint8_opad(20), llmint8_wq_bytes(300, 70), llmint8_xq_bytes(33, 300),\n'
+        "           llmint8_workspace_bytes(33, 300, 70, 20), llmint8_status_string(LLMINT8_WORKSPACE));\n"
+        "    return llmint8_quantize_rows(0, 1, 1, 0, 0, 1, 0, 0, 0, 0) == LLMINT8_INVALID_ARG ? 0 : 1;\n"
+        "}\n")
+    exe = tmp_path / "use_header"
+    lib_dir = os.path.dirname(L.LIB_PATH)
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+           "-o", str(exe), "-L", lib_dir, "-lllmint8", "-Wl,-rpath," + lib_dir]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 4)
+    assert int(out[0]) == L.opad(20) and int(out[1]) == L.wq_bytes(300, 70) and int(out[2]) == L.xq_bytes(33, 300)
+    assert int(out[3]) == L.workspace_bytes(33, 300, 70, 20) and out[4].strip()
