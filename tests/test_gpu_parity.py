@@ -478,3 +478,41 @@ def test_smallest_dimensions(s, h, o, ncol):
     torch.cuda.synchronize()
     assert np.array_equal(Cd.cpu().numpy(), ref["C"])
     assert_out_close(out.cpu().numpy(), ref["Out"])
+
+
+def test_calls_on_two_streams_with_their_own_workspaces_do_not_disturb_each_other():
+    """The library keeps no state between calls: two streams, each with its own inputs, buffers and
+    workspace, issue their calls interleaved (a tiled-path call next to a weight-streaming one, so that
+    kernels of both are in flight together); every output is what the oracle gives for its own input."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    cap = 32
+    jobs = []
+    for (s, h, o, ncol, seed) in [(300, 1024, 768, 4, 1), (16, 4096, 1024, 6, 2)]:
+        d = wl.make_custom(s, h, o, ncol, seed=seed)
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            Xd = torch.from_numpy(d["X"].view(np.int16)).cuda().view(torch.float16)
+            Wd = torch.from_numpy(d["W"].view(np.int16)).cuda().view(torch.float16)
+            ws = L.Workspace.allocate(s, h, o, cap)
+            qw = L.quantize_weight(Wd, ws)
+            outl = L.Outliers(torch.zeros(cap, dtype=torch.int32, device="cuda"),
+                              torch.zeros(1, dtype=torch.int32, device="cuda"),
+                              torch.zeros(1, dtype=torch.int32, device="cuda"), cap)
+            rows = L.QuantizedRows(torch.zeros(L.xq_bytes(s, h), dtype=torch.int8, device="cuda"),
+                                   torch.zeros(s, dtype=torch.float16, device="cuda"),
+                                   torch.zeros((s, L.opad(cap)), dtype=torch.float16, device="cuda"), s, h)
+            outs = [torch.zeros((s, o), dtype=torch.float16, device="cuda") for _ in range(6)]
+        jobs.append(dict(d=d, st=st, Xd=Xd, qw=qw, ws=ws, outl=outl, rows=rows, outs=outs))
+    torch.cuda.synchronize()
+    for k in range(6):
+        for j in jobs:
+            with torch.cuda.stream(j["st"]):
+                L.linear(j["Xd"], j["qw"], 6.0, j["outl"], j["rows"], j["ws"], out=j["outs"][k])
+    torch.cuda.synchronize()
+    for j in jobs:
+        ref = oracle.linear(j["d"]["X"], j["d"]["W"], 6.0)
+        for out in j["outs"]:
+            assert_out_close(out.cpu().numpy(), ref["Out"])
+        assert np.array_equal(bits(j["rows"].cx.cpu().numpy()), bits(ref["cx"]))
