@@ -1,9 +1,13 @@
-"""HIP path vs CPU oracle at the full benchmark sizes, in the launch
-configuration the bench times.  The oracle cannot multiply these matrices in
-full within a test, so: the outlier set, every row constant, every column
-constant and both int8 tensors are compared in full; the int32 accumulators
-and fp16 outputs are compared on whole rows at tile edges and on random
-samples the oracle computes one by one from the definition."""
+"""HIP path vs CPU oracle at the full benchmark sizes.  The oracle cannot
+multiply these matrices in full within a test, so: the outlier set, every row
+constant, every column constant and both int8 tensors are compared in full;
+the int32 accumulators and fp16 outputs are compared on whole rows at tile
+edges and on random samples the oracle computes one by one from the
+definition.  Two runs per size: the staged calls with the accumulator export
+(which sends every tile of the prefill GEMM through its guarded epilogue), and
+llmint8_linear exactly as bench.py calls it (automatic tile shape, no export:
+interior tiles take the epilogue fed from LDS), whose outputs and intermediate
+buffers are held to the same comparisons."""
 import numpy as np
 import pytest
 
@@ -44,6 +48,35 @@ def check_config(name, edge_rows, nsample=1500):
     assert_out_close(g["Out"][ri, ci], Os, scale)
     # property that holds at any size: outputs are finite and not all zero
     assert np.isfinite(g["Out"].astype(np.float32)).all() and g["Out"].any()
+
+    # ---- the one-call path in the configuration bench.py times, into fresh buffers
+    import torch
+
+    import paper_2208_07339_amd as L
+    cap = 32
+    outl = L.Outliers(torch.full((cap,), -7, dtype=torch.int32, device="cuda"),
+                      torch.full((1,), -7, dtype=torch.int32, device="cuda"),
+                      torch.full((1,), -7, dtype=torch.int32, device="cuda"), cap)
+    qrows = L.QuantizedRows(torch.full((L.xq_bytes(s, h),), 99, dtype=torch.int8, device="cuda"),
+                            torch.full((s,), 7.0, dtype=torch.float16, device="cuda"),
+                            torch.full((s, L.opad(cap)), 7.0, dtype=torch.float16, device="cuda"), s, h)
+    out = torch.full((s, o), 7.0, dtype=torch.float16, device="cuda")
+    for _ in range(2):
+        L.linear(g["Xd"], g["qw"], d["alpha"], outl, qrows, g["ws"], out=out)
+    torch.cuda.synchronize()
+    n = int(outl.count.item())
+    assert int(outl.status.item()) == 0 and outl.idx[:n].cpu().numpy().tolist() == idx.tolist()
+    assert np.array_equal(bits(qrows.cx.cpu().numpy()), bits(cx))
+    assert np.array_equal(L.export_rows(qrows).cpu().numpy(), Xq)
+    Xo = qrows.Xo.cpu().numpy()
+    assert np.array_equal(bits(Xo[:, :n]), bits(X[:, idx])) and not bits(Xo[:, n:]).any()
+    lin = out.cpu().numpy()
+    assert_out_close(lin[rows], ref["Out"], scale)
+    assert_out_close(lin[ri, ci], Os, scale)
+    # every output of the one-call path against the staged path's (the same arithmetic in another
+    # epilogue: they may differ in the order of the fp32 sums of the outlier product only)
+    assert_out_close(lin, g["Out"], scale)
+    assert np.isfinite(lin.astype(np.float32)).all()
 
 
 def test_decode_175b_ffn_up():

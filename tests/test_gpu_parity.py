@@ -71,6 +71,60 @@ def test_every_prefill_tile_shape(cfg, forced_tile):
     full_compare(wl.make_custom(330, 128, 264, 0, seed=6))
 
 
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+def test_every_prefill_tile_shape_through_the_one_call_path(cfg, forced_tile):
+    """llmint8_linear exports no accumulators, so interior tiles take the epilogue that is fed from LDS and
+    stores without guards: the code the bench times.  Every workgroup tile, vector-wise constants (a wrong
+    index into the staged c_x / c_w / Xo / W rows would show), on shapes with o % 8 == 0 whose grids have
+    interior tiles next to edge tiles: 7 and 20 outlier columns (one and two fp16 k-steps), a 16-slot outlier
+    buffer (opad = 16), a wide ragged grid, no outlier column at all, and more columns than the buffer takes."""
+    forced_tile(cfg)
+    linear_compare(wl.make_custom(512, 2048, 1024, 7, seed=61))             # every tile interior (cfg 0: 2 x 4)
+    linear_compare(wl.make_custom(600, 640, 776, 20, seed=62))              # interior + edge in both directions
+    linear_compare(wl.make_custom(256, 256, 512, 3, seed=63), cap=8)        # opad = 16
+    linear_compare(wl.make_custom(520, 384, 1544, 12, seed=64), cap=16)     # opad = 16, wide grid, ragged edges
+    linear_compare(wl.make_custom(384, 512, 768, 0, seed=65))               # no outlier product
+    linear_compare(wl.make_custom(320, 256, 640, 9, seed=66), cap=4)        # |O| > cap: the first four only
+    linear_compare(wl.make_custom(512, 1152, 576, 30, seed=67))             # nearly full 32-slot buffer
+
+
+@pytest.mark.parametrize("s,o", [(8, 64), (40, 96), (300, 264)])
+def test_accumulator_at_the_int32_bound(s, o):
+    """Section 2.1: the int8 products are accumulated as 32-bit integers.  At the largest feature dimension
+    the library accepts (h = 133 144) with every code at +-127 the accumulator reaches h * 127^2 =
+    2 147 479 576 = 2^31 - 4 072: weight-streaming path (s = 8) and tiled path (s = 40, 300), k-tile padding
+    included, and the dequantization of a value that large."""
+    import paper_2208_07339_amd as L
+    h = 133144
+    X = np.full((s, h), 1.0, np.float16)
+    X[1::2] = -0.5                                   # odd tokens: codes -127, constant 0.5
+    W = np.full((h, o), 0.25, np.float16)
+    W[:, 1::3] = -0.125                              # every third column: codes -127, constant 0.125
+    g = run_hip(X, W, 6.0, 32)
+    assert g["count"] == 0
+    sign = np.where(np.arange(s) % 2 == 1, -1, 1)[:, None] * np.where(np.arange(o) % 3 == 1, -1, 1)[None, :]
+    want = (sign * (h * 16129)).astype(np.int64)
+    assert want.max() == 2147479576 and want.min() == -2147479576
+    assert np.array_equal(g["C"].astype(np.int64), want)
+    Xq, cx = oracle.quantize_rows(X, np.zeros(0, np.int32))
+    Wq, cw = oracle.quantize_weight(W)
+    assert np.all(np.abs(Xq) == 127) and np.all(np.abs(Wq) == 127)
+    assert np.array_equal(g["Xq"], Xq) and np.array_equal(hip_weight_i8(g["qw"]), Wq)
+    rows = np.arange(min(s, 4))
+    Cm = oracle.igemm(np.ascontiguousarray(Xq[rows]), Wq)
+    assert np.array_equal(Cm.astype(np.int64), want[rows])
+    ref = oracle.output(Cm, cx[rows], cw, np.ascontiguousarray(X[rows]), W, np.zeros(0, np.int32))
+    assert_out_close(g["Out"][rows], ref)
+    # closed form for all rows: Out = h * c_x * c_w with the signs, exactly representable products
+    closed = want / 16129.0 * cx.astype(np.float64)[:, None] * cw.astype(np.float64)[None, :]
+    assert_out_close(g["Out"], closed.astype(np.float16))
+    # and through the one-call path (no accumulator export: the LDS-fed epilogue where tiles are interior)
+    import torch
+    out = L.linear(g["Xd"], g["qw"], 6.0, g["outl"], g["rows"], g["ws"])
+    torch.cuda.synchronize()
+    assert_out_close(out.cpu().numpy(), closed.astype(np.float16))
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_every_decode_work_split(cfg):
     import paper_2208_07339_amd as L
