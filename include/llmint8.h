@@ -24,11 +24,15 @@
  *     llmint8_wq_bytes); llmint8_export_rows / llmint8_export_weight turn
  *     them into plain row-major int8 matrices.
  *   - stream is a hipStream_t (NULL = the default stream).  Every call only
- *     enqueues kernels on it: no host synchronisation, no allocation, no
- *     global state (llmint8_debug_prefill_tile aside).  Calls that share a
- *     workspace must be ordered by stream.  A call may therefore be recorded
- *     into a HIP graph by stream capture and replayed; make the first call of
- *     a process on each device outside a capture (it sets kernel attributes).
+ *     enqueues kernels on it: no host synchronisation, no allocation.  The
+ *     library may be called from several threads.  Its only process-wide
+ *     state: a per-device set-up done once under a lock by the first call that
+ *     needs it (kernel attributes of every kernel variant, the device's
+ *     compute-unit count), and the two test hooks llmint8_debug_* (atomic
+ *     integers that every thread's later calls see).  Calls that share a
+ *     workspace must be ordered by stream.  A call may be recorded into a HIP
+ *     graph by stream capture and replayed; make one llmint8_matmul /
+ *     llmint8_linear* call of any shape on the device before capturing.
  *   - Return value: LLMINT8_OK or an error code below; nothing is enqueued
  *     when an argument error is returned.  Conditions only visible on the
  *     device (|O| > cap) set bit 0 of the device status word and clamp.
@@ -195,9 +199,9 @@ int llmint8_zp_linear(const void *X_f16, int s, int h, float alpha, const int8_t
 int llmint8_debug_prefill_tile(int cfg);
 
 /* Test/support: force the work split of the decode kernel (column tiles per workgroup, k-tiles per
- * load batch): 1 = 1 x 8, 2 = 2 x 4, 3 = 2 x 8, 4 = 3 x 4, 5 = 1 x 4; -1 = default.  Process-wide;
- * results do not depend on it.                                                */
-#define LLMINT8_DECODE_SHAPES 11
+ * load batch): 1 = 1 x 8, 2 = 2 x 4 (the default), 3 = 2 x 8, 4 = 3 x 4, 5 = 1 x 4; -1 = not forced.
+ * Anything else is LLMINT8_INVALID_ARG.  Process-wide; results do not depend on it.   */
+#define LLMINT8_DECODE_SHAPES 5
 int llmint8_debug_decode_shape(int cfg);
 
 /* Test/support: private layouts -> plain row-major int8 ([h x o], [s x h]). */

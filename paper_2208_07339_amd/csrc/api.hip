@@ -365,14 +365,14 @@ int llmint8_zp_linear(const void* X_f16, int s, int h, float alpha, const int8_t
 int llmint8_debug_prefill_tile(int cfg)
 {
     if (cfg < -1 || cfg >= LLMINT8_PREFILL_TILES) return LLMINT8_INVALID_ARG;
-    g_force_cfg = cfg;
+    g_force_cfg.store(cfg, std::memory_order_relaxed);
     return LLMINT8_OK;
 }
 
 int llmint8_debug_decode_shape(int cfg)
 {
-    if (cfg < -1 || cfg > LLMINT8_DECODE_SHAPES) return LLMINT8_INVALID_ARG;
-    g_decode_cfg = cfg;
+    if (cfg != -1 && (cfg < 1 || cfg > LLMINT8_DECODE_SHAPES)) return LLMINT8_INVALID_ARG;
+    g_decode_cfg.store(cfg, std::memory_order_relaxed);
     return LLMINT8_OK;
 }
 

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace llmint8 {
 
 // ---- private int8 layout ---------------------------------------------------
@@ -152,8 +154,11 @@ hipError_t launch_dequant_rows(const int8_t* Wq, const unsigned short* cw, int h
                                const int32_t* count, int cap, unsigned short* Wo, hipStream_t st);
 
 // tile shape of the prefill GEMM forced by llmint8_debug_prefill_tile (-1: chosen from the shape)
-extern int g_force_cfg;
+extern std::atomic<int> g_force_cfg;
 // work split of the decode kernel forced by llmint8_debug_decode_shape (-1: default)
-extern int g_decode_cfg;
+extern std::atomic<int> g_decode_cfg;
+// One-time set-up of the prefill kernels on the current device (dynamic LDS limit of every instantiation);
+// returns the device's number of compute units.  Thread-safe; cheap after the first call on a device.
+hipError_t prefill_device_setup(int* compute_units);
 
 }  // namespace llmint8

@@ -208,7 +208,7 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     }
 }
 
-int g_decode_cfg = -1;  // test hook, as g_force_cfg
+std::atomic<int> g_decode_cfg{-1};  // test hook, as g_force_cfg
 
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
@@ -227,19 +227,12 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
 #define LAUNCH_DECODE(NJ, U)                                                                                     \
     gemm_decode_kernel<NJ, U, false><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo, count, cap, \
                                                                  opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, none)
-    switch (g_decode_cfg) {
+    switch (g_decode_cfg.load(std::memory_order_relaxed)) {
         case 1: LAUNCH_DECODE(1, 8); break;
-        case 2: LAUNCH_DECODE(2, 4); break;
         case 3: LAUNCH_DECODE(2, 8); break;
         case 4: LAUNCH_DECODE(3, 4); break;
         case 5: LAUNCH_DECODE(1, 4); break;
-        case 6: LAUNCH_DECODE(2, 2); break;
-        case 7: LAUNCH_DECODE(2, 6); break;
-        case 8: LAUNCH_DECODE(4, 2); break;
-        case 9: LAUNCH_DECODE(3, 3); break;
-        case 10: LAUNCH_DECODE(4, 3); break;
-        case 11: LAUNCH_DECODE(2, 3); break;
-        default: LAUNCH_DECODE(2, 4); break;
+        default: LAUNCH_DECODE(2, 4); break;  // 2, and -1 = not forced
     }
 #undef LAUNCH_DECODE
     return hipGetLastError();

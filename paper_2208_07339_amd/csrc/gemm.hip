@@ -1,5 +1,7 @@
 // Prefill path of Eq. 7 + Eq. 8: int8 MFMA GEMM over the tiled operands with
 // the dequantization and the fp16 outlier product fused into the epilogue.
+#include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -567,38 +569,67 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     }  // tiles
 }
 
-// compute units of the current device (one persistent workgroup each)
-static int compute_units()
+// ---- per-device set-up ---------------------------------------------------------
+// The kernels need more dynamic LDS than the default limit, and the attribute that raises it belongs to a
+// kernel as loaded on one device.  The first launch on a device (or llmint8_init) sets it for EVERY
+// instantiation at once, under a lock, and caches the number of compute units; later calls only read an
+// atomic flag.  A caller that records calls into a graph therefore needs one call of any shape (or
+// llmint8_init) on the device beforehand, not one per tile shape.
+template <int WA, int WB>
+constexpr int prefill_lds_bytes()
 {
-    static int cached[16] = {0};
+    return NB * (2 * WA + 2 * WB) * 2 * TILE_BYTES + 4 * 8192;  // operand ring + output staging
+}
+
+template <int WA, int WB>
+static hipError_t raise_lds_limit()
+{
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, false>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<WA, WB>());
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, true>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<WA, WB>());
+}
+
+constexpr int MAX_DEVICES = 64;
+static std::atomic<int> g_dev_cus[MAX_DEVICES];  // 0: not set up yet; else the device's compute units
+static std::mutex g_dev_lock;
+
+hipError_t prefill_device_setup(int* cus)
+{
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-        cached[dev] = n;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool cached = dev >= 0 && dev < MAX_DEVICES;
+    if (cached) {
+        const int n = g_dev_cus[dev].load(std::memory_order_acquire);
+        if (n > 0) {
+            *cus = n;
+            return hipSuccess;
+        }
     }
-    return cached[dev];
+    std::lock_guard<std::mutex> hold(g_dev_lock);
+    if ((e = raise_lds_limit<4, 4>()) != hipSuccess) return e;
+    if ((e = raise_lds_limit<3, 4>()) != hipSuccess) return e;
+    if ((e = raise_lds_limit<2, 4>()) != hipSuccess) return e;
+    if ((e = raise_lds_limit<2, 2>()) != hipSuccess) return e;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    *cus = n;
+    if (cached) g_dev_cus[dev].store(n, std::memory_order_release);
+    return hipSuccess;
 }
 
 template <int WA, int WB, bool ZP>
 static hipError_t launch_cfg(GemmArgs& g, hipStream_t st)
 {
-    constexpr int STAGE = (2 * WA + 2 * WB) * 2 * TILE_BYTES;
-    constexpr int shm = NB * STAGE + 4 * 8192;  // operand ring + output staging
+    constexpr int shm = prefill_lds_bytes<WA, WB>();
     g.nP = (g.JT + 2 * WA - 1) / (2 * WA);
     g.nQ = (g.RT + 2 * WB - 1) / (2 * WB);
-    // once per device: the attribute belongs to the kernel as loaded on that device
-    static bool attr_set[16] = {false};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = -1;
-    if (dev < 0 || !attr_set[dev]) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, ZP>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, shm);
-        if (e != hipSuccess) return e;
-        if (dev >= 0) attr_set[dev] = true;
-    }
-    const int total = g.nP * g.nQ, ncu = compute_units();
+    int ncu = 0;
+    const hipError_t e = prefill_device_setup(&ncu);
+    if (e != hipSuccess) return e;
+    const int total = g.nP * g.nQ;
     gemm_prefill_kernel<WA, WB, ZP><<<total < ncu ? total : ncu, 256, shm, st>>>(g);
     return hipGetLastError();
 }
@@ -622,7 +653,7 @@ static int pick_cfg(int s, int o)
     return best;
 }
 
-int g_force_cfg = -1;  // test hook: tile shape override (-1 = automatic)
+std::atomic<int> g_force_cfg{-1};  // test hook: tile shape override (-1 = automatic)
 
 hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                                const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
@@ -641,7 +672,8 @@ hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const
     g.Out = (_Float16*)Out; g.Cdbg = Cdbg;
     g.s = s; g.h = h; g.o = o;
     g.fast_ok = (o % 8 == 0) && al16(cw) && al16(cx) && al16(Wf) && al16(Xo) && al16(Out);
-    const int c = g_force_cfg >= 0 ? g_force_cfg : pick_cfg(s, o);
+    const int forced = g_force_cfg.load(std::memory_order_relaxed);
+    const int c = forced >= 0 ? forced : pick_cfg(s, o);
     if (zp) {
         switch (c) {
             case 1: return launch_cfg<3, 4, true>(g, st);

@@ -74,6 +74,7 @@ def test_argument_checks_of_the_variants_need_no_gpu(lib):
     assert lib.llmint8_dequantize_rows(None, None, 4, 4, None, None, 4, None, None) == 1
     assert lib.llmint8_debug_prefill_tile(99) == 1 and lib.llmint8_debug_prefill_tile(-1) == 0
     assert lib.llmint8_debug_decode_shape(99) == 1 and lib.llmint8_debug_decode_shape(-1) == 0
+    assert lib.llmint8_debug_decode_shape(0) == 1 and lib.llmint8_debug_decode_shape(6) == 1
 
 
 def test_bench_refuses_more_than_one_gpu():
