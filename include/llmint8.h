@@ -26,13 +26,14 @@
  *   - stream is a hipStream_t (NULL = the default stream).  Every call only
  *     enqueues kernels on it: no host synchronisation, no allocation.  The
  *     library may be called from several threads.  Its only process-wide
- *     state: a per-device set-up done once under a lock by the first call that
- *     needs it (kernel attributes of every kernel variant, the device's
- *     compute-unit count), and the two test hooks llmint8_debug_* (atomic
+ *     state: a per-device set-up done once under a lock (kernel attributes of
+ *     every kernel variant, the device's compute-unit count, the address of
+ *     the static scratch of llmint8_linear_static), by llmint8_init or by the
+ *     first call that needs it; and the two test hooks llmint8_debug_* (atomic
  *     integers that every thread's later calls see).  Calls that share a
  *     workspace must be ordered by stream.  A call may be recorded into a HIP
- *     graph by stream capture and replayed; make one llmint8_matmul /
- *     llmint8_linear* call of any shape on the device before capturing.
+ *     graph by stream capture and replayed; call llmint8_init (or any
+ *     llmint8_matmul / llmint8_linear*) on the device once before capturing.
  *   - Return value: LLMINT8_OK or an error code below; nothing is enqueued
  *     when an argument error is returned.  Conditions only visible on the
  *     device (|O| > cap) set bit 0 of the device status word and clamp.
@@ -52,7 +53,8 @@ enum {
     LLMINT8_INVALID_ARG = 1, /* null pointer, non-positive dimension, cap < 1, unknown granularity */
     LLMINT8_SHAPE = 2,       /* h > LLMINT8_MAX_H, or a size beyond 2^31 elements per row block */
     LLMINT8_WORKSPACE = 3,   /* workspace smaller than llmint8_workspace_bytes() */
-    LLMINT8_HIP = 4          /* a kernel launch failed (hipGetLastError) */
+    LLMINT8_HIP = 4,         /* a kernel launch failed (hipGetLastError) */
+    LLMINT8_STATIC_LIMIT = 5 /* llmint8_linear_static: the sizes need more than LLMINT8_STATIC_SCRATCH_BYTES */
 };
 
 /* Largest feature dimension whose int32 accumulator cannot overflow:
@@ -64,6 +66,11 @@ typedef void *llmint8_stream_t;
 const char *llmint8_status_string(int status);
 /* Text of the HIP error behind the calling thread's most recent LLMINT8_HIP return. */
 const char *llmint8_last_hip_error(void);
+
+/* Per-device set-up for the CURRENT device (hipSetDevice), done once: kernel attributes of every
+ * kernel variant and the address of the static scratch.  Optional (the first call that needs it does the
+ * same), thread-safe, cheap when repeated.  Call it outside stream capture. */
+int llmint8_init(void);
 
 /* Leading dimension (in fp16 elements) of the gathered-outlier matrix Xo for a
  * given capacity: cap rounded up to a multiple of 16. */
@@ -133,6 +140,21 @@ int llmint8_linear(const void *X_f16, int s, int h, float alpha, const int8_t *W
                    const void *W_f16, int o, int32_t *idx, int cap, int32_t *count, int32_t *status,
                    int8_t *Xq, void *cx_f16, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
                    llmint8_stream_t stream);
+
+/* llmint8_linear for callers that cannot allocate and have no workspace to hand over (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the scratch is a static
+ * device array inside the library, LLMINT8_STATIC_SCRATCH_BYTES per GPU that uses the library, held
+ * until the process ends.  Same arguments as llmint8_linear without ws / ws_bytes, same kernels, same
+ * results bit for bit.  Returns LLMINT8_STATIC_LIMIT, with nothing enqueued, when
+ * llmint8_workspace_bytes(s, h, o, cap) exceeds LLMINT8_STATIC_SCRATCH_BYTES (every benchmark shape fits).
+ * Calls no hipMalloc / hipFree or any allocating routine.  All calls on one GPU share that GPU's array:
+ * calls that may overlap on one GPU (different streams, different threads) race on it and must be
+ * ordered by the caller; nothing in it needs clearing between calls.  The first call on a device looks
+ * the array's address up (hipGetSymbolAddress): make it, or llmint8_init, outside stream capture. */
+#define LLMINT8_STATIC_SCRATCH_BYTES (16u << 20)
+int llmint8_linear_static(const void *X_f16, int s, int h, float alpha, const int8_t *Wq, const void *cw_f16,
+                          const void *W_f16, int o, int32_t *idx, int cap, int32_t *count, int32_t *status,
+                          int8_t *Xq, void *cx_f16, void *Xo_f16, void *Out_f16, llmint8_stream_t stream);
 
 /* Baselines of Table 1: the same calls with coarser absmax constants.
  *   LLMINT8_VECTORWISE  one constant per row of X and per column of W (Section 3.1; the calls above)

@@ -10,6 +10,7 @@ SYMBOLS = [
     "llmint8_status_string", "llmint8_last_hip_error", "llmint8_opad", "llmint8_wq_bytes", "llmint8_xq_bytes",
     "llmint8_workspace_bytes", "llmint8_quantize_weight", "llmint8_find_outliers",
     "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_linear_events", "llmint8_dequantize_rows",
+    "llmint8_init", "llmint8_linear_static",
     "llmint8_quantize_weight_granular", "llmint8_quantize_rows_granular", "llmint8_linear_granular",
     "llmint8_zp_quantize_weight", "llmint8_zp_quantize_rows", "llmint8_zp_matmul", "llmint8_zp_linear",
     "llmint8_export_weight",
@@ -59,6 +60,10 @@ def lib():
     L.llmint8_matmul.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     L.llmint8_linear.restype = i32
     L.llmint8_linear.argtypes = [vp, i32, i32, f32, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.llmint8_init.restype = i32
+    L.llmint8_init.argtypes = []
+    L.llmint8_linear_static.restype = i32
+    L.llmint8_linear_static.argtypes = [vp, i32, i32, f32, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp]
     L.llmint8_dequantize_rows.restype = i32
     L.llmint8_dequantize_rows.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, vp]
     L.llmint8_quantize_weight_granular.restype = i32
@@ -253,6 +258,24 @@ def linear(X, qw, alpha, outl, rows, ws, out=None, events=None, granularity="vec
         _check(lib().llmint8_linear(*head, *tail))
     else:
         _check(lib().llmint8_linear_granular(*head, g, *tail))
+    return out
+
+
+STATIC_SCRATCH_BYTES = 16 << 20  # LLMINT8_STATIC_SCRATCH_BYTES
+
+
+def init():
+    """llmint8_init: per-device set-up of the current device (optional; the first call does the same)."""
+    _check(lib().llmint8_init())
+
+
+def linear_static(X, qw, alpha, outl, rows, out):
+    """llmint8_linear_static: llmint8_linear on the library's static scratch; every buffer is the caller's,
+    nothing is allocated (out is required)."""
+    s, h = X.shape
+    _check(lib().llmint8_linear_static(_ptr(X), s, h, float(alpha), _ptr(qw.Wq), _ptr(qw.cw), _ptr(qw.W), qw.o,
+                                       _ptr(outl.idx), outl.cap, _ptr(outl.count), _ptr(outl.status), _ptr(rows.Xq),
+                                       _ptr(rows.cx), _ptr(rows.Xo), _ptr(out), _stream()))
     return out
 
 

@@ -1,6 +1,8 @@
 // C-ABI entry points of libllmint8: argument checks, workspace carving and the
 // kernel sequences.  Declarations and argument contracts: include/llmint8.h.
+#include <atomic>
 #include <cmath>
+#include <mutex>
 
 #include "../../include/llmint8.h"
 #include "common.h"
@@ -43,6 +45,41 @@ inline int hip_status(hipError_t e)
 
 }  // namespace
 
+// Scratch of llmint8_linear_static: one array per device that loads this library, held until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address it yields
+// (per device, looked up once with that device current) is what kernels and host calls are given.
+static __device__ __align__(256) unsigned char scratch[LLMINT8_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int SCRATCH_DEVICES = 64;
+std::atomic<void*> g_scratch_ptr[SCRATCH_DEVICES];
+std::mutex g_scratch_lock;
+
+// device address of `scratch` on the current device
+hipError_t static_scratch(void** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= SCRATCH_DEVICES) return hipErrorInvalidDevice;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> hold(g_scratch_lock);
+        p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+        if (!p) {
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (!p) return hipErrorInvalidSymbol;
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return hipSuccess;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* llmint8_status_string(int status)
@@ -53,6 +90,9 @@ const char* llmint8_status_string(int status)
         case LLMINT8_SHAPE: return "unsupported shape (feature dimension above the int32 accumulation bound)";
         case LLMINT8_WORKSPACE: return "workspace too small";
         case LLMINT8_HIP: return "HIP launch error";
+        case LLMINT8_STATIC_LIMIT:
+            return "sizes need more scratch than the library's static buffer holds (use the entry point that "
+                   "takes a caller's workspace)";
         default: return "unknown status";
     }
 }
@@ -284,6 +324,33 @@ int llmint8_linear_events(const void* X_f16, int s, int h, float alpha, int gran
     return linear_impl(X_f16, s, h, alpha, granularity, Wq, cw_f16, W_f16, o, idx, cap, count, status, Xq, cx_f16,
                        Xo_f16, Out_f16, ws, ws_bytes, stream, (hipEvent_t)ev_before_matmul,
                        (hipEvent_t)ev_after_matmul);
+}
+
+// ---- one-time set-up, and the entry point that allocates nothing --------------
+
+int llmint8_init(void)
+{
+    int cus = 0;
+    hipError_t e = prefill_device_setup(&cus);
+    if (e != hipSuccess) return hip_status(e);
+    void* p = nullptr;
+    return hip_status(static_scratch(&p));
+}
+
+int llmint8_linear_static(const void* X_f16, int s, int h, float alpha, const int8_t* Wq, const void* cw_f16,
+                          const void* W_f16, int o, int32_t* idx, int cap, int32_t* count, int32_t* status, int8_t* Xq,
+                          void* cx_f16, void* Xo_f16, void* Out_f16, llmint8_stream_t stream)
+{
+    if (s < 1 || h < 1 || o < 1 || cap < 1) return LLMINT8_INVALID_ARG;
+    if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
+    if (llmint8_workspace_bytes(s, h, o, cap) > (size_t)LLMINT8_STATIC_SCRATCH_BYTES) return LLMINT8_STATIC_LIMIT;
+    void* p = nullptr;
+    const hipError_t e = static_scratch(&p);
+    if (e != hipSuccess) return hip_status(e);
+    // Nothing in the scratch has to start at zero: every kernel of the sequence reads only what a kernel
+    // earlier in the same call wrote (list counts and entries, slab maxima, partial row maxima, rebuilt rows).
+    return linear_impl(X_f16, s, h, alpha, LLMINT8_VECTORWISE, Wq, cw_f16, W_f16, o, idx, cap, count, status, Xq,
+                       cx_f16, Xo_f16, Out_f16, p, (size_t)LLMINT8_STATIC_SCRATCH_BYTES, stream, nullptr, nullptr);
 }
 
 // ---- zeropoint variant ------------------------------------------------------

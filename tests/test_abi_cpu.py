@@ -75,6 +75,19 @@ def test_argument_checks_of_the_variants_need_no_gpu(lib):
     assert lib.llmint8_debug_prefill_tile(99) == 1 and lib.llmint8_debug_prefill_tile(-1) == 0
     assert lib.llmint8_debug_decode_shape(99) == 1 and lib.llmint8_debug_decode_shape(-1) == 0
     assert lib.llmint8_debug_decode_shape(0) == 1 and lib.llmint8_debug_decode_shape(6) == 1
+    # the entry point on the static scratch: sizes are checked before anything touches a device
+    f = C.c_float(6.0)
+    assert lib.llmint8_linear_static(None, 0, 4, f, None, None, None, 4, None, 4, *([None] * 7)) == 1
+    assert lib.llmint8_linear_static(None, 4, 133145, f, None, None, None, 4, None, 4, *([None] * 7)) == 2
+    assert lib.llmint8_linear_static(None, 64, 64, f, None, None, None, 1 << 20, None, 32, *([None] * 7)) == 5
+    assert b"static" in lib.llmint8_status_string(5)
+
+
+def test_benchmark_shapes_fit_the_static_scratch(lib):
+    import paper_2208_07339_amd as L
+    from paper_2208_07339_amd import workloads as wl
+    for c in wl.CONFIGS.values():
+        assert L.workspace_bytes(c["s"], c["h"], c["o"], 32) <= L.STATIC_SCRATCH_BYTES
 
 
 def test_bench_refuses_more_than_one_gpu():
