@@ -29,13 +29,21 @@ HBM_PEAK_GBS = 8000.0
 CAP = 32                       # capacity of the outlier index list
 COPY_PROBE_BYTES = 256 << 20   # size of the calibration copies of --copy-probe
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/*pmc*.txt), or None while not measured.
+# HBM bytes per launch of the dominant kernel.  NOT read in this run (counters need their own rocprofv3
+# --pmc passes): copied from the committed summary named in TRAFFIC_SOURCE, which gives the commands;
+# None for workloads without such a summary.
+TRAFFIC_SOURCE = "profiles/bench_default_ffn13b_decode_hbm_traffic.txt"
 MEASURED_TRAFFIC = {
-    # profiles/bench_default_ffn13b_decode_hbm_traffic.txt: FETCH_SIZE / 0.5001 + WRITE_SIZE / 1.0 (KiB -> bytes)
+    # FETCH_SIZE / 0.5001 + WRITE_SIZE / 1.0 (KiB -> bytes; factors from the copy probe of the same runs)
     "ffn13b": 634.18e6 + 167.81e6,   # gemm_prefill_kernel<4,4>: operand panels re-fetched per XCD and round + Out
     "decode": 608.02e6 + 1.58e6,     # gemm_decode_kernel<2,4>
 }
+
+
+def traffic_fields(workload):
+    t = MEASURED_TRAFFIC.get(workload)
+    return {"traffic": t, "traffic_source": (TRAFFIC_SOURCE + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "
+                                             "earlier run of this command, not read in this run)") if t else None}
 
 
 WARM_MS = 60.0  # least duration of the untimed warm-up (see run_workload)
@@ -51,7 +59,7 @@ def to_dev(a):
     return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
 
 
-def run_workload(name, steps, warmup, copies=1, int8_rows=False, granularity="vectorwise", alpha=None):
+def run_workload(name, steps, warmup, copies=1, int8_rows=False, granularity="vectorwise", alpha=None, ceilings=True):
     import torch
 
     import paper_2208_07339_amd as L
@@ -115,11 +123,54 @@ def run_workload(name, steps, warmup, copies=1, int8_rows=False, granularity="ve
     torch.cuda.synchronize()
     ms_step_events = (time.perf_counter() - t0) * 1e3 / steps
     ms_pre = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
-    ms_mm = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    mm = np.array([e[1].elapsed_time(e[2]) for e in evs])
+    # whole steps from the events: start of step i to start of step i + 1 (the last one to its own end)
+    st = np.array([evs[i][0].elapsed_time(evs[i + 1][0]) for i in range(steps - 1)] + [evs[-1][0].elapsed_time(evs[-1][2])])
+    ceil = measured_ceiling(L, torch, name, qws, rows) if ceilings else None
     return dict(name=name, s=s, h=h, o=o, n_out=n_out, planted=len(d["planted"]), ms_step=ms_step,
-                ms_prepass=ms_pre, ms_matmul=ms_mm, ms_step_events=ms_step_events, warmup_steps_run=n_warm,
-                weight_quantize_ms=t_wq * 1e3,
+                ms_prepass=ms_pre, ms_matmul=float(mm.mean()), ms_matmul_median=float(np.median(mm)),
+                ms_matmul_min=float(mm.min()), ms_step_median=float(np.median(st)), ms_step_min=float(st.min()),
+                ms_step_events=ms_step_events, warmup_steps_run=n_warm,
+                weight_quantize_ms=t_wq * 1e3, ceiling=ceil,
                 inputs=d)
+
+
+def _timed_launches(torch, fn, n_warm, n_timed):
+    """n_warm untimed launches of fn(i), then n_timed back to back between two events: ms per launch."""
+    for i in range(n_warm):
+        fn(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(n_timed):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n_timed
+
+
+def measured_ceiling(L, torch, name, qws, rows):
+    """What this machine sustains, measured right after the timed steps (same warm state).
+    Prefill: the register-only int8 MFMA issue loop (llmint8_probe_mfma) on this workload's own tiled codes,
+    and on zeros.  Decode: a read-only stream (llmint8_probe_read) over the int8 weights, rotating the same
+    two copies as the timed steps."""
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    if name == "decode":
+        nbytes = qws[0].Wq.numel()
+        ms = _timed_launches(torch, lambda i: L.probe_read(qws[i % len(qws)].Wq, sink), 200, 200)
+        return {"kind": "read-only stream over the int8 weights (llmint8_probe_read)", "unit": "GB/s",
+                "value": nbytes / (ms * 1e-3) / 1e9, "ms_per_launch": ms}
+    iters = 400
+    ops = []
+    zeros = torch.zeros(1 << 20, dtype=torch.int8, device="cuda")
+    out = {}
+    for key, (A, B) in (("workload_operands", (qws[0].Wq, rows.Xq)), ("zero_operands", (zeros, zeros))):
+        ms = _timed_launches(torch, lambda i: ops.append(L.probe_mfma(A, B, iters, sink)), 150, 100)
+        out[key] = ops[-1] / (ms * 1e-3) / 1e12
+        out[key + "_ms_per_launch"] = ms
+    return {"kind": "register-only v_mfma_i32_32x32x32_i8 issue loop, 4 waves per CU, 64 MFMAs per iteration "
+                    "(llmint8_probe_mfma): on this workload's tiled codes / on zeros", "unit": "TOP/s",
+            "value": out["workload_operands"], "zero_operands": out["zero_operands"],
+            "ms_per_launch": out["workload_operands_ms_per_launch"]}
 
 
 def run_zeropoint(name, steps, warmup, alpha):
@@ -159,7 +210,29 @@ def run_zeropoint(name, steps, warmup, alpha):
                 ms_matmul_calls=times[1], weight_quantize_ms=t_wq * 1e3)
 
 
-def cpu_baseline(res, target_seconds=12.0):
+def roofline_block(res):
+    """The dominant kernel against its nominal peak and against what this box sustained in this run."""
+    s, h, o = res["s"], res["h"], res["o"]
+    if res["name"] == "decode":
+        work, scale, peak = algorithmic_bytes_decode(s, h, o, res["n_out"]), 1e9, HBM_PEAK_GBS
+        blk = {"bound": "hbm", "kernel": "gemm_decode_kernel", "unit": "GB/s"}
+    else:
+        work, scale, peak = 2.0 * s * h * o, 1e12, INT8_MFMA_PEAK_TOPS
+        blk = {"bound": "mfma", "kernel": "gemm_prefill_kernel", "unit": "TOP/s"}
+    ach = work / (res["ms_matmul"] * 1e-3) / scale
+    blk.update({"achieved": ach, "peak": peak, "frac": ach / peak,
+                "achieved_median": work / (res["ms_matmul_median"] * 1e-3) / scale,
+                "achieved_best": work / (res["ms_matmul_min"] * 1e-3) / scale})
+    c = res.get("ceiling")
+    if c:
+        blk.update({"measured_peak": c["value"], "frac_of_measured": ach / c["value"], "measured_peak_kind": c["kind"]})
+        if "zero_operands" in c:
+            blk["measured_peak_zero_operands"] = c["zero_operands"]
+    blk.update(traffic_fields(res["name"]))
+    return blk
+
+
+def cpu_baseline(res, target_seconds=12.0, weights=None):
     """The CPU oracle, as it stands, on a bounded sample: the per-call steps (outlier scan, row
     quantization, integer product, dequantization + outlier product) on the first r rows of X
     against the full weight matrix, which is quantized beforehand and not timed."""
@@ -167,7 +240,7 @@ def cpu_baseline(res, target_seconds=12.0):
     d = res["inputs"]
     X, W = d["X"], d["W"]
     s, h, o = res["s"], res["h"], res["o"]
-    Wq, cw = oracle.quantize_weight(W)
+    Wq, cw = weights if weights is not None else oracle.quantize_weight(W)
     # calibrate the sample size on a couple of rows
     r = min(s, 2)
     t0 = time.perf_counter()
@@ -203,6 +276,8 @@ def main():
     ap.add_argument("--workload", default="ffn13b", choices=["ffn13b", "decode", "attn6p7b", "ffn175b_down"])
     ap.add_argument("--no-decode", action="store_true", help="skip the secondary decode measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured-ceiling leg (MFMA issue loop / read-only stream after the timed steps)")
     ap.add_argument("--outlier-rows", default="fp16", choices=["fp16", "int8"],
                     help="fp16: outlier product with the original weight rows (Eq. 8 as printed); int8: rows "
                          "rebuilt from the int8 codes, no fp16 weights kept (measured separately, not the headline)")
@@ -252,7 +327,7 @@ def main():
         return
     i8 = a.outlier_rows == "int8"
     res = run_workload(a.workload, a.steps, a.warmup, copies=2 if a.workload == "decode" else 1, int8_rows=i8,
-                       granularity=a.granularity, alpha=a.alpha)
+                       granularity=a.granularity, alpha=a.alpha, ceilings=not a.no_ceilings)
     s, h, o = res["s"], res["h"], res["o"]
     ops = 2.0 * s * h * o
     line = {
@@ -266,52 +341,55 @@ def main():
         "config": {"workload": a.workload, "s": s, "h": h, "o": o, "alpha": a.alpha if np.isfinite(a.alpha) else "inf", "granularity": a.granularity,
                    "outlier_columns_planted": res["planted"], "outlier_columns_found": res["n_out"],
                    "outlier_capacity": CAP, "outlier_rows": a.outlier_rows},
+        "ms_per_step_median": res["ms_step_median"], "ms_per_step_min": res["ms_step_min"],
         "ms_prepass": res["ms_prepass"], "ms_matmul_kernel": res["ms_matmul"],
+        "ms_matmul_kernel_median": res["ms_matmul_median"], "ms_matmul_kernel_min": res["ms_matmul_min"],
         "ms_per_step_with_events": res["ms_step_events"], "warmup_steps_run": res["warmup_steps_run"],
         "weight_quantize_ms_once": res["weight_quantize_ms"],
     }
     if a.workload == "decode":
-        nbytes = algorithmic_bytes_decode(s, h, o, res["n_out"])
         line["metric"] = ("achieved HBM GB/s of the LLM.int8() matmul per call at decode size "
                           "(algorithmic bytes / step time), 1 MI355X")
-        line["value"] = nbytes / (res["ms_step"] * 1e-3) / 1e9
+        line["value"] = algorithmic_bytes_decode(s, h, o, res["n_out"]) / (res["ms_step"] * 1e-3) / 1e9
         line["unit"] = "GB/s"
-        ach = nbytes / (res["ms_matmul"] * 1e-3) / 1e9
-        line["roofline"] = {"bound": "hbm", "kernel": "gemm_decode_kernel", "achieved": ach,
-                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                            "traffic": MEASURED_TRAFFIC.get("decode")}
-    else:
-        ach = ops / (res["ms_matmul"] * 1e-3) / 1e12
-        line["roofline"] = {"bound": "mfma", "kernel": "gemm_prefill_kernel", "achieved": ach,
-                            "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": ach / INT8_MFMA_PEAK_TOPS,
-                            "traffic": MEASURED_TRAFFIC.get(a.workload)}
+    line["roofline"] = roofline_block(res)
 
     if not a.no_cpu_baseline and a.granularity == "vectorwise":  # the oracle leg times the method itself
-        r, t, cores = cpu_baseline(res)
+        import oracle
+        wts = oracle.quantize_weight(res["inputs"]["W"])
+        r, t, cores = cpu_baseline(res, weights=wts)
+        # the same oracle on one thread, on a smaller sample of the same rows
+        oracle.set_num_threads(1)
+        r1, t1, _ = cpu_baseline(res, target_seconds=5.0, weights=wts)
+        oracle.set_num_threads(cores)
         if a.workload == "decode":
             # the oracle reads fp16 weights; quote it in the metric's unit on the same algorithmic bytes
             v = algorithmic_bytes_decode(r, h, o, res["n_out"]) / t / 1e9
+            v1 = algorithmic_bytes_decode(r1, h, o, res["n_out"]) / t1 / 1e9
             unit = "GB/s"
         else:
             v = 2.0 * r * h * o / t / 1e12
+            v1 = 2.0 * r1 * h * o / t1 / 1e12
             unit = "TOPS"
         line["cpu_baseline"] = {"value": v, "unit": unit, "cores": cores, "kind": "oracle",
                                 "sample": f"per-call steps on the first {r} of {s} rows of X against the full "
-                                          f"{h}x{o} weights (quantized beforehand, untimed); {t:.1f} s"}
+                                          f"{h}x{o} weights (quantized beforehand, untimed); {t:.1f} s",
+                                "single_thread": {"value": v1, "unit": unit, "cores": 1,
+                                                  "sample": f"the first {r1} of {s} rows; {t1:.1f} s"}}
     del res["inputs"]
 
     if a.workload != "decode" and not a.no_decode:
         dres = run_workload("decode", a.steps, a.warmup, copies=2, int8_rows=i8, granularity=a.granularity,
-                            alpha=a.alpha)
+                            alpha=a.alpha, ceilings=not a.no_ceilings)
         nbytes = algorithmic_bytes_decode(dres["s"], dres["h"], dres["o"], dres["n_out"])
         line["decode"] = {
             "workload": "decode", "s": dres["s"], "h": dres["h"], "o": dres["o"],
-            "ms_per_step": dres["ms_step"], "ms_prepass": dres["ms_prepass"], "ms_matmul_kernel": dres["ms_matmul"],
+            "ms_per_step": dres["ms_step"], "ms_per_step_median": dres["ms_step_median"],
+            "ms_per_step_min": dres["ms_step_min"], "ms_prepass": dres["ms_prepass"],
+            "ms_matmul_kernel": dres["ms_matmul"], "ms_matmul_kernel_median": dres["ms_matmul_median"],
+            "ms_matmul_kernel_min": dres["ms_matmul_min"],
             "value": nbytes / (dres["ms_step"] * 1e-3) / 1e9, "unit": "GB/s",
-            "roofline": {"bound": "hbm", "kernel": "gemm_decode_kernel",
-                         "achieved": nbytes / (dres["ms_matmul"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                         "unit": "GB/s", "frac": nbytes / (dres["ms_matmul"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "traffic": MEASURED_TRAFFIC.get("decode")},
+            "roofline": roofline_block(dres),
         }
     print(json.dumps(line))
 

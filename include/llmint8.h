@@ -214,6 +214,19 @@ int llmint8_zp_linear(const void *X_f16, int s, int h, float alpha, const int8_t
                       int8_t *Xq, int32_t *zc_x, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
                       llmint8_stream_t stream);
 
+/* Measurement support: the ceilings the roofline fractions are held against, measured on the box itself.
+ * llmint8_probe_mfma: one workgroup per compute unit runs a register-only issue loop of the int8 MFMA
+ *   in the shape of the prefill GEMM's main loop (Eq. 7: 4 x 4 accumulator tiles per wave, 64 MFMAs per
+ *   iteration), its operands read once from the tiled int8 buffers A_tiles / B_tiles (llmint8_xq_bytes /
+ *   llmint8_wq_bytes layouts, or a buffer of zeros; at least one 1 KiB tile each): no memory traffic in
+ *   the loop, so its rate is what the matrix cores sustain on operands with those statistics.  *ops (host,
+ *   may be NULL) receives the int8 operations the launch performs; time it with events on the stream.
+ * llmint8_probe_read: a read-only stream over buf (bytes >= 1024, 16-byte aligned; whole KiB are read).
+ * sink: 4 bytes of device memory (written with negligible probability, never read).          */
+int llmint8_probe_mfma(const int8_t *A_tiles, size_t a_bytes, const int8_t *B_tiles, size_t b_bytes, int iters,
+                       int32_t *sink, double *ops, llmint8_stream_t stream);
+int llmint8_probe_read(const void *buf, size_t bytes, int32_t *sink, llmint8_stream_t stream);
+
 /* Test/support: force the workgroup tile of the prefill GEMM (output columns x tokens):
  * 0 = 256 x 256, 1 = 192 x 256, 2 = 128 x 256, 3 = 128 x 128; -1 = choose from the shape (default).
  * Process-wide; results do not depend on it.                                  */
@@ -225,6 +238,12 @@ int llmint8_debug_prefill_tile(int cfg);
  * Anything else is LLMINT8_INVALID_ARG.  Process-wide; results do not depend on it.   */
 #define LLMINT8_DECODE_SHAPES 5
 int llmint8_debug_decode_shape(int cfg);
+
+/* Test/support: force the pre-pass (Section 3.2 scan + Section 3.1 row quantization) that llmint8_linear*
+ * runs for s > 32 when X allows 16-byte loads: 0 = scan by row slabs, column lists, row constants and
+ * quantizer as four kernels; 1 = scan that leaves outlier masks and a fused quantizer, two kernels (what
+ * -1, not forced, runs as well).  Process-wide; results do not depend on it.  */
+int llmint8_debug_prepass(int cfg);
 
 /* Test/support: private layouts -> plain row-major int8 ([h x o], [s x h]). */
 int llmint8_export_weight(const int8_t *Wq, int h, int o, int8_t *W_i8_rowmajor, llmint8_stream_t stream);

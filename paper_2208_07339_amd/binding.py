@@ -10,12 +10,12 @@ SYMBOLS = [
     "llmint8_status_string", "llmint8_last_hip_error", "llmint8_opad", "llmint8_wq_bytes", "llmint8_xq_bytes",
     "llmint8_workspace_bytes", "llmint8_quantize_weight", "llmint8_find_outliers",
     "llmint8_quantize_rows", "llmint8_matmul", "llmint8_linear", "llmint8_linear_events", "llmint8_dequantize_rows",
-    "llmint8_init", "llmint8_linear_static",
+    "llmint8_init", "llmint8_linear_static", "llmint8_probe_mfma", "llmint8_probe_read",
     "llmint8_quantize_weight_granular", "llmint8_quantize_rows_granular", "llmint8_linear_granular",
     "llmint8_zp_quantize_weight", "llmint8_zp_quantize_rows", "llmint8_zp_matmul", "llmint8_zp_linear",
     "llmint8_export_weight",
     "llmint8_export_rows", "llmint8_debug_prefill_tile",
-    "llmint8_debug_decode_shape",
+    "llmint8_debug_decode_shape", "llmint8_debug_prepass",
 ]
 
 _lib = None
@@ -64,6 +64,10 @@ def lib():
     L.llmint8_init.argtypes = []
     L.llmint8_linear_static.restype = i32
     L.llmint8_linear_static.argtypes = [vp, i32, i32, f32, vp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.llmint8_probe_mfma.restype = i32
+    L.llmint8_probe_mfma.argtypes = [vp, sz, vp, sz, i32, vp, C.POINTER(C.c_double), vp]
+    L.llmint8_probe_read.restype = i32
+    L.llmint8_probe_read.argtypes = [vp, sz, vp, vp]
     L.llmint8_dequantize_rows.restype = i32
     L.llmint8_dequantize_rows.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, vp]
     L.llmint8_quantize_weight_granular.restype = i32
@@ -89,6 +93,8 @@ def lib():
     L.llmint8_export_rows.argtypes = [vp, i32, i32, vp, vp]
     L.llmint8_debug_prefill_tile.restype = i32
     L.llmint8_debug_prefill_tile.argtypes = [i32]
+    L.llmint8_debug_prepass.restype = i32
+    L.llmint8_debug_prepass.argtypes = [i32]
     L.llmint8_debug_decode_shape.restype = i32
     L.llmint8_debug_decode_shape.argtypes = [i32]
     _lib = L
@@ -279,9 +285,27 @@ def linear_static(X, qw, alpha, outl, rows, out):
     return out
 
 
+def probe_mfma(A_tiles, B_tiles, iters, sink):
+    """llmint8_probe_mfma on two tiled int8 device buffers; returns the int8 operations of the launch."""
+    ops = C.c_double(0.0)
+    _check(lib().llmint8_probe_mfma(_ptr(A_tiles), A_tiles.numel(), _ptr(B_tiles), B_tiles.numel(), int(iters),
+                                    _ptr(sink), C.byref(ops), _stream()))
+    return ops.value
+
+
+def probe_read(buf, sink):
+    """llmint8_probe_read over a device buffer (bytes)."""
+    _check(lib().llmint8_probe_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()))
+
+
 def debug_prefill_tile(cfg):
     """llmint8_debug_prefill_tile: force the prefill GEMM's workgroup tile (-1 = automatic)."""
     _check(lib().llmint8_debug_prefill_tile(int(cfg)))
+
+
+def debug_prepass(cfg):
+    """llmint8_debug_prepass: force the pre-pass variant of llmint8_linear for s > 32 (-1 = automatic)."""
+    _check(lib().llmint8_debug_prepass(int(cfg)))
 
 
 def debug_decode_shape(cfg):

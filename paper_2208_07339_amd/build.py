@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libllmint8.so")
-SOURCES = ["api.hip", "prepass.hip", "gemm.hip", "decode.hip", "zeropoint.hip"]
+SOURCES = ["api.hip", "prepass.hip", "gemm.hip", "decode.hip", "zeropoint.hip", "ceiling.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -30,7 +30,7 @@ def build(verbose=False):
             print(err)
         return obj
 
-    with ThreadPoolExecutor(5) as ex:
+    with ThreadPoolExecutor(6) as ex:
         objs = list(ex.map(cc, SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
     return LIB

@@ -333,9 +333,44 @@ def test_linear_prefill_sizes():
     linear_compare(wl.make_custom(48, 256, 64, 0, seed=47), alpha=float("inf"))
 
 
-def test_linear_row_maximum_inside_an_outlier_column():
+@pytest.fixture
+def forced_prepass():
+    import paper_2208_07339_amd as L
+    yield L.debug_prepass
+    L.debug_prepass(-1)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_both_prepasses_of_the_one_call_path(mode, forced_prepass):
+    """llmint8_linear for s > 32 has two pre-passes (scan by row slabs + lists + row constants + quantizer;
+    column-complete scan + fused quantizer) and picks one from the shape: each of them forced, on shapes
+    that take every branch: several row groups per scan workgroup, a single 64-column block, ragged K,
+    |O| > cap, every column an outlier, more outlier columns than the fused kernel lists in LDS (with and
+    without overflow), rows that are all zero, no outlier at all."""
+    forced_prepass(mode)
+    linear_compare(wl.make_custom(100, 512, 256, 3, seed=41))
+    linear_compare(wl.make_custom(300, 1000, 520, 4, seed=42))
+    linear_compare(wl.make_custom(257, 4160, 264, 6, seed=43))
+    linear_compare(wl.make_custom(2500, 320, 64, 5, seed=48))                 # 2 500 rows: three passes of a scan workgroup
+    linear_compare(wl.make_custom(33, 64, 32, 1, seed=49))                    # one 64-column block
+    linear_compare(wl.make_custom(50, 8, 16, 1, seed=50))                     # one 8-column chunk
+    linear_compare(wl.make_custom(70, 384, 96, 9, seed=44), cap=4)            # |O| > cap
+    linear_compare(wl.make_custom(40, 96, 64, 2, seed=45), alpha=0.0, cap=96)   # every column
+    linear_compare(wl.make_custom(64, 600, 64, 300, seed=46, frac=0.3), cap=300)
+    linear_compare(wl.make_custom(40, 2048, 64, 3, seed=81), alpha=0.0, cap=2048)   # 2 048 outlier columns
+    linear_compare(wl.make_custom(40, 2048, 64, 3, seed=82), alpha=0.0, cap=1500)   # ... and |O| > cap on top
+    linear_compare(wl.make_custom(48, 256, 64, 0, seed=47))
+    d = wl.make_custom(200, 1024, 128, 4, seed=83)
+    d["X"][7] = 0
+    d["X"][199] = 0
+    linear_compare(d)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_linear_row_maximum_inside_an_outlier_column(mode, forced_prepass):
     """Rows whose largest magnitude below alpha sits in an outlier column (alone, or tied with a regular
     column): the row constant must come from the regular columns only."""
+    forced_prepass(mode)
     d = wl.make_custom(200, 1024, 128, 4, seed=51)
     X = d["X"]
     j0, j1 = int(d["planted"][0]), int(d["planted"][-1])
