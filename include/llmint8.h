@@ -239,12 +239,6 @@ int llmint8_debug_prefill_tile(int cfg);
 #define LLMINT8_DECODE_SHAPES 5
 int llmint8_debug_decode_shape(int cfg);
 
-/* Test/support: force the pre-pass (Section 3.2 scan + Section 3.1 row quantization) that llmint8_linear*
- * runs for s > 32 when X allows 16-byte loads: 0 = scan by row slabs, column lists, row constants and
- * quantizer as four kernels; 1 = scan that leaves outlier masks and a fused quantizer, two kernels (what
- * -1, not forced, runs as well).  Process-wide; results do not depend on it.  */
-int llmint8_debug_prepass(int cfg);
-
 /* Test/support: private layouts -> plain row-major int8 ([h x o], [s x h]). */
 int llmint8_export_weight(const int8_t *Wq, int h, int o, int8_t *W_i8_rowmajor, llmint8_stream_t stream);
 int llmint8_export_rows(const int8_t *Xq, int s, int h, int8_t *X_i8_rowmajor, llmint8_stream_t stream);

@@ -15,7 +15,7 @@ SYMBOLS = [
     "llmint8_zp_quantize_weight", "llmint8_zp_quantize_rows", "llmint8_zp_matmul", "llmint8_zp_linear",
     "llmint8_export_weight",
     "llmint8_export_rows", "llmint8_debug_prefill_tile",
-    "llmint8_debug_decode_shape", "llmint8_debug_prepass",
+    "llmint8_debug_decode_shape",
 ]
 
 _lib = None
@@ -93,8 +93,6 @@ def lib():
     L.llmint8_export_rows.argtypes = [vp, i32, i32, vp, vp]
     L.llmint8_debug_prefill_tile.restype = i32
     L.llmint8_debug_prefill_tile.argtypes = [i32]
-    L.llmint8_debug_prepass.restype = i32
-    L.llmint8_debug_prepass.argtypes = [i32]
     L.llmint8_debug_decode_shape.restype = i32
     L.llmint8_debug_decode_shape.argtypes = [i32]
     _lib = L
@@ -301,11 +299,6 @@ def probe_read(buf, sink):
 def debug_prefill_tile(cfg):
     """llmint8_debug_prefill_tile: force the prefill GEMM's workgroup tile (-1 = automatic)."""
     _check(lib().llmint8_debug_prefill_tile(int(cfg)))
-
-
-def debug_prepass(cfg):
-    """llmint8_debug_prepass: force the pre-pass variant of llmint8_linear for s > 32 (-1 = automatic)."""
-    _check(lib().llmint8_debug_prepass(int(cfg)))
 
 
 def debug_decode_shape(cfg):

@@ -18,22 +18,9 @@ inline void* ws_base(void* ws) { return (void*)align_up((uintptr_t)ws, 256); }
 // outlier scan: list scratch first, then the slab maxima
 inline size_t scratch_ws(int h, int cap) { return align_up(outlier_lists_bytes(h, cap), 256); }
 inline size_t slab_ws(int s, int h) { return align_up((size_t)colmax_slabs(s, h) * h * 2, 256); }
-// partial row maxima of the scans that also prepare the row constants: [ceil(h / 128)][s] fp16 bits (the
-// two-kernel pre-pass; the four-kernel one uses [ceil(h / 512)][s] of it), and the slab masks of the former
-inline size_t rowpart_ws(int s, int h) { return align_up((size_t)((h + 127) / 128) * s * 2, 256); }
-inline size_t mask_ws(int s, int h)
-{
-    int rps = 0;
-    return align_up((size_t)prepass_slabs(s, h, &rps) * ((h + 127) / 128) * 16, 256);
-}
-inline size_t outlier_ws(int s, int h, int cap)
-{
-    return scratch_ws(h, cap) + slab_ws(s, h) + rowpart_ws(s, h) + mask_ws(s, h);
-}
-inline bool prepass_fused()
-{
-    return g_prepass_cfg.load(std::memory_order_relaxed) != 0;  // -1 (not forced) or 1
-}
+// partial row maxima of the fused column / row scan: [ceil(h / 512)][s] fp16 bits
+inline size_t rowpart_ws(int s, int h) { return align_up((size_t)((h + 511) / 512) * s * 2, 256); }
+inline size_t outlier_ws(int s, int h, int cap) { return scratch_ws(h, cap) + slab_ws(s, h) + rowpart_ws(s, h); }
 inline size_t weight_ws(int h, int o) { return align_up((size_t)colmax_slabs(h, o) * o * 2, 256); }
 // rebuilt outlier rows of W (used when no fp16 weights are given): [opad x o] fp16, behind everything else
 inline size_t rows_ws(int o, int cap) { return align_up((size_t)opad_of(cap) * o * 2, 256); }
@@ -286,16 +273,10 @@ static int linear_impl(const void* X_f16, int s, int h, float alpha, int granula
             unsigned short* part = (unsigned short*)(base + scratch_ws(h, cap));
             const int nslab = colmax_slabs(s, h);
             const unsigned thr = threshold_bits(alpha);
-            unsigned short* rowpart = (unsigned short*)(base + scratch_ws(h, cap) + slab_ws(s, h));
-            if (!shared_cx && h % 8 == 0 && !misaligned(X_f16, 16) && prepass_fused()) {
-                // two kernels, X read twice: a scan by column blocks and row slabs (outlier masks + partial row
-                // maxima), then row constants, codes, gathered columns and the outlier list in one kernel
-                unsigned char* smask = (unsigned char*)rowpart + rowpart_ws(s, h);
-                e = launch_prepass_fused(X_f16, s, h, thr, smask, rowpart, idx, cap, count, status,
-                                         (unsigned short*)cx_f16, (unsigned short*)Xo_f16, Xq, st);
-            } else if (!shared_cx && h % 8 == 0 && !misaligned(X_f16, 16)) {
+            if (!shared_cx && h % 8 == 0 && !misaligned(X_f16, 16)) {
                 // X is read twice instead of three times: the column scan leaves partial row maxima, from which
                 // a small kernel gets the row constants once the outlier columns are known
+                unsigned short* rowpart = (unsigned short*)(base + scratch_ws(h, cap) + slab_ws(s, h));
                 e = launch_colmax_rowmax(X_f16, s, h, part, nslab, rowpart, thr, st);
                 if (e == hipSuccess) e = launch_outlier_lists(part, nslab, h, thr, L, cap, st);
                 if (e == hipSuccess)
@@ -452,13 +433,6 @@ int llmint8_debug_prefill_tile(int cfg)
 {
     if (cfg < -1 || cfg >= LLMINT8_PREFILL_TILES) return LLMINT8_INVALID_ARG;
     g_force_cfg.store(cfg, std::memory_order_relaxed);
-    return LLMINT8_OK;
-}
-
-int llmint8_debug_prepass(int cfg)
-{
-    if (cfg < -1 || cfg > 1) return LLMINT8_INVALID_ARG;
-    g_prepass_cfg.store(cfg, std::memory_order_relaxed);
     return LLMINT8_OK;
 }
 

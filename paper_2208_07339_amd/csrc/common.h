@@ -107,15 +107,6 @@ hipError_t launch_colmax_rowmax(const void* X, int s, int h, unsigned short* par
 hipError_t launch_quantize_rows_rowpart(const void* X, int s, int h, OutlierLists L, unsigned thr,
                                         const unsigned short* rowpart, int32_t* idx, int32_t* count, int32_t* status,
                                         int cap, int8_t* Xq, unsigned short* cx, unsigned short* Xo, hipStream_t st);
-// whole pre-pass of a longer X in two kernels (needs h % 8 == 0 and a 16-byte aligned X): a scan by column
-// blocks of 128 and row slabs that leaves smask[slabs][16 ceil(h / 128)] (bit j % 8 of byte j / 8 of a slab's
-// row: column j reaches the threshold within the slab) and rowpart[ceil(h / 128)][s] (partial row maxima
-// below the threshold), then row constants + codes + gathered columns + idx / count / status in one kernel
-constexpr int LLMINT8_MAX_H_BLOCKS = (133144 + 127) / 128;  // 128-column blocks at the largest feature dimension
-int prepass_slabs(int s, int h, int* rows_per_slab);
-hipError_t launch_prepass_fused(const void* X, int s, int h, unsigned thr, unsigned char* smask,
-                                unsigned short* rowpart, int32_t* idx, int cap, int32_t* count, int32_t* status,
-                                unsigned short* cx, unsigned short* Xo, int8_t* Xq, hipStream_t st);
 // whole pre-pass of a short X (s <= 32): outlier scan, row constants, codes, gathered columns
 hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
                                 int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,
@@ -166,9 +157,6 @@ hipError_t launch_dequant_rows(const int8_t* Wq, const unsigned short* cw, int h
 extern std::atomic<int> g_force_cfg;
 // work split of the decode kernel forced by llmint8_debug_decode_shape (-1: default)
 extern std::atomic<int> g_decode_cfg;
-// pre-pass of llmint8_linear for s > 32 forced by llmint8_debug_prepass (-1: chosen from the shape;
-// 0: slab scan + lists + row constants + quantizer, four kernels; 1: slab scan with masks + fused quantizer)
-extern std::atomic<int> g_prepass_cfg;
 // One-time set-up of the prefill kernels on the current device (dynamic LDS limit of every instantiation);
 // returns the device's number of compute units.  Thread-safe; cheap after the first call on a device.
 hipError_t prefill_device_setup(int* compute_units);

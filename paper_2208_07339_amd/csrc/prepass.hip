@@ -1,8 +1,6 @@
 // Bandwidth-bound passes around the int8 GEMM: column absmax / outlier scan
 // (Section 3.2), per-row absmax quantization of the non-outlier part of X and
 // per-column absmax quantization of W (Sections 2.1, 3.1), layout export.
-#include <type_traits>
-
 #include "common.h"
 
 namespace llmint8 {
@@ -98,8 +96,6 @@ int colmax_slabs(int rows, int cols)
 }
 
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
-
-std::atomic<int> g_prepass_cfg{-1};  // test hook: pre-pass variant of llmint8_linear for s > 32 (-1 = automatic)
 
 hipError_t launch_colmax_partial(const void* M, int rows, int cols, unsigned short* part, int nslab,
                                  hipStream_t st)
@@ -943,445 +939,6 @@ __global__ void __launch_bounds__(256) row_const_kernel(const unsigned short* __
         }
     }
     if (i < s && lane == 0 && !(all_slow || need)) cx[i] = (unsigned short)m1;
-}
-
-// ---------------------------------------------------------------------------
-// Two-kernel pre-pass of llmint8_linear for s > 32 (X allows 16-byte loads).
-//
-// scan_slab_kernel: a workgroup owns 128 columns (256 bytes of a row) and a
-// slab of rows.  It writes, as a 128-bit mask smask[slab][column block], which
-// of its columns reach the threshold within the slab, and per row the largest
-// magnitude BELOW the threshold among its 128 columns, rowpart[block][row].
-// Entries of non-outlier columns are all below the threshold, so the maximum
-// of a row's partials is its constant c_x unless that maximum sits in an
-// outlier column.  Every mask is written, set or not: nothing has to be
-// cleared beforehand and no workgroup waits for another.
-//
-// quantize_fused_kernel: a workgroup owns 32 rows (one row tile) and a run of
-// 256-feature blocks.  Its prologue ORs the slab masks (a few KiB whatever the
-// shape: the launcher picks the number of slabs so) into the outlier mask of
-// all columns, whose popcount prefix sums are the positions of the outlier
-// columns in ascending order (no lists to chase), reduces its rows' partial
-// maxima, and gathers its rows' entries in the outlier columns: with m1 = the
-// largest below-threshold magnitude of the row and mo = the largest such
-// magnitude inside the outlier columns, mo < m1 means m1 sits in a non-outlier
-// column, so c_x = m1; otherwise (rare), and whenever more columns qualify than
-// cap allows (then the columns beyond cap count as ordinary ones and their
-// large entries belong to c_x), the workgroup scans that row again without the
-// outlier columns.  Then it quantizes its blocks.  Group 0 also writes c_x and
-// Xo, its first workgroup idx, count and status.  The loads of the prologue
-// and of the first tile of X are all requested up front: two dependent round
-// trips to memory (masks / partials, then the gather) before the codes flow.
-// ---------------------------------------------------------------------------
-constexpr int SC_CW = 128;         // columns per scan workgroup
-constexpr int SC_U = 8;            // row groups (of 16 rows) in flight per workgroup
-constexpr int QF_PF = 4;            // blocks of X a quantizer workgroup keeps in flight (16 registers each)
-constexpr int IDX_SLOTS = 1024;    // outlier columns whose indices are kept in LDS; more: every row takes the slow path
-
-__device__ __forceinline__ us8 shfl_xor_us8(us8 v, int d)
-{
-    u4 t = __builtin_bit_cast(u4, v);
-    t.x = (unsigned)__shfl_xor((int)t.x, d);
-    t.y = (unsigned)__shfl_xor((int)t.y, d);
-    t.z = (unsigned)__shfl_xor((int)t.z, d);
-    t.w = (unsigned)__shfl_xor((int)t.w, d);
-    return __builtin_bit_cast(us8, t);
-}
-
-// elementwise max of two packed fp16 magnitudes with a lane of the same 16-lane row, by DPP (no LDS traffic)
-template <int CTRL>
-__device__ __forceinline__ us2 dpp_max2(us2 a)
-{
-    const int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), CTRL, 0xf, 0xf, false);
-    return __builtin_elementwise_max(a, __builtin_bit_cast(us2, t));
-}
-// maximum over the 16 lanes of a row, in every lane: neighbour, other pair, other quad (half mirror), other half (mirror)
-__device__ __forceinline__ us2 row16_max2(us2 a)
-{
-    a = dpp_max2<0xB1>(a);   // quad_perm [1, 0, 3, 2]
-    a = dpp_max2<0x4E>(a);   // quad_perm [2, 3, 0, 1]
-    a = dpp_max2<0x141>(a);  // row_half_mirror
-    a = dpp_max2<0x140>(a);  // row_mirror
-    return a;
-}
-
-__global__ void __launch_bounds__(256) scan_slab_kernel(const unsigned short* __restrict__ X, int s, int h, unsigned thr,
-                                                        int rows_per_slab, unsigned char* __restrict__ smask, int pitch,
-                                                        unsigned short* __restrict__ rowpart)
-{
-    __shared__ us8 red[4][16];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int cc = lane & 15, r4 = lane >> 4;  // a wave-wide load covers 4 rows x 256 bytes
-    const int cb = blockIdx.x, sl = blockIdx.y;
-    const int c0 = cb * SC_CW + cc * 8;
-    const bool in = c0 < h;  // h is a multiple of 8: a chunk lies inside the matrix or outside
-    const unsigned short* p = X + (in ? c0 : 0);
-    const us8 thrv = (us8)((unsigned short)thr);
-    unsigned short* rp = rowpart + (size_t)cb * s;
-    const int r_begin = sl * rows_per_slab;
-    const int r_end = (r_begin + rows_per_slab) < s ? (r_begin + rows_per_slab) : s;
-    us8 m = (us8)(0);
-    // batches of 128 rows (16 per wave-load position, SC_U loads per lane), two batches in flight
-    us8 v[2][SC_U];
-    auto request = [&](auto B, int base) {
-        constexpr int BB = decltype(B)::value;
-        const int r0 = base + w * 4 + r4;
-#pragma unroll
-        for (int u = 0; u < SC_U; u++) {
-            v[BB][u] = (us8)(0);
-            if (in && r0 + 16 * u < r_end) v[BB][u] = *(const us8*)(p + (size_t)(r0 + 16 * u) * h);
-        }
-    };
-    auto consume = [&](auto B, int base) {
-        constexpr int BB = decltype(B)::value;
-        const int r0 = base + w * 4 + r4;
-        unsigned short x[SC_U];
-#pragma unroll
-        for (int u = 0; u < SC_U; u++) {
-            const us8 a = v[BB][u] & (unsigned short)0x7fff;
-            m = __builtin_elementwise_max(m, a);
-            const us8 below = a & __builtin_convertvector(a < thrv, us8);  // entries that reach the threshold drop out
-            x[u] = hmax8(below);
-        }
-        // two rows per register through the reduction over the 16 lanes of a row
-#pragma unroll
-        for (int k = 0; k < SC_U / 2; k++) {
-            us2 a = {x[2 * k], x[2 * k + 1]};
-            a = row16_max2(a);
-            if (cc == 0) {
-                const int ra = r0 + 16 * (2 * k), rb = ra + 16;
-                if (ra < r_end) rp[ra] = a.x;
-                if (rb < r_end) rp[rb] = a.y;
-            }
-        }
-    };
-    using B0 = std::integral_constant<int, 0>;
-    using B1 = std::integral_constant<int, 1>;
-    constexpr int BATCH = 16 * SC_U;
-    request(B0{}, r_begin);
-    if (r_begin + BATCH < r_end) request(B1{}, r_begin + BATCH);
-    for (int base = r_begin; base < r_end; base += 2 * BATCH) {
-        consume(B0{}, base);
-        if (base + 2 * BATCH < r_end) request(B0{}, base + 2 * BATCH);
-        if (base + BATCH < r_end) {
-            consume(B1{}, base + BATCH);
-            if (base + 3 * BATCH < r_end) request(B1{}, base + 3 * BATCH);
-        }
-    }
-    // column maxima: over the 4 row positions of a wave, then over the 4 waves
-    m = __builtin_elementwise_max(m, shfl_xor_us8(m, 16));
-    m = __builtin_elementwise_max(m, shfl_xor_us8(m, 32));
-    if (r4 == 0) red[w][cc] = m;
-    __syncthreads();
-    if (tid < 16) {  // tid = cc here
-        const us8 mm = __builtin_elementwise_max(__builtin_elementwise_max(red[0][tid], red[1][tid]),
-                                                 __builtin_elementwise_max(red[2][tid], red[3][tid]));
-        unsigned byte = 0;
-        if (in) {
-#pragma unroll
-            for (int e = 0; e < 8; e++)
-                if ((unsigned)mm[e] >= thr) byte |= 1u << e;
-        }
-        smask[(size_t)sl * pitch + cb * 16 + tid] = (unsigned char)byte;
-    }
-}
-
-__global__ void __launch_bounds__(256) quantize_fused_kernel(const unsigned short* __restrict__ X, int s, int h,
-                                                             unsigned thr, const unsigned char* __restrict__ smask,
-                                                             int pitch, int nslab,
-                                                             const unsigned short* __restrict__ rowpart, int ncb,
-                                                             int cap, int opad, int bpg, int KT,
-                                                             int32_t* __restrict__ idx, int32_t* __restrict__ count,
-                                                             int32_t* __restrict__ status,
-                                                             unsigned short* __restrict__ cx,
-                                                             unsigned short* __restrict__ Xo, int8_t* __restrict__ Xq)
-{
-    extern __shared__ unsigned long long s_mask[];  // [2 ncb] masks of the columns that count as outliers, then int s_pos[2 ncb]
-    __shared__ __attribute__((aligned(16))) int8_t stage[8 * TILE_BYTES];
-    __shared__ int s_idx[IDX_SLOTS];
-    __shared__ unsigned s_part[8][32];
-    __shared__ unsigned s_cx[32];
-    __shared__ int s_again[32];
-    __shared__ int s_wsum[4];
-    __shared__ unsigned s_red[4];
-    const int nwords = 2 * ncb;  // 64 columns per word
-    int* s_pos = (int*)(s_mask + nwords);
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int rt = blockIdx.x, grp = blockIdx.y;
-    const int row0 = rt * 32;
-    const int nblk = (KT + 7) / 8;  // blocks of 256 features (8 tiles)
-    const int blk0 = grp * bpg, blk1 = (blk0 + bpg) < nblk ? (blk0 + bpg) : nblk;
-    const bool first = (rt == 0 && grp == 0);
-    const int kseg = (tid & 31) * 8;
-
-    // ---- everything whose address is known is requested first: the first QF_PF blocks of X (their latency
-    // covers the prologue's), the partial maxima, the slab masks
-    us8 xv[QF_PF][4];
-    auto load_tile = [&](auto J, int blk) {
-        constexpr int JJ = decltype(J)::value;
-#pragma unroll
-        for (int q = 0; q < 4; q++) {
-            const int i = row0 + q * 8 + (tid >> 5), k = blk * 256 + kseg;
-            xv[JJ][q] = (us8)(0);
-            if (blk < blk1 && i < s && k < h) xv[JJ][q] = *(const us8*)(X + (size_t)i * h + k);
-        }
-    };
-    load_tile(std::integral_constant<int, 0>{}, blk0);
-    load_tile(std::integral_constant<int, 1>{}, blk0 + 1);
-    load_tile(std::integral_constant<int, 2>{}, blk0 + 2);
-    load_tile(std::integral_constant<int, 3>{}, blk0 + 3);
-    for (int q = tid; q < nwords; q += 256) s_mask[q] = 0;
-    {
-        const int i = tid & 31, gq = tid >> 5;
-        unsigned rp_max = 0;
-        if (row0 + i < s)
-            for (int b = gq; b < ncb; b += 64) {  // 8 independent loads in flight
-                unsigned t8[8];
-#pragma unroll
-                for (int u = 0; u < 8; u++)
-                    t8[u] = (b + 8 * u < ncb) ? (unsigned)rowpart[(size_t)(b + 8 * u) * s + row0 + i] : 0u;
-#pragma unroll
-                for (int u = 0; u < 8; u++) rp_max = t8[u] > rp_max ? t8[u] : rp_max;
-            }
-        s_part[gq][i] = rp_max;
-    }
-    __syncthreads();  // the cleared masks
-    {
-        const int npiece = nslab * ncb;  // 16-byte pieces: 128 columns of one slab
-        unsigned* mw = (unsigned*)s_mask;
-        for (int q0 = tid; q0 < npiece; q0 += 1024) {
-            u4 v[4];
-#pragma unroll
-            for (int u = 0; u < 4; u++) {
-                const int q = q0 + 256 * u;
-                v[u] = (u4)(0u);
-                if (q < npiece) {
-                    const int sl = q / ncb, pc = q - sl * ncb;
-                    v[u] = *(const u4*)(smask + (size_t)sl * pitch + pc * 16);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; u++) {
-                const int q = q0 + 256 * u;
-                if (q < npiece && (v[u].x | v[u].y | v[u].z | v[u].w)) {  // outlier columns are rare
-                    const int pc = q % ncb;
-                    if (v[u].x) atomicOr(&mw[pc * 4 + 0], v[u].x);
-                    if (v[u].y) atomicOr(&mw[pc * 4 + 1], v[u].y);
-                    if (v[u].z) atomicOr(&mw[pc * 4 + 2], v[u].z);
-                    if (v[u].w) atomicOr(&mw[pc * 4 + 3], v[u].w);
-                }
-            }
-        }
-    }
-    __syncthreads();
-
-    // ---- positions of the qualifying columns in the ascending order: prefix sums of popcounts
-    constexpr int PER_MAX = (2 * LLMINT8_MAX_H_BLOCKS + 255) / 256;
-    const int per = (nwords + 255) / 256;  // consecutive words per thread
-    unsigned long long mk[PER_MAX];
-    int pc = 0;
-#pragma unroll
-    for (int e = 0; e < PER_MAX; e++) {
-        const int l = tid * per + e;
-        mk[e] = (e < per && l < nwords) ? s_mask[l] : 0ull;
-        pc += __popcll(mk[e]);
-    }
-    int incl = pc;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int t = __shfl_up(incl, d);
-        if (lane >= d) incl += t;
-    }
-    if (lane == 63) s_wsum[w] = incl;
-    __syncthreads();
-    int woff = 0, total = 0;
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-        if (q < w) woff += s_wsum[q];
-        total += s_wsum[q];
-    }
-    const int cnt = total < cap ? total : cap;
-    const bool big = cnt > IDX_SLOTS;
-    const bool all_slow = total > cap || big;  // columns beyond cap are ordinary ones: their large entries belong to c_x
-    {
-        int pos = woff + incl - pc;
-#pragma unroll
-        for (int e = 0; e < PER_MAX; e++) {
-            const int l = tid * per + e;
-            if (e < per && l < nwords) {  // only this thread reads or writes word l here
-                unsigned long long m = mk[e], eff = 0;
-                s_pos[l] = pos;
-                while (m) {
-                    const int b = __builtin_ctzll(m);
-                    m &= m - 1;
-                    if (pos < cap) {
-                        eff |= 1ull << b;
-                        if (pos < IDX_SLOTS) s_idx[pos] = l * 64 + b;
-                        if (first) idx[pos] = l * 64 + b;
-                    }
-                    pos++;
-                }
-                s_mask[l] = eff;
-            }
-        }
-    }
-    if (first && tid == 0) {
-        *count = cnt;
-        if (status) *status = total > cap ? 1 : 0;
-    }
-    __syncthreads();
-
-    // ---- row constants.  Thread (i, q): row i of the tile, 8 threads per row.
-    {
-        const int i = tid >> 3, q = tid & 7;
-        const int row = row0 + i;
-        const unsigned short* xr = X + (size_t)(row < s ? row : 0) * h;
-        unsigned m1 = 0, mo = 0;
-#pragma unroll
-        for (int g = 0; g < 8; g++) m1 = s_part[g][i] > m1 ? s_part[g][i] : m1;
-        if (row < s && !big) {
-            for (int t = q; t < cnt; t += 8) {
-                const unsigned short v = xr[s_idx[t]];
-                const unsigned a = v & 0x7fffu;
-                if (a < thr) mo = a > mo ? a : mo;
-                if (grp == 0) Xo[(size_t)row * opad + t] = v;
-            }
-        }
-        if (row < s && grp == 0)
-            for (int t = cnt + q; t < opad; t += 8) Xo[(size_t)row * opad + t] = 0;
-#pragma unroll
-        for (int d = 1; d <= 4; d <<= 1) {
-            const unsigned t2 = (unsigned)__shfl_xor((int)mo, d);
-            mo = t2 > mo ? t2 : mo;
-        }
-        const bool need = row < s && (all_slow || (mo >= m1 && m1 > 0));
-        if (q == 0) {
-            s_again[i] = need ? 1 : 0;
-            s_cx[i] = (row < s && !need) ? m1 : 0u;
-        }
-    }
-    __syncthreads();
-    // rare: rows whose largest below-threshold magnitude may sit in an outlier column (or all rows when more
-    // columns qualify than count): the workgroup scans such a row again without the outlier columns
-    for (int r = 0; r < 32; r++) {
-        if (!s_again[r]) continue;  // uniform
-        const unsigned short* row2 = X + (size_t)(row0 + r) * h;
-        unsigned m = 0;
-        for (int c0 = tid * 8; c0 < h; c0 += 2048) {
-            const us8 v = *(const us8*)(row2 + c0) & (unsigned short)0x7fff;
-            const unsigned bits = (unsigned)(s_mask[c0 >> 6] >> (c0 & 63)) & 0xffu;
-#pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const unsigned x = ((bits >> e) & 1u) ? 0u : (unsigned)v[e];
-                m = x > m ? x : m;
-            }
-        }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            const unsigned t = (unsigned)__shfl_xor((int)m, d);
-            m = t > m ? t : m;
-        }
-        if (lane == 0) s_red[w] = m;
-        __syncthreads();
-        if (tid == 0) {
-            const unsigned a = s_red[0] > s_red[1] ? s_red[0] : s_red[1];
-            const unsigned b = s_red[2] > s_red[3] ? s_red[2] : s_red[3];
-            s_cx[r] = a > b ? a : b;
-        }
-        if (big && grp == 0) {  // more outlier columns than the LDS list holds: gather straight from the masks
-            for (int l = tid; l < nwords; l += 256) {
-                unsigned long long mm = s_mask[l];
-                int pos = s_pos[l];
-                while (mm) {
-                    const int b = __builtin_ctzll(mm);
-                    mm &= mm - 1;
-                    Xo[(size_t)(row0 + r) * opad + pos] = row2[l * 64 + b];
-                    pos++;
-                }
-            }
-        }
-        __syncthreads();  // s_red is reused by the next row; s_cx[r] is published
-    }
-    if (grp == 0 && tid < 32 && row0 + tid < s) cx[row0 + tid] = (unsigned short)s_cx[tid];
-
-    // ---- codes of this workgroup's blocks of 32 rows x 256 features into the tiled layout; a block's
-    // registers are refilled with the block QF_PF further on as soon as its codes are staged
-    auto code_block = [&](auto J, int blk) {
-        constexpr int JJ = decltype(J)::value;
-        if (blk >= blk1) return;  // uniform
-        const int k = blk * 256 + kseg;
-        const unsigned bits = (k >> 6) < nwords ? (unsigned)(s_mask[k >> 6] >> (k & 63)) & 0xffu : 0u;
-#pragma unroll
-        for (int q = 0; q < 4; q++) {
-            const int r = q * 8 + (tid >> 5);
-            const float c = f16_bits_to_float((unsigned short)s_cx[r]);  // 0 for rows past the matrix
-            const float rc = c > 0.0f ? 1.0f / c : 0.0f;
-            unsigned lo = 0, hi = 0;
-#pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const int qv = (c > 0.0f && !((bits >> e) & 1u)) ? q8(f16_bits_to_float(xv[JJ][q][e]), c, rc) : 0;
-                const unsigned byte = (unsigned)qv & 0xffu;
-                if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
-            }
-            u2 pk = {lo, hi};
-            *(u2*)(stage + (kseg >> 5) * TILE_BYTES + tile_byte(r, kseg & 31)) = pk;
-        }
-        load_tile(J, blk + QF_PF);
-        __syncthreads();
-        const int kt0 = blk * 8;
-#pragma unroll
-        for (int half = 0; half < 2; half++) {
-            const int off = half * 4096 + tid * 16;
-            if (kt0 + (off >> 10) < KT)
-                *(u4*)(Xq + ((size_t)rt * KT + kt0) * TILE_BYTES + off) = *(const u4*)(stage + off);
-        }
-        __syncthreads();  // the staging buffer is reused by the next block
-    };
-    for (int blk = blk0; blk < blk1; blk += QF_PF) {
-        code_block(std::integral_constant<int, 0>{}, blk);
-        code_block(std::integral_constant<int, 1>{}, blk + 1);
-        code_block(std::integral_constant<int, 2>{}, blk + 2);
-        code_block(std::integral_constant<int, 3>{}, blk + 3);
-    }
-}
-
-// Row slabs of the scan: enough workgroups (column blocks x slabs) to cover the chip about three times, at
-// least 64 rows each.  The masks every quantizer workgroup ORs together are then slabs x h / 8 bytes, a few
-// KiB whatever the shape.
-int prepass_slabs(int s, int h, int* rows_per_slab)
-{
-    const int ncb = (h + SC_CW - 1) / SC_CW;
-    int n = (768 + ncb - 1) / ncb;
-    const int most = (s + 63) / 64;
-    n = n > most ? most : n;
-    n = n < 1 ? 1 : n;
-    const int rps = (((s + n - 1) / n) + 15) & ~15;
-    *rows_per_slab = rps;
-    return (s + rps - 1) / rps;
-}
-
-hipError_t launch_prepass_fused(const void* X, int s, int h, unsigned thr, unsigned char* smask,
-                                unsigned short* rowpart, int32_t* idx, int cap, int32_t* count, int32_t* status,
-                                unsigned short* cx, unsigned short* Xo, int8_t* Xq, hipStream_t st)
-{
-    const int ncb = (h + SC_CW - 1) / SC_CW, KT = k_tiles(h), RT = row_tiles(s);
-    const int pitch = ncb * 16;
-    int rps = 0;
-    const int nslab = prepass_slabs(s, h, &rps);
-    scan_slab_kernel<<<dim3(ncb, nslab), 256, 0, st>>>((const unsigned short*)X, s, h, thr, rps, smask, pitch, rowpart);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    // feature groups: enough workgroups to cover the chip two or three times, each with a run of whole blocks
-    // (the prologue is repeated by every workgroup: few, long runs keep it small against the payload)
-    const int nblk = (KT + 7) / 8;
-    int G = (640 + RT - 1) / RT;
-    G = G < 1 ? 1 : (G > nblk ? nblk : G);
-    const int bpg = (nblk + G - 1) / G;
-    G = (nblk + bpg - 1) / bpg;
-    const size_t shm = (size_t)2 * ncb * (sizeof(unsigned long long) + sizeof(int));
-    quantize_fused_kernel<<<dim3(RT, G), 256, shm, st>>>((const unsigned short*)X, s, h, thr, smask, pitch, nslab, rowpart,
-                                                         ncb, cap, opad_of(cap), bpg, KT, idx, count, status, cx, Xo, Xq);
-    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------

@@ -333,21 +333,10 @@ def test_linear_prefill_sizes():
     linear_compare(wl.make_custom(48, 256, 64, 0, seed=47), alpha=float("inf"))
 
 
-@pytest.fixture
-def forced_prepass():
-    import paper_2208_07339_amd as L
-    yield L.debug_prepass
-    L.debug_prepass(-1)
-
-
-@pytest.mark.parametrize("mode", [0, 1])
-def test_both_prepasses_of_the_one_call_path(mode, forced_prepass):
-    """llmint8_linear for s > 32 has two pre-passes (scan by row slabs + lists + row constants + quantizer;
-    column-complete scan + fused quantizer) and picks one from the shape: each of them forced, on shapes
-    that take every branch: several row groups per scan workgroup, a single 64-column block, ragged K,
-    |O| > cap, every column an outlier, more outlier columns than the fused kernel lists in LDS (with and
+def test_linear_prefill_branches_of_the_prepass():
+    """llmint8_linear for s > 32 on shapes that take every branch of its pre-pass: several row slabs, a single
+    512-column block, ragged K, |O| > cap, every column an outlier, thousands of outlier columns (with and
     without overflow), rows that are all zero, no outlier at all."""
-    forced_prepass(mode)
     linear_compare(wl.make_custom(100, 512, 256, 3, seed=41))
     linear_compare(wl.make_custom(300, 1000, 520, 4, seed=42))
     linear_compare(wl.make_custom(257, 4160, 264, 6, seed=43))
@@ -366,11 +355,9 @@ def test_both_prepasses_of_the_one_call_path(mode, forced_prepass):
     linear_compare(d)
 
 
-@pytest.mark.parametrize("mode", [0, 1])
-def test_linear_row_maximum_inside_an_outlier_column(mode, forced_prepass):
+def test_linear_row_maximum_inside_an_outlier_column():
     """Rows whose largest magnitude below alpha sits in an outlier column (alone, or tied with a regular
     column): the row constant must come from the regular columns only."""
-    forced_prepass(mode)
     d = wl.make_custom(200, 1024, 128, 4, seed=51)
     X = d["X"]
     j0, j1 = int(d["planted"][0]), int(d["planted"][-1])
