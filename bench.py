@@ -59,7 +59,8 @@ def to_dev(a):
     return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
 
 
-def run_workload(name, steps, warmup, copies=1, int8_rows=False, granularity="vectorwise", alpha=None, ceilings=True):
+def run_workload(name, steps, warmup, copies=1, int8_rows=False, granularity="vectorwise", alpha=None, ceilings=True,
+                 hold=None):
     import torch
 
     import paper_2208_07339_amd as L
@@ -127,6 +128,20 @@ def run_workload(name, steps, warmup, copies=1, int8_rows=False, granularity="ve
     # whole steps from the events: start of step i to start of step i + 1 (the last one to its own end)
     st = np.array([evs[i][0].elapsed_time(evs[i + 1][0]) for i in range(steps - 1)] + [evs[-1][0].elapsed_time(evs[-1][2])])
     ceil = measured_ceiling(L, torch, name, qws, rows) if ceilings else None
+    if hold:  # keep this load on the GPU for an outside power / clock sampler
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        zeros = torch.zeros(1 << 20, dtype=torch.int8, device="cuda")
+        t_end, n = time.perf_counter() + hold[1], 0
+        while time.perf_counter() < t_end:
+            for _ in range(64):
+                if hold[0] == "steps":
+                    step(n)
+                elif hold[0] == "probe":
+                    L.probe_mfma(qws[0].Wq, rows.Xq, 400, sink)
+                else:
+                    L.probe_mfma(zeros, zeros, 400, sink)
+                n += 1
+            torch.cuda.synchronize()
     return dict(name=name, s=s, h=h, o=o, n_out=n_out, planted=len(d["planted"]), ms_step=ms_step,
                 ms_prepass=ms_pre, ms_matmul=float(mm.mean()), ms_matmul_median=float(np.median(mm)),
                 ms_matmul_min=float(mm.min()), ms_step_median=float(np.median(st)), ms_step_min=float(st.min()),
@@ -289,6 +304,11 @@ def main():
     ap.add_argument("--quantizer", default="absmax", choices=["absmax", "zeropoint"],
                     help="zeropoint: the asymmetric quantization of Eq. 1-5 per row of X / column of W (Table 1's "
                          "zeropoint rows; measured separately, not the headline)")
+    ap.add_argument("--hold", default=None, choices=["steps", "probe", "probe-zeros"],
+                    help="after the measurement keep the GPU busy for --hold-seconds with back-to-back steps of the "
+                         "workload, or launches of the MFMA issue loop on its codes / on zeros, so that an outside "
+                         "sampler (amd-smi metric --power --clock) can read socket power and clocks under that load")
+    ap.add_argument("--hold-seconds", type=float, default=8.0)
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three device-to-device copies of 256 MiB first: under rocprofv3 --pmc their "
                          "FETCH_SIZE / WRITE_SIZE readings calibrate the counters (paper_2208_07339_amd/pmc_summary.py)")
@@ -327,7 +347,8 @@ def main():
         return
     i8 = a.outlier_rows == "int8"
     res = run_workload(a.workload, a.steps, a.warmup, copies=2 if a.workload == "decode" else 1, int8_rows=i8,
-                       granularity=a.granularity, alpha=a.alpha, ceilings=not a.no_ceilings)
+                       granularity=a.granularity, alpha=a.alpha, ceilings=not a.no_ceilings,
+                       hold=(a.hold, a.hold_seconds) if a.hold else None)
     s, h, o = res["s"], res["h"], res["o"]
     ops = 2.0 * s * h * o
     line = {

@@ -4,7 +4,8 @@ import os
 from dataclasses import dataclass
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libllmint8.so")
+# LLMINT8_LIB names another build of the same library (the measurement build libllmint8_stamps.so)
+LIB_PATH = os.environ.get("LLMINT8_LIB") or os.path.join(HERE, "libllmint8.so")
 
 SYMBOLS = [
     "llmint8_status_string", "llmint8_last_hip_error", "llmint8_opad", "llmint8_wq_bytes", "llmint8_xq_bytes",

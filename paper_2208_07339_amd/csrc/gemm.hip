@@ -83,6 +83,23 @@ struct GemmArgs {
 // slots of the epilogue stages), so a tile does not start with an empty
 // pipeline.  Ring slots are addressed relative to a per-tile base for that.
 // ---------------------------------------------------------------------------
+// Measurement build (-DLLMINT8_GEMM_STAMPS, a library of its own: see build.py): every wave of one workgroup
+// records the shader clock at the phase boundaries of its second tile.  Stamp k of wave w is g_stamps[w][k]:
+//   0 tile start, 1 first stage in LDS, 2 K loop done, 3 epilogue operands in LDS, 4 next tile's first two
+//   stages requested, 5 row constants / outlier columns of X in registers, then per pass over two column
+//   tiles (p = 0, 1): 6+6p column constants / outlier rows of W in registers, and per 64 x 64 block (q = 0, 1)
+//   7+6p+2q dequantized and staged, 8+6p+2q written out; 20 tile done.
+// In the product build the macro is empty.
+#ifdef LLMINT8_GEMM_STAMPS
+__device__ long long g_stamps[4][32];
+#define STAMP(k)                                                                                  \
+    do {                                                                                          \
+        if (blockIdx.x == 9 && lane == 0 && pos == (int)(blockIdx.x >> 3) + gx) g_stamps[w][k] = clock64(); \
+    } while (0)
+#else
+#define STAMP(k) do { } while (0)
+#endif
+
 constexpr int NB = 4;
 constexpr int OSLOTS = 32;  // outlier slots staged through LDS; more are read from memory directly
 
@@ -267,7 +284,8 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         const unsigned vo = MODE == 0 ? stage_off(st + NB) : 0u;
 #pragma unroll
         for (int i = 0; i < NMFMA; i++) {
-            const int c = i / (WA * WB), a = (i / WB) % WA, b = i % WB;
+            // boustrophedon over the WA x WB tiles: consecutive MFMAs share one operand register set
+            const int c = i / (WA * WB), a = (i / WB) % WA, b = (a & 1) ? WB - 1 - i % WB : i % WB;
             acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(RP[SS][c][a], RQ[SS][c][b], acc[a][b], 0, 0, 0);
             FENCE();
 #pragma unroll
@@ -302,7 +320,9 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         // epilogue can only make this wait longer).  The barrier also tells that every wave is done with
         // the previous tile's epilogue stages, whose slots take stages 2 and 3 (with nst == 2: this
         // tile's own epilogue stages) once stage 0 is on its way into registers.
+        STAMP(0);
         STAGE_SYNC(PIECES);
+        STAMP(1);
 #pragma unroll
         for (int i = 0; i < NRD; i++) rd(I0_{}, sbase, i);
         FENCE();
@@ -321,7 +341,9 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         }
         stage(I0_{}, std::integral_constant<int, 3>{}, st);
         stage(I1_{}, std::integral_constant<int, 4>{}, st + 1);
+        STAMP(2);
         STAGE_SYNC(0);  // the epilogue stages have landed, every wave is done with the operand slots
+        STAMP(3);
 
         const int eslot = (sbase + nst) % NB;  // 0 or 2; the second epilogue stage follows it
         const bool has_next = pos + gx < n_x;
@@ -332,6 +354,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
             issue_stage(1, (eslot + 3) % NB);
         }
 
+        STAMP(4);
         // ---- epilogue ----------------------------------------------------------
         // acc[a][b][r] of lane l: token i = I0 + b*32 + (l & 31),
         //                         column j = J0 + a*32 + 8*(r >> 2) + 4*(l >> 5) + (r & 3)
@@ -429,6 +452,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_wave_barrier();
             }
+            STAMP(5);
             int unit = 0;
 #pragma unroll
             for (int a0 = 0; a0 < WA; a0 += 2) {
@@ -467,6 +491,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                         wa[aa][1] = cnt > 16 ? load_w_mem(cJ0w + jl + ll, 16) : (v8h)(0);
                     }
                 }
+                STAMP(6 + 6 * (a0 / 2));
 #pragma unroll
                 for (int b0 = 0; b0 < WB; b0 += 2, unit++) {
                     int8_t* sb = stg + (unit % NSTG) * 8192;
@@ -529,6 +554,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                     }
                     // The staged values are read back by other lanes of the same wave, through pointers of another
                     // type: LDS serves a wave's requests in order, the compiler must not reorder them either.
+                    STAMP(7 + 6 * (a0 / 2) + 2 * (b0 / 2));
                     asm volatile("" ::: "memory");
                     // ---- write the staged block: a lane moves 16 bytes, 8 lanes cover a token's 128 bytes
 #pragma unroll
@@ -551,6 +577,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                         }
                     }
                     asm volatile("" ::: "memory");  // the next block's staging writes stay behind these reads
+                    STAMP(8 + 6 * (a0 / 2) + 2 * (b0 / 2));
                 }
             }
         };
@@ -563,6 +590,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                 epilogue(std::false_type{});
         }
 
+        STAMP(20);
         if (!has_next) break;
         sbase = (eslot + 2) % NB;
         pos += gx;
@@ -691,3 +719,11 @@ hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const
 }
 
 }  // namespace llmint8
+
+#ifdef LLMINT8_GEMM_STAMPS
+// measurement build only: the 4 x 32 clock stamps of the last launch (host buffer of 128 long long)
+extern "C" int llmint8_debug_read_stamps(long long* out)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(llmint8::g_stamps), sizeof(long long) * 4 * 32);
+}
+#endif

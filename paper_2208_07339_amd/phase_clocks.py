@@ -1,0 +1,62 @@
+"""Shader-clock stamps at the phase boundaries of one tile of the prefill GEMM.
+
+    python -m paper_2208_07339_amd.build --stamps        # builds libllmint8_stamps.so (measurement build)
+    LLMINT8_LIB=paper_2208_07339_amd/libllmint8_stamps.so python -m paper_2208_07339_amd.phase_clocks [workload]
+
+Runs 300 back-to-back calls of llmint8_linear on the workload (default ffn13b), then prints, for each of the
+four waves of one workgroup, the clocks spent in each phase of that workgroup's second tile (so the workload
+must give every workgroup at least two tiles: ffn13b, ffn175b_down), and the K loop's clocks per stage against
+the clocks its MFMAs alone need (32 per v_mfma_i32_32x32x32_i8).
+"""
+import ctypes as C
+import sys
+
+import numpy as np
+
+
+PHASES = [(0, 1, "wait for the first stage"), (1, 2, "K loop"), (2, 3, "wait for the epilogue operands"),
+          (3, 4, "request the next tile's first two stages"), (4, 5, "row constants, outlier columns of X"),
+          (5, 20, "dequantize + outlier product + store (four 64 x 64 blocks)")]
+
+
+def main():
+    import torch
+
+    import paper_2208_07339_amd as L
+    from paper_2208_07339_amd import workloads as wl
+    if not hasattr(L.lib(), "llmint8_debug_read_stamps"):
+        sys.exit("this library has no clock stamps: build with `python -m paper_2208_07339_amd.build --stamps` and "
+                 "set LLMINT8_LIB to libllmint8_stamps.so")
+    name = sys.argv[1] if len(sys.argv) > 1 else "ffn13b"
+    d = wl.make(name)
+    s, h, o = d["s"], d["h"], d["o"]
+    X = torch.from_numpy(d["X"].view(np.int16)).cuda().view(torch.float16)
+    W = torch.from_numpy(d["W"].view(np.int16)).cuda().view(torch.float16)
+    ws = L.Workspace.allocate(s, h, o, 32)
+    qw = L.quantize_weight(W, ws)
+    outl = L.find_outliers(X, d["alpha"], 32, ws)
+    rows = L.quantize_rows(X, outl)
+    out = torch.empty((s, o), dtype=torch.float16, device="cuda")
+    for _ in range(300):
+        L.linear(X, qw, d["alpha"], outl, rows, ws, out)
+    torch.cuda.synchronize()
+    buf = (C.c_longlong * 128)()
+    fn = L.lib().llmint8_debug_read_stamps
+    fn.argtypes = [C.c_void_p]
+    assert fn(buf) == 0
+    t = np.array(list(buf), dtype=np.int64).reshape(4, 32)
+    if not t[:, 20].all():
+        sys.exit(f"{name}: no workgroup has a second tile, nothing was stamped")
+    stages = 2 * ((h + 127) // 128)
+    print(f"{name}: s={s} h={h} o={o}, {stages} K stages per tile; clocks of the second tile of workgroup 9, waves 0-3")
+    for a, b, what in PHASES:
+        print(f"  {what:62s} " + " ".join(f"{int(t[w, b] - t[w, a]):8d}" for w in range(4)))
+    total = t[:, 20] - t[:, 0]
+    kloop = t[:, 2] - t[:, 1]
+    print(f"  {'whole tile':62s} " + " ".join(f"{int(v):8d}" for v in total))
+    print(f"  K loop per stage: {kloop.mean() / stages:.0f} clocks; share of the tile outside the K loop: "
+          f"{100 * (1 - kloop.mean() / total.mean()):.1f} %")
+
+
+if __name__ == "__main__":
+    main()
