@@ -40,6 +40,46 @@ __device__ inline double zp_range(unsigned lohi)
            (double)f16_bits_to_float((unsigned short)(lohi & 0xffffu));
 }
 
+// fp16( q * c_w / 127 ) for an int8 code q and a column constant given as fp16 bits, rounded once to nearest
+// even: a weight rebuilt from its code (the variant that keeps no 16-bit weights).
+// The exact quotient in 32-bit integer arithmetic: c_w = m * 2^E with an 11-bit m, so the value is
+// (|q| * m / 127) * 2^E.  |q| * m (18 bits) is shifted up until its leading one sits at bit 30, which leaves
+// the quotient by 127 with 24 or 25 significant bits, more than the 11 + 1 the rounding looks at; the
+// division keeps its remainder as a sticky bit.  (Checked against 64-bit arithmetic for every code and every
+// finite constant.)
+__device__ inline unsigned short dequant_bits(int q, unsigned cwb)
+{
+    cwb &= 0x7fffu;
+    if (q == 0 || cwb == 0) return 0;
+    const unsigned sign = q < 0 ? 0x8000u : 0u;
+    const unsigned a = (unsigned)(q < 0 ? -q : q);
+    const unsigned e = cwb >> 10, f = cwb & 0x3ffu;
+    const unsigned m = e ? 1024u + f : f;
+    const int E = e ? (int)e - 25 : -24;
+    const unsigned t = a * m;
+    const int sh0 = __builtin_clz(t) - 1;
+    const unsigned tn = t << sh0;                  // value = tn / 127 * 2^(E - sh0)
+    const unsigned Q = tn / 127u, R = tn % 127u;
+    const int msb = 31 - __builtin_clz(Q);         // 23 or 24
+    int ev = msb + E - sh0;                        // value in [2^ev, 2^(ev+1))
+    const bool normal = ev >= -14;
+    const int sh = normal ? msb - 10 : sh0 - E - 24;  // Q / 2^sh counts fp16 quanta (2^(ev-10), or 2^-24 for subnormals); 13 .. 30
+    unsigned mant = Q >> sh;
+    const unsigned rem = Q & ((1u << sh) - 1u), half = 1u << (sh - 1);
+    if (rem > half || (rem == half && (R != 0 || (mant & 1u)))) mant++;
+    unsigned bits;
+    if (normal) {
+        if (mant == 2048) {
+            mant = 1024;
+            ev++;
+        }
+        bits = ((unsigned)(ev + 15) << 10) | (mant - 1024);
+    } else {
+        bits = mant;  // 1024 here is the smallest normal number, as it should be
+    }
+    return (unsigned short)(sign | bits);
+}
+
 // Smallest magnitude bit pattern whose value is >= alpha (0 if alpha <= 0,
 // 0x7c00 if no finite fp16 reaches alpha).
 __host__ inline unsigned threshold_bits(float alpha)

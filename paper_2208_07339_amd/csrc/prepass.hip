@@ -1093,40 +1093,6 @@ hipError_t launch_quantize_rows_rowpart(const void* X, int s, int h, OutlierList
 // to nearest even of the exact quotient, zero rows for t >= |O|.
 // ---------------------------------------------------------------------------
 
-// The exact quotient in integer arithmetic: c_w = m * 2^E with an 11-bit m, so the value is
-// (|q| * m / 127) * 2^E; the division keeps its remainder as a sticky bit for the rounding.
-__device__ inline unsigned short dequant_bits(int q, unsigned cwb)
-{
-    cwb &= 0x7fffu;
-    if (q == 0 || cwb == 0) return 0;
-    const unsigned sign = q < 0 ? 0x8000u : 0u;
-    const unsigned a = (unsigned)(q < 0 ? -q : q);
-    const unsigned e = cwb >> 10, f = cwb & 0x3ffu;
-    const unsigned m = e ? 1024u + f : f;
-    const int E = e ? (int)e - 25 : -24;
-    const unsigned long long num = (unsigned long long)(a * m) << 20;  // value = num / 127 * 2^(E - 20)
-    const unsigned long long Q = num / 127u;
-    const unsigned R = (unsigned)(num % 127u);
-    const int msb = 63 - __builtin_clzll(Q);  // Q >= 2^20 / 127 > 0
-    int ev = msb + E - 20;                    // value in [2^ev, 2^(ev+1))
-    const bool normal = ev >= -14;
-    const int sh = normal ? msb - 10 : -(E + 4);  // Q / 2^sh counts fp16 quanta (2^(ev-10), or 2^-24 for subnormals)
-    unsigned long long mant = Q >> sh;
-    const unsigned long long rem = Q & ((1ull << sh) - 1ull), half = 1ull << (sh - 1);
-    if (rem > half || (rem == half && (R != 0 || (mant & 1ull)))) mant++;
-    unsigned bits;
-    if (normal) {
-        if (mant == 2048) {
-            mant = 1024;
-            ev++;
-        }
-        bits = ((unsigned)(ev + 15) << 10) | (unsigned)(mant - 1024);
-    } else {
-        bits = (unsigned)mant;  // 1024 here is the smallest normal number, as it should be
-    }
-    return (unsigned short)(sign | bits);
-}
-
 __global__ void __launch_bounds__(256) dequant_rows_kernel(const int8_t* __restrict__ Wq,
                                                            const unsigned short* __restrict__ cw, int h, int o, int KT,
                                                            const int32_t* __restrict__ idx,
