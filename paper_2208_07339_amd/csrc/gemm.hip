@@ -84,7 +84,7 @@ struct GemmArgs {
 // pipeline.  Ring slots are addressed relative to a per-tile base for that.
 // ---------------------------------------------------------------------------
 // Measurement build (-DLLMINT8_GEMM_STAMPS, a library of its own: see build.py): every wave of one workgroup
-// records the shader clock at the phase boundaries of its second tile.  Stamp k of wave w is g_stamps[w][k]:
+// records the shader clock at the phase boundaries of its second tile (its only tile, if it has one).  Stamp k of wave w is g_stamps[w][k]:
 //   0 tile start, 1 first stage in LDS, 2 K loop done, 3 epilogue operands in LDS, 4 next tile's first two
 //   stages requested, 5 row constants / outlier columns of X in registers, then per pass over two column
 //   tiles (p = 0, 1): 6+6p column constants / outlier rows of W in registers, and per 64 x 64 block (q = 0, 1)
@@ -94,7 +94,7 @@ struct GemmArgs {
 __device__ long long g_stamps[4][32];
 #define STAMP(k)                                                                                  \
     do {                                                                                          \
-        if (blockIdx.x == 9 && lane == 0 && pos == (int)(blockIdx.x >> 3) + gx) g_stamps[w][k] = clock64(); \
+        if (blockIdx.x == 9 && lane == 0 && pos == stamp_pos) g_stamps[w][k] = clock64();                   \
     } while (0)
 #else
 #define STAMP(k) do { } while (0)
@@ -104,10 +104,10 @@ constexpr int NB = 4;
 constexpr int OSLOTS = 32;  // outlier slots staged through LDS; more are read from memory directly
 
 //
-// ZP: zeropoint constants (Eq. 1-5) in place of c_x / c_w.  Every tile then takes the guarded
-// epilogue, which reads its operands from memory, adds the correction terms of the unrolled
-// product of Eq. 5 to the accumulators (in double: with zeropoints far from 0 they are large and
-// cancel) and divides by nd_x nd_w.
+// ZP: zeropoint constants (Eq. 1-5) in place of c_x / c_w.  The epilogue adds the correction terms of
+// the unrolled product of Eq. 5 to the accumulators (in double: with zeropoints far from 0 they are
+// large and cancel) and divides by nd_x nd_w.  The records of the tile's tokens and the three planes
+// of column factors travel through the epilogue stages like the absmax constants do.
 template <int WA, int WB, bool ZP>
 __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
 {
@@ -120,7 +120,9 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     constexpr int OPSPAN = NMFMA;                // MFMA slots of a stage that carry its requests and LDS reads
     constexpr int NEW = 16;                      // epilogue-stage pieces holding W rows: [32 slots][256 columns] fp16
     constexpr int NEX = 4 * WB;                  // pieces holding Xo: [64*WB tokens][opad <= 32 slots] fp16
-    static_assert(NEW + NEX + 1 <= 8 * PIECES, "epilogue operands must fit two stages");
+    constexpr int NZX = ZP ? WB : 0;             // zeropoint: pieces holding the tokens' records, 64 of 16 bytes each
+    constexpr int NZP = ZP ? (WA + 1) / 2 : 0;   // zeropoint: pieces per plane of column factors, 128 doubles each
+    static_assert(NEW + NEX + 1 + NZX + 3 * NZP <= 8 * PIECES, "epilogue operands must fit two stages");
 
     extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -139,6 +141,9 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     const int gx = ((int)gridDim.x - xcd + 7) >> 3;                              // workgroups on this XCD
     int pos = blockIdx.x >> 3;
     if (pos >= n_x) return;
+#ifdef LLMINT8_GEMM_STAMPS
+    const int stamp_pos = pos + (pos + gx < n_x ? gx : 0);
+#endif
 
     int cnt = *g.count;
     cnt = cnt < 0 ? 0 : (cnt > g.cap ? g.cap : cnt);
@@ -171,7 +176,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         const int qi = q0 + inband - pj * bh;
         J0w = pj * 64 * WA;
         I0w = qi * 64 * WB;
-        interior = !ZP && g.fast_ok && !g.Cdbg && opad <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 64 * WB <= s);
+        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 64 * WB <= s);
 #pragma unroll
         for (int k = 0; k < PIECES; k++) {
             const int p = w * PIECES + k;
@@ -199,7 +204,9 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     // Source of piece n (0 .. 8*PIECES-1) of the epilogue stages, per lane.  Layout of the two stages:
     // pieces 0..15: rows O of W_f16, [32 slots][256 columns] (a slot row is 512 bytes whatever WA is; lanes past
     // the tile's 64*WA columns repeat chunk 0); then 4*WB pieces of Xo, [64*WB tokens][opad slots] as it lies in
-    // memory; then one piece with c_w (lanes 0-31) and c_x (lanes 32-63); the rest repeats that piece.
+    // memory; then one piece with c_w (lanes 0-31) and c_x (lanes 32-63).  Zeropoint: that piece is idle, and
+    // WB pieces with the records of the tile's tokens and 3 x NZP pieces with the planes of column factors
+    // follow.  Whatever is left of the two stages re-reads a harmless piece.
     auto esrc = [&](int n) -> const void* {
         // The addresses depend on the tile only; the opaque copy of the lane number keeps the compiler from
         // computing all of them at the start of the tile and carrying them through the K loop in registers.
@@ -216,9 +223,21 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
             const int pn = (n - NEW) * 32 < NEX * opad ? (n - NEW) : 0;  // opad == 16: half as many pieces
             return g.Xo + ((size_t)I0w * opad + pn * 512 + ln * 8);
         }
-        if (ln < 32) return g.cw + (J0w + wchunk);
-        const int c = (ln - 32) < 8 * WB ? (ln - 32) : 0;
-        return g.cx + (I0w + c * 8);
+        if constexpr (ZP) {
+            const int m = n - (NEW + NEX + 1);
+            if (m >= 0 && m < NZX) return g.zp.zcx + (I0w + m * 64 + ln);
+            if (m >= NZX && m < NZX + 3 * NZP) {
+                const int q = (m - NZX) / NZP, pp = (m - NZX) % NZP;
+                const int c = pp * 128 + 2 * ln;  // columns past the tile (odd WA) re-read the tile's first two
+                return g.zp.colc + ((size_t)q * g.zp.pitch + J0w + (c < 64 * WA ? c : 0));
+            }
+            return g.Xq + ln * 16;
+        } else {
+            if (n > NEW + NEX) return g.Xq + ln * 16;
+            if (ln < 32) return g.cw + (J0w + wchunk);
+            const int c = (ln - 32) < 8 * WB ? (ln - 32) : 0;
+            return g.cx + (I0w + c * 8);
+        }
     };
     // Request piece k of an operand stage into ring slot `slot`.  vo = byte offset of this lane within the
     // piece's row tile (stage * 2 KiB + lane * 16), the same for all pieces of a stage.  Uniform 64-bit base
@@ -371,6 +390,8 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         const int8_t* EX = E + NEW * TILE_BYTES;                                           // [64*WB][opad] fp16
         const unsigned short* ECw = (const unsigned short*)(E + (NEW + NEX) * TILE_BYTES); // [64*WA]
         const unsigned short* ECx = ECw + 256;                                             // [64*WB]
+        const int4* EZx = (const int4*)(E + (NEW + NEX + 1) * TILE_BYTES);                 // zeropoint: [64*WB] records
+        const double* EZc = (const double*)(E + (NEW + NEX + 1 + NZX) * TILE_BYTES);       // 3 planes of NZP*128 doubles
         // output staging behind the ring (the ring slots are busy with the next tile): 8 KiB per wave
         constexpr int NSTG = 1;
         int8_t* stg = lds + NB * STAGE + w * (8192 * NSTG);
@@ -421,7 +442,14 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                 const int il = wq * 32 * WB + b * 32 + ll;  // token within the workgroup tile
                 const int i = cI0w + il;
                 if (FAST) {
-                    sx[b] = f16_bits_to_float(ECx[il]) * (1.0f / 16129.0f);
+                    if constexpr (ZP) {
+                        const int4 rec = EZx[il];
+                        zsa[b] = zp_range((unsigned)rec.x) * (1.0 / 254.0);
+                        zza[b] = (double)rec.y;
+                        zrs[b] = (double)rec.z;
+                    } else {
+                        sx[b] = f16_bits_to_float(ECx[il]) * (1.0f / 16129.0f);
+                    }
                     xb[b][0] = *(const v8h*)(EX + il * (2 * opad) + gl * 16);
                     xb[b][1] = (v8h)(0);
                     if (cnt > 16) xb[b][1] = *(const v8h*)(EX + il * (2 * opad) + (2 + gl) * 16);  // then opad == 32
@@ -441,8 +469,11 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
             // zeropoint: this wave's 32*WA columns of the three factor planes, copied once per tile into a
             // wave-private piece of the epilogue-stage slots (they hold nothing such tiles need, and are
             // not refilled before every wave has passed the barrier at the top of the next tile)
+            // (interior tiles find the planes of the whole workgroup tile in the epilogue stages instead)
             double* ZC = (double*)(lds + eslot * STAGE) + w * (3 * 32 * WA);
-            if constexpr (ZP) {
+            const double* zc0 = FAST ? EZc + wp * 32 * WA : ZC;  // this wave's first column in plane 0
+            const int zstride = FAST ? NZP * 128 : 32 * WA;     // doubles from plane to plane
+            if constexpr (ZP && !FAST) {
 #pragma unroll
                 for (int q = 0; q < 3; q++)
                     for (int c = lane_e; c < 32 * WA; c += 64)
@@ -465,13 +496,15 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                     if (aa >= na) break;
                     const int jl = wp * 32 * WA + (a0 + aa) * 32;  // first column of the MFMA tile within the workgroup tile
                     if (FAST) {
+                        if constexpr (!ZP) {
 #pragma unroll
-                        for (int rr = 0; rr < 4; rr++) {
-                            const uint2 pk = *(const uint2*)(ECw + jl + 8 * rr + 4 * gl);
-                            cwv[aa][4 * rr + 0] = f16_bits_to_float((unsigned short)(pk.x & 0xffff));
-                            cwv[aa][4 * rr + 1] = f16_bits_to_float((unsigned short)(pk.x >> 16));
-                            cwv[aa][4 * rr + 2] = f16_bits_to_float((unsigned short)(pk.y & 0xffff));
-                            cwv[aa][4 * rr + 3] = f16_bits_to_float((unsigned short)(pk.y >> 16));
+                            for (int rr = 0; rr < 4; rr++) {
+                                const uint2 pk = *(const uint2*)(ECw + jl + 8 * rr + 4 * gl);
+                                cwv[aa][4 * rr + 0] = f16_bits_to_float((unsigned short)(pk.x & 0xffff));
+                                cwv[aa][4 * rr + 1] = f16_bits_to_float((unsigned short)(pk.x >> 16));
+                                cwv[aa][4 * rr + 2] = f16_bits_to_float((unsigned short)(pk.y & 0xffff));
+                                cwv[aa][4 * rr + 3] = f16_bits_to_float((unsigned short)(pk.y >> 16));
+                            }
                         }
 #pragma unroll
                         for (int ks = 0; ks < 2; ks++)
@@ -535,7 +568,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
 #pragma unroll
                                 for (int r = 0; r < 16; r++) {
                                     const int c = a * 32 + 8 * (r >> 2) + 4 * gl + (r & 3);
-                                    const double cp = ZC[c], cq = ZC[32 * WA + c], cr = ZC[2 * 32 * WA + c];
+                                    const double cp = zc0[c], cq = zc0[zstride + c], cr = zc0[2 * zstride + c];
                                     d[r] += (float)(zsa[b] * __builtin_fma((double)acc[a][b][r], cp,
                                                                            __builtin_fma(zrs[b], cq, zza[b] * cr)));
                                 }
@@ -581,14 +614,10 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                 }
             }
         };
-        if constexpr (ZP) {
+        if (cinterior)
+            epilogue(std::true_type{});
+        else
             epilogue(std::false_type{});
-        } else {
-            if (cinterior)
-                epilogue(std::true_type{});
-            else
-                epilogue(std::false_type{});
-        }
 
         STAMP(20);
         if (!has_next) break;
@@ -699,7 +728,8 @@ hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const
     g.cap = cap; g.opad = opad_of(cap);
     g.Out = (_Float16*)Out; g.Cdbg = Cdbg;
     g.s = s; g.h = h; g.o = o;
-    g.fast_ok = (o % 8 == 0) && al16(cw) && al16(cx) && al16(Wf) && al16(Xo) && al16(Out);
+    g.fast_ok = (o % 8 == 0) && al16(cw) && al16(cx) && al16(Wf) && al16(Xo) && al16(Out) && al16(g.zp.zcx) &&
+                al16(g.zp.colc);
     const int forced = g_force_cfg.load(std::memory_order_relaxed);
     const int c = forced >= 0 ? forced : pick_cfg(s, o);
     if (zp) {

@@ -4,9 +4,10 @@
     LLMINT8_LIB=paper_2208_07339_amd/libllmint8_stamps.so python -m paper_2208_07339_amd.phase_clocks [workload]
 
 Runs 300 back-to-back calls of llmint8_linear on the workload (default ffn13b), then prints, for each of the
-four waves of one workgroup, the clocks spent in each phase of that workgroup's second tile (so the workload
-must give every workgroup at least two tiles: ffn13b, ffn175b_down), and the K loop's clocks per stage against
-the clocks its MFMAs alone need (32 per v_mfma_i32_32x32x32_i8).
+four waves of one workgroup, the clocks spent in each phase of that workgroup's second tile (its only tile
+where the workload gives it one: attn6p7b; then nothing is requested for a next tile), and the K loop's
+clocks per stage (its MFMAs alone need 32 clocks per v_mfma_i32_32x32x32_i8: 1024 per stage of a 256 x 256
+tile, 768 at 192 x 256, 512 at 128 x 256).
 """
 import ctypes as C
 import sys
@@ -46,9 +47,9 @@ def main():
     assert fn(buf) == 0
     t = np.array(list(buf), dtype=np.int64).reshape(4, 32)
     if not t[:, 20].all():
-        sys.exit(f"{name}: no workgroup has a second tile, nothing was stamped")
+        sys.exit(f"{name}: workgroup 9 has no tile, nothing was stamped")
     stages = 2 * ((h + 127) // 128)
-    print(f"{name}: s={s} h={h} o={o}, {stages} K stages per tile; clocks of the second tile of workgroup 9, waves 0-3")
+    print(f"{name}: s={s} h={h} o={o}, {stages} K stages per tile; clocks of one tile of workgroup 9, waves 0-3")
     for a, b, what in PHASES:
         print(f"  {what:62s} " + " ".join(f"{int(t[w, b] - t[w, a]):8d}" for w in range(4)))
     total = t[:, 20] - t[:, 0]

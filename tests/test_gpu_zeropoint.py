@@ -97,6 +97,27 @@ def test_zeropoint_on_one_sided_inputs(s, h, o, ncol, alpha):
         assert (ref["zp_x"] != 0).all()  # these rows are far from symmetric
 
 
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+def test_every_prefill_tile_shape(cfg):
+    """Each workgroup tile of the prefill GEMM in its zeropoint form, on grids with interior tiles (records and
+    column factors staged through LDS, stores without guards) next to edge tiles: 7 and 20 outlier columns, a
+    16-slot outlier buffer, one-sided and shifted inputs (zeropoints far from 0: the correction terms of Eq. 5
+    are large and cancel)."""
+    import paper_2208_07339_amd as L
+    L.debug_prefill_tile(cfg)
+    try:
+        d = wl.make_custom(512, 1024, 1024, 7, seed=91)
+        zp_compare(one_sided(d), d["W"], 6.0)
+        d = wl.make_custom(600, 640, 776, 20, seed=92)
+        zp_compare(one_sided(d, shift=1.5), d["W"], 6.0)
+        d = wl.make_custom(256, 256, 512, 3, seed=93)
+        zp_compare(one_sided(d), d["W"], 6.0, cap=8)
+        d = wl.make_custom(384, 512, 768, 0, seed=94)
+        zp_compare(one_sided(d, shift=-2.0), d["W"], INF)
+    finally:
+        L.debug_prefill_tile(-1)
+
+
 @pytest.mark.parametrize("s,h,o", [(16, 512, 256), (150, 384, 320)])
 def test_zeropoint_on_the_symmetric_recipe_and_a_shifted_one(s, h, o):
     d = wl.make_custom(s, h, o, 3, seed=77)
