@@ -37,6 +37,20 @@ __device__ __forceinline__ int zp_u(unsigned short xb, double D)
     return (int)__builtin_rint(254.0 * (double)f16_bits_to_float(xb) / D);
 }
 
+// The same u(x) without a division per element: with rD = the correctly rounded reciprocal of D (one
+// division per vector, by the caller), q = a rD is within an ulp of a / D (a = 254 x, exact), the fused
+// multiply-add gives the remainder a - q D exactly, and q + r rD rounds to the correctly rounded quotient
+// (Markstein's correction step; its one exception, a divisor whose significand is all ones, cannot occur:
+// D is a difference of two fp16 values and has at most 41 significant bits).  rint() then sees the same
+// double as in zp_u.
+__device__ __forceinline__ int zp_u_rcp(unsigned short xb, double D, double rD)
+{
+    const double a = 254.0 * (double)f16_bits_to_float(xb);
+    const double q = a * rD;
+    const double r = __builtin_fma(-q, D, a);
+    return (int)__builtin_rint(__builtin_fma(r, rD, q));
+}
+
 __device__ inline int4 make_const(unsigned kmin, unsigned kmax)
 {
     const unsigned lo = key_f16(kmin), hi = key_f16(kmax);
@@ -98,16 +112,18 @@ __global__ void __launch_bounds__(256) zp_quantize_weight_kernel(const unsigned 
     const int cg = tid & 31, sub = tid >> 5;
     const int j0 = jt0 * 32 + cg * 8;
     csum[tid] = 0;
-    double D[8];
+    double D[8], rD[8];
     int z[8], part[8];
 #pragma unroll
     for (int e = 0; e < 8; e++) {
         D[e] = 0.0;
+        rD[e] = 0.0;
         z[e] = 0;
         part[e] = 0;
         if (j0 + e < o) {
             const int4 r = zc[j0 + e];
             D[e] = zp_range((unsigned)r.x);
+            rD[e] = D[e] > 0.0 ? 1.0 / D[e] : 0.0;
             z[e] = r.y;
         }
     }
@@ -119,7 +135,7 @@ __global__ void __launch_bounds__(256) zp_quantize_weight_kernel(const unsigned 
 #pragma unroll
         for (int e = 0; e < 8; e++) {
             int qv = 0;  // padding rows and columns of the tiles stay zero
-            if (k < h && D[e] > 0.0) qv = zp_u(W[(size_t)k * o + j0 + e], D[e]) - z[e];
+            if (k < h && D[e] > 0.0) qv = zp_u_rcp(W[(size_t)k * o + j0 + e], D[e], rD[e]) - z[e];
             part[e] += qv;
             const int jj = cg * 8 + e;
             stage[(jj >> 5) * TILE_BYTES + tile_byte(jj & 31, kk)] = (int8_t)qv;
@@ -176,7 +192,8 @@ hipError_t launch_zp_quantize_weight(const void* W, int h, int o, int8_t* Wq, in
 __global__ void __launch_bounds__(256) zp_row_range_kernel(const unsigned short* __restrict__ X, int s, int h,
                                                            const int32_t* __restrict__ idx,
                                                            const int32_t* __restrict__ count, int cap, int opad,
-                                                           int4* __restrict__ zc, unsigned short* __restrict__ Xo)
+                                                           int4* __restrict__ zc, unsigned short* __restrict__ Xo,
+                                                           int vec_ok)
 {
     extern __shared__ unsigned bitmap[];  // ceil(h / 32) words, then 8 words of reduction space
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -202,12 +219,26 @@ __global__ void __launch_bounds__(256) zp_row_range_kernel(const unsigned short*
     }
     __syncthreads();
     unsigned kmin = 0xffffu, kmax = 0u;
-    for (int c = tid; c < h; c += 256)
-        if (!((bitmap[c >> 5] >> (c & 31)) & 1u)) {
-            const unsigned k = f16_key(row[c]);
-            kmin = k < kmin ? k : kmin;
-            kmax = k > kmax ? k : kmax;
+    if (vec_ok) {
+        for (int c0 = tid * 8; c0 < h; c0 += 2048) {
+            const us8 v = *(const us8*)(row + c0);
+            const unsigned bits = (bitmap[c0 >> 5] >> (c0 & 31)) & 0xffu;
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                if (!((bits >> e) & 1u)) {
+                    const unsigned k = f16_key(v[e]);
+                    kmin = k < kmin ? k : kmin;
+                    kmax = k > kmax ? k : kmax;
+                }
         }
+    } else {
+        for (int c = tid; c < h; c += 256)
+            if (!((bitmap[c >> 5] >> (c & 31)) & 1u)) {
+                const unsigned k = f16_key(row[c]);
+                kmin = k < kmin ? k : kmin;
+                kmax = k > kmax ? k : kmax;
+            }
+    }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
         const unsigned a = (unsigned)__shfl_xor((int)kmin, d), b = (unsigned)__shfl_xor((int)kmax, d);
@@ -236,7 +267,8 @@ __global__ void __launch_bounds__(256) zp_row_range_kernel(const unsigned short*
 __global__ void __launch_bounds__(256) zp_quantize_rows_kernel(const unsigned short* __restrict__ X, int s, int h,
                                                                const int32_t* __restrict__ idx,
                                                                const int32_t* __restrict__ count, int cap,
-                                                               int4* __restrict__ zc, int8_t* __restrict__ Xq, int KT)
+                                                               int4* __restrict__ zc, int8_t* __restrict__ Xq, int KT,
+                                                               int vec_ok)
 {
     __shared__ __attribute__((aligned(16))) int8_t stage[8 * TILE_BYTES];
     __shared__ unsigned bitmap[8];
@@ -261,17 +293,27 @@ __global__ void __launch_bounds__(256) zp_quantize_rows_kernel(const unsigned sh
         const int i = rt * 32 + r;
         double D = 0.0;
         int z = 0;
+        us8 v = (us8)(0);
         if (i < s) {
             const int4 rec = zc[i];
             D = zp_range((unsigned)rec.x);
             z = rec.y;
+            const unsigned short* row = X + (size_t)i * h;
+            if (vec_ok && k + 8 <= h) {
+                v = *(const us8*)(row + k);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    if (k + e < h) v[e] = row[k + e];
+            }
         }
+        const double rD = D > 0.0 ? 1.0 / D : 0.0;
         unsigned lo = 0, hi = 0;
         int part = 0;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
             int qv = 0;
-            if (D > 0.0 && k + e < h && !((bits >> e) & 1u)) qv = zp_u(X[(size_t)i * h + k + e], D) - z;
+            if (D > 0.0 && k + e < h && !((bits >> e) & 1u)) qv = zp_u_rcp(v[e], D, rD) - z;
             part += qv;
             const unsigned byte = (unsigned)qv & 0xffu;
             if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
@@ -298,11 +340,13 @@ hipError_t launch_zp_quantize_rows(const void* X, int s, int h, const int32_t* i
 {
     const int KT = k_tiles(h), RT = row_tiles(s);
     const size_t shm = ((size_t)(h + 31) / 32 + 8) * sizeof(unsigned);
-    zp_row_range_kernel<<<s, 256, shm, st>>>((const unsigned short*)X, s, h, idx, count, cap, opad_of(cap), zc, Xo);
+    const int vec_ok = (h % 8 == 0) && (((uintptr_t)X & 15) == 0);
+    zp_row_range_kernel<<<s, 256, shm, st>>>((const unsigned short*)X, s, h, idx, count, cap, opad_of(cap), zc, Xo,
+                                             vec_ok);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     zp_quantize_rows_kernel<<<dim3(RT, (KT * 32 + 255) / 256), 256, 0, st>>>((const unsigned short*)X, s, h, idx, count,
-                                                                            cap, zc, Xq, KT);
+                                                                            cap, zc, Xq, KT, vec_ok);
     return hipGetLastError();
 }
 
