@@ -592,3 +592,101 @@ def test_calls_on_two_streams_with_their_own_workspaces_do_not_disturb_each_othe
         for out in j["outs"]:
             assert_out_close(out.cpu().numpy(), ref["Out"])
         assert np.array_equal(bits(j["rows"].cx.cpu().numpy()), bits(ref["cx"]))
+
+
+def test_calls_from_two_host_threads():
+    """The library may be called from several threads (its one-time per-device set-up is taken under a lock):
+    two threads, each with its own stream, inputs and workspace, call llmint8_linear concurrently (ctypes
+    releases the interpreter lock during the call); every output is what the oracle gives for its input."""
+    import threading
+
+    import torch
+
+    import paper_2208_07339_amd as L
+    cap = 32
+    jobs, errors = [], []
+    for (s, h, o, ncol, seed) in [(300, 1024, 768, 4, 11), (200, 640, 520, 3, 12)]:
+        d = wl.make_custom(s, h, o, ncol, seed=seed)
+        Xd = torch.from_numpy(d["X"].view(np.int16)).cuda().view(torch.float16)
+        Wd = torch.from_numpy(d["W"].view(np.int16)).cuda().view(torch.float16)
+        ws = L.Workspace.allocate(s, h, o, cap)
+        qw = L.quantize_weight(Wd, ws)
+        outl = L.Outliers(torch.zeros(cap, dtype=torch.int32, device="cuda"),
+                          torch.zeros(1, dtype=torch.int32, device="cuda"),
+                          torch.zeros(1, dtype=torch.int32, device="cuda"), cap)
+        rows = L.QuantizedRows(torch.zeros(L.xq_bytes(s, h), dtype=torch.int8, device="cuda"),
+                               torch.zeros(s, dtype=torch.float16, device="cuda"),
+                               torch.zeros((s, L.opad(cap)), dtype=torch.float16, device="cuda"), s, h)
+        out = torch.zeros((s, o), dtype=torch.float16, device="cuda")
+        jobs.append(dict(d=d, Xd=Xd, qw=qw, ws=ws, outl=outl, rows=rows, out=out, st=torch.cuda.Stream()))
+    torch.cuda.synchronize()
+
+    def work(j):
+        try:
+            with torch.cuda.stream(j["st"]):
+                for _ in range(50):
+                    L.linear(j["Xd"], j["qw"], 6.0, j["outl"], j["rows"], j["ws"], out=j["out"])
+            j["st"].synchronize()
+        except Exception as e:  # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for j in jobs:
+        ref = oracle.linear(j["d"]["X"], j["d"]["W"], 6.0)
+        assert_out_close(j["out"].cpu().numpy(), ref["Out"])
+        assert np.array_equal(bits(j["rows"].cx.cpu().numpy()), bits(ref["cx"]))
+
+
+def test_graph_capture_after_init_only_in_a_fresh_process():
+    """llmint8_init does the whole per-device set-up, so a process may capture its very first call of any
+    shape: a fresh interpreter calls llmint8_init, captures llmint8_linear for a tiled shape and for a
+    weight-streaming shape without any eager call before, replays each twice and compares with an eager call."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = r'''
+import numpy as np, torch, sys
+sys.path.insert(0, %r)
+import paper_2208_07339_amd as L
+from paper_2208_07339_amd import workloads as wl
+torch.cuda.init()
+L.init()
+cap = 32
+for (s, h, o) in [(300, 640, 776), (16, 1024, 768)]:
+    d = wl.make_custom(s, h, o, 4, seed=5)
+    Xd = torch.from_numpy(d["X"].view(np.int16)).cuda().view(torch.float16)
+    Wd = torch.from_numpy(d["W"].view(np.int16)).cuda().view(torch.float16)
+    ws = L.Workspace.allocate(s, h, o, cap)
+    qw = L.quantize_weight(Wd, ws)
+    mk = lambda: (L.Outliers(torch.zeros(cap, dtype=torch.int32, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda"),
+                             torch.zeros(1, dtype=torch.int32, device="cuda"), cap),
+                  L.QuantizedRows(torch.zeros(L.xq_bytes(s, h), dtype=torch.int8, device="cuda"), torch.zeros(s, dtype=torch.float16, device="cuda"),
+                                  torch.zeros((s, L.opad(cap)), dtype=torch.float16, device="cuda"), s, h),
+                  torch.zeros((s, o), dtype=torch.float16, device="cuda"))
+    outl, rows, out = mk()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        L.linear(Xd, qw, 6.0, outl, rows, ws, out=out)
+    res = []
+    for _ in range(2):
+        out.fill_(7.0)
+        g.replay()
+        torch.cuda.synchronize()
+        res.append(out.clone())
+    outl2, rows2, out2 = mk()
+    L.linear(Xd, qw, 6.0, outl2, rows2, ws, out=out2)
+    torch.cuda.synchronize()
+    assert torch.equal(res[0].view(torch.int16), out2.view(torch.int16)) and torch.equal(res[1].view(torch.int16), out2.view(torch.int16))
+    assert out2.abs().max().item() > 0
+print("graph after init ok")
+''' % root
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "graph after init ok" in r.stdout, r.stdout + r.stderr
