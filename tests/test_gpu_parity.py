@@ -690,3 +690,39 @@ print("graph after init ok")
 ''' % root
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and "graph after init ok" in r.stdout, r.stdout + r.stderr
+
+
+@pytest.mark.parametrize("s", [16, 300])
+def test_non_finite_inputs_do_not_fault(s):
+    """NaN / Inf in X or W are outside the contract (results unspecified) but must not fault: both paths run to
+    completion, the columns of X that hold them count as outlier columns (their magnitude bits reach any
+    threshold), and outputs whose row of X and column of W are finite stay finite."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    d = wl.make_custom(s, 512, 256, 3, seed=97)
+    X, W = d["X"].copy(), d["W"].copy()
+    X[2, 100] = np.float16("nan")
+    X[5, 300] = np.float16("inf")
+    X[7, 301] = -np.float16("inf")
+    W[40, 9] = np.float16("inf")
+    W[41, 200] = np.float16("nan")
+    Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.float16)
+    Wd = torch.from_numpy(W.view(np.int16)).cuda().view(torch.float16)
+    cap = 32
+    ws = L.Workspace.allocate(s, 512, 256, cap)
+    qw = L.quantize_weight(Wd, ws)
+    outl = L.Outliers(torch.zeros(cap, dtype=torch.int32, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda"),
+                      torch.zeros(1, dtype=torch.int32, device="cuda"), cap)
+    rows = L.QuantizedRows(torch.zeros(L.xq_bytes(s, 512), dtype=torch.int8, device="cuda"),
+                           torch.zeros(s, dtype=torch.float16, device="cuda"),
+                           torch.zeros((s, L.opad(cap)), dtype=torch.float16, device="cuda"), s, 512)
+    out = L.linear(Xd, qw, 6.0, outl, rows, ws)
+    torch.cuda.synchronize()
+    n = int(outl.count.item())
+    got = set(outl.idx[:n].cpu().numpy().tolist())
+    assert {100, 300, 301} <= got and set(d["planted"].tolist()) <= got
+    o = out.cpu().numpy().astype(np.float32)
+    clean_rows = [i for i in range(s) if i not in (2, 5, 7)]
+    clean_cols = [j for j in range(256) if j not in (9, 200)]
+    assert np.isfinite(o[np.ix_(clean_rows, clean_cols)]).all()
