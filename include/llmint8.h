@@ -234,7 +234,7 @@ int llmint8_probe_read(const void *buf, size_t bytes, int32_t *sink, llmint8_str
 int llmint8_debug_prefill_tile(int cfg);
 
 /* Test/support: force the work split of the decode kernel (column tiles per workgroup, k-tiles per
- * load batch): 1 = 1 x 8, 2 = 2 x 4 (the default), 3 = 2 x 8, 4 = 3 x 4, 5 = 1 x 4; -1 = not forced.
+ * load batch): 1 = 1 x 8 (the default), 2 = 2 x 4, 3 = 2 x 8, 4 = 3 x 4, 5 = 1 x 4; -1 = not forced.
  * Anything else is LLMINT8_INVALID_ARG.  Process-wide; results do not depend on it.   */
 #define LLMINT8_DECODE_SHAPES 5
 int llmint8_debug_decode_shape(int cfg);

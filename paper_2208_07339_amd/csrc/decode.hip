@@ -228,11 +228,14 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
     gemm_decode_kernel<NJ, U, false><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo, count, cap, \
                                                                  opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, none)
     switch (g_decode_cfg.load(std::memory_order_relaxed)) {
-        case 1: LAUNCH_DECODE(1, 8); break;
         case 3: LAUNCH_DECODE(2, 8); break;
         case 4: LAUNCH_DECODE(3, 4); break;
         case 5: LAUNCH_DECODE(1, 4); break;
-        default: LAUNCH_DECODE(2, 4); break;  // 2, and -1 = not forced
+        case 2: LAUNCH_DECODE(2, 4); break;
+        default: LAUNCH_DECODE(1, 8); break;  // 1, and -1 = not forced: twice as many workgroups as 2 x 4, three full
+                                              // rounds of two per CU at the 175B-shaped decode size (96.2 against
+                                              // 98.0 us there; 1 x 4: 97.4, 1 x 6: 98.0, 1 x 12 and 1 x 16: 109.6,
+                                              // 2 x 4 with eight waves per workgroup, one workgroup per CU: 111)
     }
 #undef LAUNCH_DECODE
     return hipGetLastError();
