@@ -54,16 +54,26 @@ struct GemmArgs {
 };
 
 // ---------------------------------------------------------------------------
-// One workgroup = 4 waves (2 x 2) computes 64*WA output columns x 64*WB tokens;
-// a wave owns WA x WB MFMA tiles of 32 x 32 (16*WA*WB accumulator registers per
-// lane).  The MFMA "A" operand is a W tile (its 32 rows are output columns j),
-// the "B" operand an X tile (32 tokens i): a lane ends up with 4 consecutive
-// output columns of one token per register quad.
+// One workgroup = 2 x WQ waves (column halves x token parts; WQ = 2 or 4) computes
+// 64*WA output columns x 32*WQ*WB tokens; a wave owns WA x WB MFMA tiles of
+// 32 x 32 (16*WA*WB accumulator registers per lane).  The MFMA "A" operand is a
+// W tile (its 32 rows are output columns j), the "B" operand an X tile (32
+// tokens i): a lane ends up with 4 consecutive output columns of one token per
+// register quad.
 //
-// K pipeline.  A stage is 64 features (2 MFMA k-steps) of all 2*(WA+WB) row
+// Shapes built: 256 x 256 and 128 x 256 (columns x tokens) with eight waves
+// (two per SIMD, 128 / 64 accumulator registers each), 192 x 256 and 128 x 128
+// with four.  Eight waves read each X tile from LDS twice as often, but two
+// waves per SIMD cover each other's waits in the epilogue, which takes 7.5 k
+// clocks instead of 13 k at 256 x 256 (the K loop is the same: 1 150-1 170
+// clocks per stage); measured A/B on one box: 338.5 against 344.7 us on a
+// 4096 x 5120 x 20480 product, 38.1 against 39.3 us on 2048 x 4096 x 4096.
+// 192 x 256 does not split evenly over eight waves (14 row tiles).
+//
+// K pipeline.  A stage is 64 features (2 MFMA k-steps) of all 2*WA + WQ*WB row
 // tiles; NB = 4 stages form a ring in LDS.  Tiles go global -> LDS with
-// 16-byte direct loads (one 1 KiB tile piece per wave instruction, WA+WB per
-// wave and stage) and come back with one ds_read_b128 per operand (linear,
+// 16-byte direct loads (one 1 KiB tile piece per wave instruction, the pieces
+// of a stage dealt evenly to the waves) and come back with one ds_read_b128 per operand (linear,
 // conflict free).  The operands of a whole stage sit in registers, double
 // buffered: while the MFMAs of stage st run from one register set, stage st+1
 // is read from LDS into the other and stage st+4 is requested from memory.
@@ -91,7 +101,7 @@ struct GemmArgs {
 //   7+6p+2q dequantized and staged, 8+6p+2q written out; 20 tile done.
 // In the product build the macro is empty.
 #ifdef LLMINT8_GEMM_STAMPS
-__device__ long long g_stamps[4][32];
+__device__ long long g_stamps[8][32];
 #define STAMP(k)                                                                                  \
     do {                                                                                          \
         if (blockIdx.x == 9 && lane == 0 && pos == stamp_pos) g_stamps[w][k] = clock64();                   \
@@ -108,27 +118,29 @@ constexpr int OSLOTS = 32;  // outlier slots staged through LDS; more are read f
 // the unrolled product of Eq. 5 to the accumulators (in double: with zeropoints far from 0 they are
 // large and cancel) and divides by nd_x nd_w.  The records of the tile's tokens and the three planes
 // of column factors travel through the epilogue stages like the absmax constants do.
-template <int WA, int WB, bool ZP>
-__global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
+template <int WA, int WB, int WQ, bool ZP>
+__global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArgs g)
 {
-    constexpr int TW = 2 * WA, TX = 2 * WB;
-    constexpr int PIECES = WA + WB;              // direct loads per wave per stage
+    constexpr int NWAVES = 2 * WQ;               // waves: 2 along the columns x WQ along the tokens
+    constexpr int TW = 2 * WA, TX = WQ * WB;     // row tiles of W and of X in the workgroup tile
+    constexpr int PIECES = (TW + TX) / WQ;       // direct loads per wave per stage
+    static_assert(PIECES * WQ == TW + TX && (WQ == 2 || WQ == 4), "the pieces of a stage must divide evenly among the waves");
     constexpr int STAGE = (TW + TX) * 2 * TILE_BYTES;
     constexpr int NMFMA = 2 * WA * WB;
     constexpr int NRD = 2 * (WA + WB);
     constexpr int NOPS = PIECES + NRD;
     constexpr int OPSPAN = NMFMA;                // MFMA slots of a stage that carry its requests and LDS reads
     constexpr int NEW = 16;                      // epilogue-stage pieces holding W rows: [32 slots][256 columns] fp16
-    constexpr int NEX = 4 * WB;                  // pieces holding Xo: [64*WB tokens][opad <= 32 slots] fp16
-    constexpr int NZX = ZP ? WB : 0;             // zeropoint: pieces holding the tokens' records, 64 of 16 bytes each
+    constexpr int NEX = 2 * TX;                  // pieces holding Xo: [32*TX tokens][opad <= 32 slots] fp16
+    constexpr int NZX = ZP ? TX / 2 : 0;         // zeropoint: pieces holding the tokens' records, 64 of 16 bytes each
     constexpr int NZP = ZP ? (WA + 1) / 2 : 0;   // zeropoint: pieces per plane of column factors, 128 doubles each
-    static_assert(NEW + NEX + 1 + NZX + 3 * NZP <= 8 * PIECES, "epilogue operands must fit two stages");
+    static_assert(TX % 2 == 0 && NEW + NEX + 1 + NZX + 3 * NZP <= 2 * NWAVES * PIECES, "epilogue operands must fit two stages");
 
     extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int s = g.s, o = g.o, KT = g.KT, opad = g.opad;
-    const int wp = w >> 1, wq = w & 1;  // wave position: column half, token half
+    const int wp = w / WQ, wq = w % WQ;  // wave position: column half, token part
 
     // ---- this workgroup's tiles.  Hardware deals consecutive workgroup ids round-robin to the 8
     // XCDs; each XCD gets a contiguous run of the tile order, so that tiles sharing operand panels
@@ -175,8 +187,8 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         const int pj = inband / bh;
         const int qi = q0 + inband - pj * bh;
         J0w = pj * 64 * WA;
-        I0w = qi * 64 * WB;
-        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 64 * WB <= s);
+        I0w = qi * 32 * TX;
+        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 32 * TX <= s);
 #pragma unroll
         for (int k = 0; k < PIECES; k++) {
             const int p = w * PIECES + k;
@@ -203,9 +215,9 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
 
     // Source of piece n (0 .. 8*PIECES-1) of the epilogue stages, per lane.  Layout of the two stages:
     // pieces 0..15: rows O of W_f16, [32 slots][256 columns] (a slot row is 512 bytes whatever WA is; lanes past
-    // the tile's 64*WA columns repeat chunk 0); then 4*WB pieces of Xo, [64*WB tokens][opad slots] as it lies in
+    // the tile's 64*WA columns repeat chunk 0); then 2*TX pieces of Xo, [32*TX tokens][opad slots] as it lies in
     // memory; then one piece with c_w (lanes 0-31) and c_x (lanes 32-63).  Zeropoint: that piece is idle, and
-    // WB pieces with the records of the tile's tokens and 3 x NZP pieces with the planes of column factors
+    // TX/2 pieces with the records of the tile's tokens and 3 x NZP pieces with the planes of column factors
     // follow.  Whatever is left of the two stages re-reads a harmless piece.
     auto esrc = [&](int n) -> const void* {
         // The addresses depend on the tile only; the opaque copy of the lane number keeps the compiler from
@@ -235,7 +247,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         } else {
             if (n > NEW + NEX) return g.Xq + ln * 16;
             if (ln < 32) return g.cw + (J0w + wchunk);
-            const int c = (ln - 32) < 8 * WB ? (ln - 32) : 0;
+            const int c = (ln - 32) < 4 * TX ? (ln - 32) : 0;
             return g.cx + (I0w + c * 8);
         }
     };
@@ -259,7 +271,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
     };
     auto dma_e = [&](int e, int slot, int k) {
         int8_t* dst = lds + slot * STAGE + (w * PIECES + k) * TILE_BYTES;
-        __builtin_amdgcn_global_load_lds(GPTR(esrc(e * 4 * PIECES + w * PIECES + k)), LPTR(dst), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GPTR(esrc(e * NWAVES * PIECES + w * PIECES + k)), LPTR(dst), 16, 0, 0);
     };
 
     v16i acc[WA][WB];
@@ -393,8 +405,9 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
         const int4* EZx = (const int4*)(E + (NEW + NEX + 1) * TILE_BYTES);                 // zeropoint: [64*WB] records
         const double* EZc = (const double*)(E + (NEW + NEX + 1 + NZX) * TILE_BYTES);       // 3 planes of NZP*128 doubles
         // output staging behind the ring (the ring slots are busy with the next tile): 8 KiB per wave
-        constexpr int NSTG = 1;
-        int8_t* stg = lds + NB * STAGE + w * (8192 * NSTG);
+        // (a block of 64 tokens x 64 columns), 4 KiB (32 tokens) with eight waves
+        constexpr int BU = WQ == 2 ? 2 : 1;  // token tiles per staged block
+        int8_t* stg = lds + NB * STAGE + w * (BU * 4096);
 
         // rows O of the fp16 weights for column jcol, outlier slots t0 + 8*gl .. +7, straight from memory
         auto load_w_mem = [&](int jcol, int t0) {
@@ -484,7 +497,6 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                 __builtin_amdgcn_wave_barrier();
             }
             STAMP(5);
-            int unit = 0;
 #pragma unroll
             for (int a0 = 0; a0 < WA; a0 += 2) {
                 constexpr int WA_ = WA;
@@ -526,15 +538,15 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                 }
                 STAMP(6 + 6 * (a0 / 2));
 #pragma unroll
-                for (int b0 = 0; b0 < WB; b0 += 2, unit++) {
-                    int8_t* sb = stg + (unit % NSTG) * 8192;
-                    // ---- 64 tokens x 64 columns: dequantize, add the outlier product, stage as fp16 rows in LDS
+                for (int b0 = 0; b0 < WB; b0 += BU) {
+                    int8_t* sb = stg;
+                    // ---- 32*BU tokens x 64 columns: dequantize, add the outlier product, stage as fp16 rows in LDS
 #pragma unroll
                     for (int aa = 0; aa < 2; aa++) {
                         if (aa >= na) break;
                         const int a = a0 + aa;
 #pragma unroll
-                        for (int bb = 0; bb < 2; bb++) {
+                        for (int bb = 0; bb < BU; bb++) {
                             if (b0 + bb >= WB) break;
                             const int b = b0 + bb;
                             // Eq. 8: outlier product first (fp32 accumulation in the matrix unit), then one fused
@@ -587,11 +599,11 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                     }
                     // The staged values are read back by other lanes of the same wave, through pointers of another
                     // type: LDS serves a wave's requests in order, the compiler must not reorder them either.
-                    STAMP(7 + 6 * (a0 / 2) + 2 * (b0 / 2));
+                    STAMP(7 + 6 * (a0 / 2) + 2 * (b0 / BU));
                     asm volatile("" ::: "memory");
                     // ---- write the staged block: a lane moves 16 bytes, 8 lanes cover a token's 128 bytes
 #pragma unroll
-                    for (int p = 0; p < 8; p++) {
+                    for (int p = 0; p < 4 * BU; p++) {
                         const int tl = p * 8 + (lane_e >> 3), q = lane_e & 7;
                         const u4 v = *(const u4*)(sb + tl * 128 + ((q ^ ((tl >> 1) & 7)) << 4));
                         const int i = I0 + b0 * 32 + tl;
@@ -610,7 +622,7 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
                         }
                     }
                     asm volatile("" ::: "memory");  // the next block's staging writes stay behind these reads
-                    STAMP(8 + 6 * (a0 / 2) + 2 * (b0 / 2));
+                    STAMP(8 + 6 * (a0 / 2) + 2 * (b0 / BU));
                 }
             }
         };
@@ -632,20 +644,20 @@ __global__ void __launch_bounds__(256, 1) gemm_prefill_kernel(const GemmArgs g)
 // instantiation at once, under a lock, and caches the number of compute units; later calls only read an
 // atomic flag.  A caller that records calls into a graph therefore needs one call of any shape (or
 // llmint8_init) on the device beforehand, not one per tile shape.
-template <int WA, int WB>
+template <int WA, int WB, int WQ>
 constexpr int prefill_lds_bytes()
 {
-    return NB * (2 * WA + 2 * WB) * 2 * TILE_BYTES + 4 * 8192;  // operand ring + output staging
+    return NB * (2 * WA + WQ * WB) * 2 * TILE_BYTES + 32768;  // operand ring + output staging (32 KiB over all waves)
 }
 
-template <int WA, int WB>
+template <int WA, int WB, int WQ>
 static hipError_t raise_lds_limit()
 {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, false>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<WA, WB>());
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, WQ, false>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<WA, WB, WQ>());
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, true>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<WA, WB>());
+    return hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, WQ, true>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<WA, WB, WQ>());
 }
 
 constexpr int MAX_DEVICES = 64;
@@ -666,10 +678,10 @@ hipError_t prefill_device_setup(int* cus)
         }
     }
     std::lock_guard<std::mutex> hold(g_dev_lock);
-    if ((e = raise_lds_limit<4, 4>()) != hipSuccess) return e;
-    if ((e = raise_lds_limit<3, 4>()) != hipSuccess) return e;
-    if ((e = raise_lds_limit<2, 4>()) != hipSuccess) return e;
-    if ((e = raise_lds_limit<2, 2>()) != hipSuccess) return e;
+    if ((e = raise_lds_limit<4, 2, 4>()) != hipSuccess) return e;
+    if ((e = raise_lds_limit<3, 4, 2>()) != hipSuccess) return e;
+    if ((e = raise_lds_limit<2, 2, 4>()) != hipSuccess) return e;
+    if ((e = raise_lds_limit<2, 2, 2>()) != hipSuccess) return e;
     int n = 0;
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
     *cus = n;
@@ -677,17 +689,17 @@ hipError_t prefill_device_setup(int* cus)
     return hipSuccess;
 }
 
-template <int WA, int WB, bool ZP>
+template <int WA, int WB, int WQ, bool ZP>
 static hipError_t launch_cfg(GemmArgs& g, hipStream_t st)
 {
-    constexpr int shm = prefill_lds_bytes<WA, WB>();
+    constexpr int shm = prefill_lds_bytes<WA, WB, WQ>();
     g.nP = (g.JT + 2 * WA - 1) / (2 * WA);
-    g.nQ = (g.RT + 2 * WB - 1) / (2 * WB);
+    g.nQ = (g.RT + WQ * WB - 1) / (WQ * WB);
     int ncu = 0;
     const hipError_t e = prefill_device_setup(&ncu);
     if (e != hipSuccess) return e;
     const int total = g.nP * g.nQ;
-    gemm_prefill_kernel<WA, WB, ZP><<<total < ncu ? total : ncu, 256, shm, st>>>(g);
+    gemm_prefill_kernel<WA, WB, WQ, ZP><<<total < ncu ? total : ncu, 128 * WQ, shm, st>>>(g);
     return hipGetLastError();
 }
 
@@ -734,26 +746,26 @@ hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const
     const int c = forced >= 0 ? forced : pick_cfg(s, o);
     if (zp) {
         switch (c) {
-            case 1: return launch_cfg<3, 4, true>(g, st);
-            case 2: return launch_cfg<2, 4, true>(g, st);
-            case 3: return launch_cfg<2, 2, true>(g, st);
-            default: return launch_cfg<4, 4, true>(g, st);
+            case 1: return launch_cfg<3, 4, 2, true>(g, st);
+            case 2: return launch_cfg<2, 2, 4, true>(g, st);
+            case 3: return launch_cfg<2, 2, 2, true>(g, st);
+            default: return launch_cfg<4, 2, 4, true>(g, st);
         }
     }
     switch (c) {
-        case 1: return launch_cfg<3, 4, false>(g, st);
-        case 2: return launch_cfg<2, 4, false>(g, st);
-        case 3: return launch_cfg<2, 2, false>(g, st);
-        default: return launch_cfg<4, 4, false>(g, st);
+        case 1: return launch_cfg<3, 4, 2, false>(g, st);
+        case 2: return launch_cfg<2, 2, 4, false>(g, st);
+        case 3: return launch_cfg<2, 2, 2, false>(g, st);
+        default: return launch_cfg<4, 2, 4, false>(g, st);
     }
 }
 
 }  // namespace llmint8
 
 #ifdef LLMINT8_GEMM_STAMPS
-// measurement build only: the 4 x 32 clock stamps of the last launch (host buffer of 128 long long)
+// measurement build only: the 8 x 32 clock stamps of the last launch (host buffer of 256 long long; rows 4-7 only with eight waves)
 extern "C" int llmint8_debug_read_stamps(long long* out)
 {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(llmint8::g_stamps), sizeof(long long) * 4 * 32);
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(llmint8::g_stamps), sizeof(long long) * 8 * 32);
 }
 #endif

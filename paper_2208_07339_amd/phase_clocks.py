@@ -1,12 +1,12 @@
 """Shader-clock stamps at the phase boundaries of one tile of the prefill GEMM.
 
     python -m paper_2208_07339_amd.build --stamps        # builds libllmint8_stamps.so (measurement build)
-    LLMINT8_LIB=paper_2208_07339_amd/libllmint8_stamps.so python -m paper_2208_07339_amd.phase_clocks [workload]
+    LLMINT8_LIB=paper_2208_07339_amd/libllmint8_stamps.so python -m paper_2208_07339_amd.phase_clocks [workload [tile]]
 
-Runs 300 back-to-back calls of llmint8_linear on the workload (default ffn13b), then prints, for each of the
-four waves of one workgroup, the clocks spent in each phase of that workgroup's second tile (its only tile
-where the workload gives it one: attn6p7b; then nothing is requested for a next tile), and the K loop's
-clocks per stage (its MFMAs alone need 32 clocks per v_mfma_i32_32x32x32_i8: 1024 per stage of a 256 x 256
+Runs 300 back-to-back calls of llmint8_linear on the workload (default ffn13b), then prints, for the first
+four waves of one workgroup (it has eight at 256 x 256 and 128 x 256), the clocks spent in each phase of that
+workgroup's second tile (its only tile where the workload gives it one: attn6p7b; then nothing is requested
+for a next tile), and the K loop's clocks per stage (its MFMAs alone need 32 clocks per v_mfma_i32_32x32x32_i8: 1024 per stage of a 256 x 256
 tile, 768 at 192 x 256, 512 at 128 x 256).
 """
 import ctypes as C
@@ -17,7 +17,7 @@ import numpy as np
 
 PHASES = [(0, 1, "wait for the first stage"), (1, 2, "K loop"), (2, 3, "wait for the epilogue operands"),
           (3, 4, "request the next tile's first two stages"), (4, 5, "row constants, outlier columns of X"),
-          (5, 20, "dequantize + outlier product + store (four 64 x 64 blocks)")]
+          (5, 20, "dequantize + outlier product + store")]
 
 
 def main():
@@ -29,6 +29,8 @@ def main():
         sys.exit("this library has no clock stamps: build with `python -m paper_2208_07339_amd.build --stamps` and "
                  "set LLMINT8_LIB to libllmint8_stamps.so")
     name = sys.argv[1] if len(sys.argv) > 1 else "ffn13b"
+    if len(sys.argv) > 2:
+        L.debug_prefill_tile(int(sys.argv[2]))  # optional: force a workgroup tile (llmint8_debug_prefill_tile)
     d = wl.make(name)
     s, h, o = d["s"], d["h"], d["o"]
     X = torch.from_numpy(d["X"].view(np.int16)).cuda().view(torch.float16)
@@ -41,11 +43,12 @@ def main():
     for _ in range(300):
         L.linear(X, qw, d["alpha"], outl, rows, ws, out)
     torch.cuda.synchronize()
-    buf = (C.c_longlong * 128)()
+    buf = (C.c_longlong * 256)()
     fn = L.lib().llmint8_debug_read_stamps
     fn.argtypes = [C.c_void_p]
     assert fn(buf) == 0
-    t = np.array(list(buf), dtype=np.int64).reshape(4, 32)
+    t = np.array(list(buf), dtype=np.int64).reshape(8, 32)
+    t = t[:4]  # an eight-wave workgroup stamps eight rows; its first four waves are shown
     if not t[:, 20].all():
         sys.exit(f"{name}: workgroup 9 has no tile, nothing was stamped")
     stages = 2 * ((h + 127) // 128)
