@@ -134,6 +134,8 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     constexpr int NEX = 2 * TX;                  // pieces holding Xo: [32*TX tokens][opad <= 32 slots] fp16
     constexpr int NZX = ZP ? TX / 2 : 0;         // zeropoint: pieces holding the tokens' records, 64 of 16 bytes each
     constexpr int NZP = ZP ? (WA + 1) / 2 : 0;   // zeropoint: pieces per plane of column factors, 128 doubles each
+    constexpr int NST = (WA + 1) / 2 * 4 * WB;   // store instructions of a wave in the unguarded epilogue
+    static_assert((NB - 2) * PIECES + NST < 64, "vmcnt is a 6-bit counter");
     static_assert(TX % 2 == 0 && NEW + NEX + 1 + NZX + 3 * NZP <= 2 * NWAVES * PIECES, "epilogue operands must fit two stages");
 
     extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
@@ -304,12 +306,13 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     // slot of stage st and the reads of stage st+1 into the other register set.
     // MODE 0: operand stage st+NB; 1 / 2: first / second epilogue stage; 3: nothing left to request;
     // 4: last stage (nothing to request, nothing to read).
+    // MODE 5: MODE 0 for stage 0 of a tile, where the stores of the previous tile's epilogue may still fly too.
     auto stage = [&](auto S, auto M, int st) {
         constexpr int SS = decltype(S)::value;
-        constexpr int MODE = decltype(M)::value;
+        constexpr int MODE = decltype(M)::value == 5 ? 0 : decltype(M)::value;
         // My pieces of stage st+1 have landed (two younger stages may still fly) and my reads of stage st
         // are complete; after the barrier the same holds for every wave.
-        STAGE_SYNC((NB - 2) * PIECES);
+        STAGE_SYNC((NB - 2) * PIECES + (decltype(M)::value == 5 ? NST : 0));
         FENCE();
         const int slot = (unsigned)(sbase + st) % NB, nslot = (unsigned)(sbase + st + 1) % NB;
         const unsigned vo = MODE == 0 ? stage_off(st + NB) : 0u;
@@ -338,6 +341,12 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     issue_stage(0, 0);
     issue_stage(1, 1);
 
+    // Memory operations of a wave complete in the order they were issued, and the requests of a tile's first two
+    // stages are issued before the epilogue of the tile before it.  After an unguarded epilogue exactly NST
+    // stores follow them (anything else the compiler may add only makes the waits below stricter), so the first
+    // two waits of the next tile can leave those stores in flight and the K loop starts while they drain.
+    // After a guarded epilogue, or with no tile before, everything is waited for instead.
+    bool after_fast = false;
     for (;;) {  // tiles of this workgroup
         const int cJ0w = J0w, cI0w = I0w;  // the tile being computed (the loader moves on before its epilogue)
         const bool cinterior = interior;
@@ -347,12 +356,17 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
             for (int b = 0; b < WB; b++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) acc[a][b][r] = 0;
-        // Stage 0 has landed once at most the pieces of stage 1 are in flight (stores of the previous
-        // epilogue can only make this wait longer).  The barrier also tells that every wave is done with
+        // Stage 0 has landed once at most the pieces of stage 1 (and the stores of an unguarded epilogue
+        // before this tile) are in flight.  The barrier also tells that every wave is done with
         // the previous tile's epilogue stages, whose slots take stages 2 and 3 (with nst == 2: this
         // tile's own epilogue stages) once stage 0 is on its way into registers.
         STAMP(0);
-        STAGE_SYNC(PIECES);
+        if (nst < 6)
+            STAGE_SYNC(PIECES);
+        else if (after_fast)
+            STAGE_SYNC(PIECES + NST);
+        else
+            STAGE_SYNC(0);
         STAMP(1);
 #pragma unroll
         for (int i = 0; i < NRD; i++) rd(I0_{}, sbase, i);
@@ -361,6 +375,11 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
         issue_stage(3, (sbase + 3) % NB);
         FENCE();
         int st = 0;
+        if (nst >= 6) {
+            stage(I0_{}, std::integral_constant<int, 5>{}, 0);
+            stage(I1_{}, I0_{}, 1);
+            st = 2;
+        }
         for (; st + 6 <= nst; st += 2) {
             stage(I0_{}, I0_{}, st);
             stage(I1_{}, I0_{}, st + 1);
@@ -633,6 +652,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
 
         STAMP(20);
         if (!has_next) break;
+        after_fast = cinterior;
         sbase = (eslot + 2) % NB;
         pos += gx;
     }  // tiles

@@ -3,8 +3,8 @@
     python -m paper_2208_07339_amd.build --stamps        # builds libllmint8_stamps.so (measurement build)
     LLMINT8_LIB=paper_2208_07339_amd/libllmint8_stamps.so python -m paper_2208_07339_amd.phase_clocks [workload [tile]]
 
-Runs 300 back-to-back calls of llmint8_linear on the workload (default ffn13b), then prints, for the first
-four waves of one workgroup (it has eight at 256 x 256 and 128 x 256), the clocks spent in each phase of that
+Runs 300 back-to-back calls of llmint8_linear on the workload (default ffn13b), then prints, for the waves
+of one workgroup (eight at 256 x 256 and 128 x 256, else four), the clocks spent in each phase of that
 workgroup's second tile (its only tile where the workload gives it one: attn6p7b; then nothing is requested
 for a next tile), and the K loop's clocks per stage (its MFMAs alone need 32 clocks per v_mfma_i32_32x32x32_i8: 1024 per stage of a 256 x 256
 tile, 768 at 192 x 256, 512 at 128 x 256).
@@ -48,16 +48,18 @@ def main():
     fn.argtypes = [C.c_void_p]
     assert fn(buf) == 0
     t = np.array(list(buf), dtype=np.int64).reshape(8, 32)
-    t = t[:4]  # an eight-wave workgroup stamps eight rows; its first four waves are shown
+    nw = 8 if t[4:, 20].all() else 4  # rows 4-7 stay zero where the workgroup has four waves
+    t = t[:nw]
     if not t[:, 20].all():
         sys.exit(f"{name}: workgroup 9 has no tile, nothing was stamped")
     stages = 2 * ((h + 127) // 128)
-    print(f"{name}: s={s} h={h} o={o}, {stages} K stages per tile; clocks of one tile of workgroup 9, waves 0-3")
+    print(f"{name}: s={s} h={h} o={o}, {stages} K stages per tile; clocks of one tile of workgroup 9, waves 0-{nw - 1}")
     for a, b, what in PHASES:
-        print(f"  {what:62s} " + " ".join(f"{int(t[w, b] - t[w, a]):8d}" for w in range(4)))
+        print(f"  {what:62s} " + " ".join(f"{int(t[w, b] - t[w, a]):7d}" for w in range(nw)))
     total = t[:, 20] - t[:, 0]
     kloop = t[:, 2] - t[:, 1]
-    print(f"  {'whole tile':62s} " + " ".join(f"{int(v):8d}" for v in total))
+    print(f"  {'whole tile':62s} " + " ".join(f"{int(v):7d}" for v in total))
+    print(f"  {'start of the tile relative to wave 0':62s} " + " ".join(f"{int(t[w, 0] - t[0, 0]):7d}" for w in range(nw)))
     print(f"  K loop per stage: {kloop.mean() / stages:.0f} clocks; share of the tile outside the K loop: "
           f"{100 * (1 - kloop.mean() / total.mean()):.1f} %")
 
