@@ -421,8 +421,17 @@ int llmint8_zp_linear(const void* X_f16, int s, int h, float alpha, const int8_t
         return LLMINT8_INVALID_ARG;
     if (h > LLMINT8_MAX_H) return LLMINT8_SHAPE;
     if (ws_bytes < llmint8_workspace_bytes(s, h, o, cap)) return LLMINT8_WORKSPACE;
-    int r = llmint8_find_outliers(X_f16, s, h, alpha, idx, cap, count, status, ws, ws_bytes, stream);
-    if (r == LLMINT8_OK) r = llmint8_zp_quantize_rows(X_f16, s, h, idx, count, cap, Xq, zc_x, Xo_f16, stream);
+    int r;
+    if (s <= 32) {
+        // short X: outlier scan, records, codes and gathered columns in two kernels (the same results as the
+        // two calls below)
+        const OutlierLists L = carve_outlier_lists((char*)ws_base(ws), h, cap);
+        r = hip_status(launch_prepass_small(X_f16, s, h, threshold_bits(alpha), L, idx, cap, count, status, nullptr,
+                                            (unsigned short*)Xo_f16, Xq, 0, (hipStream_t)stream, (int4*)zc_x));
+    } else {
+        r = llmint8_find_outliers(X_f16, s, h, alpha, idx, cap, count, status, ws, ws_bytes, stream);
+        if (r == LLMINT8_OK) r = llmint8_zp_quantize_rows(X_f16, s, h, idx, count, cap, Xq, zc_x, Xo_f16, stream);
+    }
     if (r == LLMINT8_OK)
         r = llmint8_zp_matmul(Xq, zc_x, Xo_f16, idx, count, cap, Wq, zc_w, W_f16, s, h, o, Out_f16, nullptr, ws,
                               ws_bytes, stream);

@@ -40,6 +40,52 @@ __device__ inline double zp_range(unsigned lohi)
            (double)f16_bits_to_float((unsigned short)(lohi & 0xffffu));
 }
 
+// ---- zeropoint quantization (Section 2.1, Eq. 1-3), shared by the kernels of zeropoint.hip and the
+// short-X pre-pass.  Order-preserving key of a finite fp16 bit pattern: keys compare as unsigned integers
+// the way the values compare as numbers (-0 directly below +0).
+__device__ inline unsigned f16_key(unsigned b) { return (b & 0x8000u) ? (~b & 0xffffu) : (b | 0x8000u); }
+__device__ inline unsigned key_f16(unsigned k)
+{
+    const unsigned b = (k & 0x8000u) ? (k & 0x7fffu) : (~k & 0xffffu);
+    return (b & 0x7fffu) ? b : 0u;  // a zero is reported as +0
+}
+
+// u(x) = round-half-even(254 x / D) for D > 0.  254 x and D are exact in double, the division is correctly
+// rounded, and a quotient that is not a tie lies at least 2^-50 (relative) from the nearest half-integer,
+// so rint() of the double quotient is the exact answer.  |u| <= 254 * 2^11.
+__device__ __forceinline__ int zp_u(unsigned short xb, double D)
+{
+    return (int)__builtin_rint(254.0 * (double)f16_bits_to_float(xb) / D);
+}
+
+// The same u(x) without a division per element: with rD = the correctly rounded reciprocal of D (one
+// division per vector, by the caller), q = a rD is within an ulp of a / D (a = 254 x, exact), the fused
+// multiply-add gives the remainder a - q D exactly, and q + r rD rounds to the correctly rounded quotient
+// (Markstein's correction step; its one exception, a divisor whose significand is all ones, cannot occur:
+// D is a difference of two fp16 values and has at most 41 significant bits).  rint() then sees the same
+// double as in zp_u.
+__device__ __forceinline__ int zp_u_rcp(unsigned short xb, double D, double rD)
+{
+    const double a = 254.0 * (double)f16_bits_to_float(xb);
+    const double q = a * rD;
+    const double r = __builtin_fma(-q, D, a);
+    return (int)__builtin_rint(__builtin_fma(r, rD, q));
+}
+
+// The record of a vector from the keys of its smallest and largest element: fp16 bits of lo and hi,
+// zp = u(lo) + 127 (Eq. 2), and a zero for the sum of the codes, which the quantizer accumulates.
+__device__ inline int4 make_const(unsigned kmin, unsigned kmax)
+{
+    const unsigned lo = key_f16(kmin), hi = key_f16(kmax);
+    const double D = zp_range(lo | (hi << 16));
+    int4 r;
+    r.x = (int)(lo | (hi << 16));
+    r.y = D > 0.0 ? zp_u((unsigned short)lo, D) + 127 : 0;
+    r.z = 0;
+    r.w = 0;
+    return r;
+}
+
 // fp16( q * c_w / 127 ) for an int8 code q and a column constant given as fp16 bits, rounded once to nearest
 // even: a weight rebuilt from its code (the variant that keeps no 16-bit weights).
 // The exact quotient in 32-bit integer arithmetic: c_w = m * 2^E with an 11-bit m, so the value is
@@ -105,13 +151,14 @@ constexpr int MAXLISTS = 1024;  // runs of 256 columns; h <= LLMINT8_MAX_H needs
 struct OutlierLists {
     int* count;               // [MAXLISTS] qualifying columns in each run of 256 columns
     int* cand;                // [lists][capc] their indices, ascending
-    unsigned short* rowpart;  // [ceil(h / 512)][32] partial row maxima (short-X scan only)
+    unsigned short* rowpart;  // [2][ceil(h / 512)][32] short-X scan only: partial row maxima (absmax), or the keys of
+                              // the partial row minima followed by those of the maxima (zeropoint)
 };
 __host__ __device__ inline int list_capacity(int cap) { return cap < 256 ? cap : 256; }
 inline size_t outlier_lists_bytes(int h, int cap)
 {
     const size_t nl = (size_t)(h + 255) / 256, nwg = (size_t)(h + 511) / 512;
-    return MAXLISTS * 4 + nl * list_capacity(cap) * 4 + nwg * 32 * 2;
+    return MAXLISTS * 4 + nl * list_capacity(cap) * 4 + 2 * nwg * 32 * 2;
 }
 inline OutlierLists carve_outlier_lists(char* base, int h, int cap)
 {
@@ -147,10 +194,11 @@ hipError_t launch_colmax_rowmax(const void* X, int s, int h, unsigned short* par
 hipError_t launch_quantize_rows_rowpart(const void* X, int s, int h, OutlierLists L, unsigned thr,
                                         const unsigned short* rowpart, int32_t* idx, int32_t* count, int32_t* status,
                                         int cap, int8_t* Xq, unsigned short* cx, unsigned short* Xo, hipStream_t st);
-// whole pre-pass of a short X (s <= 32): outlier scan, row constants, codes, gathered columns
+// whole pre-pass of a short X (s <= 32): outlier scan, row constants, codes, gathered columns.
+// zc != NULL: zeropoint records [s] in place of cx (which is then not written), codes u(x) - zp.
 hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
                                 int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,
-                                int shared_cx, hipStream_t st);
+                                int shared_cx, hipStream_t st, int4* zc = nullptr);
 hipError_t launch_colmax_final(const unsigned short* part, int nslab, int cols, unsigned short* out,
                                hipStream_t st);
 hipError_t launch_quantize_weight(const void* W, int h, int o, const unsigned short* cw, int8_t* Wq,

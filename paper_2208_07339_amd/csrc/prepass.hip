@@ -377,9 +377,17 @@ hipError_t launch_spread_max(unsigned short* c, int n, hipStream_t st)
 // places the lists, reduces the partial row maxima to the row constants and
 // quantizes its features; workgroup 0 also writes idx, count, status, c_x and
 // the gathered columns Xo.
+//
+// ZP: zeropoint constants (Section 2.1, Eq. 1-3) in place of absmax ones.  The
+// scan leaves, per row, the keys of the smallest and the largest entry among
+// its non-outlier columns and clears the rows' records; the quantizer turns
+// them into the records (range, zeropoint), writes the codes u(x) - zp and adds
+// its part of every row's sum of codes into the record.
 // ---------------------------------------------------------------------------
+template <bool ZP>
 __global__ void __launch_bounds__(256) scan_small_kernel(const unsigned short* __restrict__ X, int s, int h,
-                                                         unsigned thr, int vec_ok, OutlierLists L, int capc)
+                                                         unsigned thr, int vec_ok, OutlierLists L, int capc,
+                                                         int4* __restrict__ zc)
 {
     __shared__ us8 red[4][64];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -400,9 +408,10 @@ __global__ void __launch_bounds__(256) scan_small_kernel(const unsigned short* _
                     if (c0 + e < h) v[r][e] = p[e];
             }
         }
-        v[r] &= (unsigned short)0x7fff;
-        m = __builtin_elementwise_max(m, v[r]);
+        if (!ZP) v[r] &= (unsigned short)0x7fff;
+        m = __builtin_elementwise_max(m, v[r] & (unsigned short)0x7fff);
     }
+    if (ZP && blockIdx.x == 0 && tid < s) zc[tid] = make_int4(0, 0, 0, 0);
     red[w][lane] = m;
     __syncthreads();
     m = __builtin_elementwise_max(__builtin_elementwise_max(red[0][lane], red[1][lane]),
@@ -414,18 +423,43 @@ __global__ void __launch_bounds__(256) scan_small_kernel(const unsigned short* _
     // partial row maxima over this workgroup's non-outlier columns
 #pragma unroll
     for (int r = 0; r < 8; r++) {
-        unsigned mx = 0;
+        if constexpr (!ZP) {
+            unsigned mx = 0;
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const unsigned x = ((flags >> e) & 1u) ? 0u : (unsigned)v[r][e];
-            mx = x > mx ? x : mx;
-        }
+            for (int e = 0; e < 8; e++) {
+                const unsigned x = ((flags >> e) & 1u) ? 0u : (unsigned)v[r][e];
+                mx = x > mx ? x : mx;
+            }
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            const unsigned t = (unsigned)__shfl_xor((int)mx, d);
-            mx = t > mx ? t : mx;
+            for (int d = 32; d >= 1; d >>= 1) {
+                const unsigned t = (unsigned)__shfl_xor((int)mx, d);
+                mx = t > mx ? t : mx;
+            }
+            if (lane == 0) L.rowpart[(size_t)blockIdx.x * 32 + w + 4 * r] = (unsigned short)mx;  // 0 for rows >= s
+        } else {
+            // keys of the smallest and the largest entry; an empty set (rows >= s, nothing but outlier
+            // columns) is min 0xffff above max 0
+            unsigned kmin = 0xffffu, kmax = 0u;
+            if (w + 4 * r < s) {
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    if (!((flags >> e) & 1u) && c0 + e < h) {
+                        const unsigned k = f16_key(v[r][e]);
+                        kmin = k < kmin ? k : kmin;
+                        kmax = k > kmax ? k : kmax;
+                    }
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const unsigned a = (unsigned)__shfl_xor((int)kmin, d), b = (unsigned)__shfl_xor((int)kmax, d);
+                kmin = a < kmin ? a : kmin;
+                kmax = b > kmax ? b : kmax;
+            }
+            if (lane == 0) {
+                L.rowpart[(size_t)blockIdx.x * 32 + w + 4 * r] = (unsigned short)kmin;
+                L.rowpart[((size_t)gridDim.x + blockIdx.x) * 32 + w + 4 * r] = (unsigned short)kmax;
+            }
         }
-        if (lane == 0) L.rowpart[(size_t)blockIdx.x * 32 + w + 4 * r] = (unsigned short)mx;  // 0 for rows >= s
     }
     if (w == 0) {  // the two lists of this workgroup (lanes 0-31, lanes 32-63), ascending: lane, then bit
         const int mine = __popc(flags);
@@ -449,6 +483,7 @@ __global__ void __launch_bounds__(256) scan_small_kernel(const unsigned short* _
     }
 }
 
+template <bool ZP>
 __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned short* __restrict__ X, int s, int h,
                                                              OutlierLists L, int capc, int vec_ok,
                                                              int32_t* __restrict__ idx, int cap, int opad,
@@ -456,13 +491,18 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
                                                              int32_t* __restrict__ status,
                                                              unsigned short* __restrict__ cx,
                                                              unsigned short* __restrict__ Xo,
-                                                             int8_t* __restrict__ Xq, int KT, int shared_cx)
+                                                             int8_t* __restrict__ Xq, int KT, int shared_cx,
+                                                             int4* __restrict__ zc)
 {
     extern __shared__ unsigned fullmap[];  // ceil(h / 32) words, used only when |O| > cap
     __shared__ __attribute__((aligned(16))) int8_t stage[8 * TILE_BYTES];
     __shared__ int s_cnt[MAXLISTS], s_base[MAXLISTS];
     __shared__ unsigned s_part[8][32];
     __shared__ unsigned s_cxb[32];
+    __shared__ unsigned s_part_lo[ZP ? 8 : 1][32];  // zeropoint: s_part / s_cxb hold the keys of the maxima, these of the minima
+    __shared__ unsigned s_lo[ZP ? 32 : 1];
+    __shared__ double s_D[ZP ? 32 : 1], s_rD[ZP ? 32 : 1];  // zeropoint: range of each row and its reciprocal
+    __shared__ int s_z[ZP ? 32 : 1];                        // and its zeropoint
     __shared__ unsigned bitmap[8];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int k0 = blockIdx.x * 256;
@@ -489,14 +529,26 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
         }
     }
     unsigned rp_max = 0;  // max over workgroups gq, gq+8, .. of rowpart[.][i]
+    unsigned rp_min = 0xffffu;
     {
         const int i = tid & 31, gq = tid >> 5;
         for (int b = gq; b < nwg; b += 32) {  // 4 independent loads in flight
-            unsigned t4[4];
+            unsigned t4[4], t5[4];
 #pragma unroll
-            for (int u = 0; u < 4; u++) t4[u] = (b + 8 * u < nwg) ? (unsigned)L.rowpart[(size_t)(b + 8 * u) * 32 + i] : 0u;
+            for (int u = 0; u < 4; u++) {
+                const size_t at = (size_t)(b + 8 * u) * 32 + i;
+                if constexpr (ZP) {
+                    t5[u] = (b + 8 * u < nwg) ? (unsigned)L.rowpart[at] : 0xffffu;
+                    t4[u] = (b + 8 * u < nwg) ? (unsigned)L.rowpart[(size_t)nwg * 32 + at] : 0u;
+                } else {
+                    t4[u] = (b + 8 * u < nwg) ? (unsigned)L.rowpart[at] : 0u;
+                }
+            }
 #pragma unroll
-            for (int u = 0; u < 4; u++) rp_max = t4[u] > rp_max ? t4[u] : rp_max;
+            for (int u = 0; u < 4; u++) {
+                rp_max = t4[u] > rp_max ? t4[u] : rp_max;
+                if constexpr (ZP) rp_min = t5[u] < rp_min ? t5[u] : rp_min;
+            }
         }
     }
 
@@ -508,12 +560,17 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
     // ---- row constants
     if (!overflow) {
         s_part[tid >> 5][tid & 31] = rp_max;
+        if constexpr (ZP) s_part_lo[tid >> 5][tid & 31] = rp_min;
         __syncthreads();
         if (tid < 32) {
-            unsigned m2 = 0;
+            unsigned m2 = 0, m1 = 0xffffu;
 #pragma unroll
-            for (int q = 0; q < 8; q++) m2 = s_part[q][tid] > m2 ? s_part[q][tid] : m2;
+            for (int q = 0; q < 8; q++) {
+                m2 = s_part[q][tid] > m2 ? s_part[q][tid] : m2;
+                if constexpr (ZP) m1 = s_part_lo[q][tid] < m1 ? s_part_lo[q][tid] : m1;
+            }
             s_cxb[tid] = m2;
+            if constexpr (ZP) s_lo[tid] = m1;
         }
     } else {
         // only the first cap columns count as outliers: redo the row maxima with their bitmap
@@ -529,19 +586,34 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
         }
         __syncthreads();
         for (int i = w; i < 32; i += 4) {
-            unsigned mx = 0;
+            unsigned mx = 0, mn = 0xffffu;
             if (i < s)
                 for (int c = lane; c < h; c += 64) {
-                    const unsigned x =
-                        ((fullmap[c >> 5] >> (c & 31)) & 1u) ? 0u : (unsigned)(X[(size_t)i * h + c] & 0x7fff);
-                    mx = x > mx ? x : mx;
+                    if constexpr (ZP) {
+                        if (!((fullmap[c >> 5] >> (c & 31)) & 1u)) {
+                            const unsigned k = f16_key(X[(size_t)i * h + c]);
+                            mn = k < mn ? k : mn;
+                            mx = k > mx ? k : mx;
+                        }
+                    } else {
+                        const unsigned x =
+                            ((fullmap[c >> 5] >> (c & 31)) & 1u) ? 0u : (unsigned)(X[(size_t)i * h + c] & 0x7fff);
+                        mx = x > mx ? x : mx;
+                    }
                 }
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) {
                 const unsigned t = (unsigned)__shfl_xor((int)mx, d);
                 mx = t > mx ? t : mx;
+                if constexpr (ZP) {
+                    const unsigned u = (unsigned)__shfl_xor((int)mn, d);
+                    mn = u < mn ? u : mn;
+                }
             }
-            if (lane == 0) s_cxb[i] = mx;
+            if (lane == 0) {
+                s_cxb[i] = mx;
+                if constexpr (ZP) s_lo[i] = mn;
+            }
         }
     }
     // ---- outlier columns among this workgroup's 256 features: list k0 / 256
@@ -555,7 +627,23 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
             }
     }
     __syncthreads();
-    if (shared_cx) {  // tensor-wise baseline: one constant, the largest of the row maxima (rows >= s hold 0)
+    if constexpr (ZP) {  // the rows' records: range, zeropoint (a row with no non-outlier column: all zero)
+        if (tid < 32) {
+            int4 r = make_int4(0, 0, 0, 0);
+            if (tid < s && s_lo[tid] <= s_cxb[tid]) r = make_const(s_lo[tid], s_cxb[tid]);
+            const double D = zp_range((unsigned)r.x);
+            s_D[tid] = D;
+            s_rD[tid] = D > 0.0 ? 1.0 / D : 0.0;
+            s_z[tid] = r.y;
+            if (blockIdx.x == 0 && tid < s) {  // the sum of the codes (word 2) was cleared by the scan and is added to below
+                int* rec = (int*)(zc + tid);
+                rec[0] = r.x;
+                rec[1] = r.y;
+            }
+        }
+        __syncthreads();
+    }
+    if (!ZP && shared_cx) {  // tensor-wise baseline: one constant, the largest of the row maxima (rows >= s hold 0)
         unsigned t = 0;
 #pragma unroll
         for (int q = 0; q < 32; q++) t = s_cxb[q] > t ? s_cxb[q] : t;
@@ -580,7 +668,7 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
             *count = cnt;
             if (status) *status = overflow ? 1 : 0;
         }
-        if (tid < s) cx[tid] = (unsigned short)s_cxb[tid];
+        if (!ZP && tid < s) cx[tid] = (unsigned short)s_cxb[tid];
     }
 
     // ---- codes of 32 rows x 256 features into the tiled layout
@@ -589,14 +677,32 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
     for (int q = 0; q < 4; q++) {
         const int r = q * 8 + (tid >> 5);
         const us8 v = xv[q];
-        const float c = (r < s) ? f16_bits_to_float((unsigned short)s_cxb[r]) : 0.0f;
-        const float rc = c > 0.0f ? 1.0f / c : 0.0f;
         unsigned lo = 0, hi = 0;
+        if constexpr (ZP) {
+            const double D = (r < s) ? s_D[r] : 0.0, rD = s_rD[r];
+            const int z = s_z[r];
+            int part = 0;
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const int qv = (c > 0.0f && !((bits >> e) & 1u)) ? q8(f16_bits_to_float(v[e]), c, rc) : 0;
-            const unsigned byte = (unsigned)qv & 0xffu;
-            if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
+            for (int e = 0; e < 8; e++) {
+                int qv = 0;
+                if (D > 0.0 && k + e < h && !((bits >> e) & 1u)) qv = zp_u_rcp(v[e], D, rD) - z;
+                part += qv;
+                const unsigned byte = (unsigned)qv & 0xffu;
+                if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
+            }
+            // the 32 lanes that share row r (one half of a wave) add up their parts
+#pragma unroll
+            for (int d = 16; d >= 1; d >>= 1) part += __shfl_xor(part, d);
+            if ((tid & 31) == 0 && r < s && part) atomicAdd(&zc[r].z, part);
+        } else {
+            const float c = (r < s) ? f16_bits_to_float((unsigned short)s_cxb[r]) : 0.0f;
+            const float rc = c > 0.0f ? 1.0f / c : 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const int qv = (c > 0.0f && !((bits >> e) & 1u)) ? q8(f16_bits_to_float(v[e]), c, rc) : 0;
+                const unsigned byte = (unsigned)qv & 0xffu;
+                if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
+            }
         }
         u2 pk = {lo, hi};
         *(u2*)(stage + (kseg >> 5) * TILE_BYTES + tile_byte(r, kseg & 31)) = pk;
@@ -612,18 +718,27 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
 
 hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
                                 int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,
-                                int shared_cx, hipStream_t st)
+                                int shared_cx, hipStream_t st, int4* zc)
 {
     const int capc = list_capacity(cap);
     const int vec_ok = (h % 8 == 0) && aligned16(X);
     const int KT = k_tiles(h);
-    scan_small_kernel<<<(h + 511) / 512, 256, 0, st>>>((const unsigned short*)X, s, h, thr, vec_ok, L, capc);
+    const int nscan = (h + 511) / 512, nquant = (KT * 32 + 255) / 256;
+    const size_t shm = ((size_t)(h + 31) / 32) * sizeof(unsigned);
+    if (zc) {
+        scan_small_kernel<true><<<nscan, 256, 0, st>>>((const unsigned short*)X, s, h, thr, vec_ok, L, capc, zc);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        quantize_small_kernel<true><<<nquant, 256, shm, st>>>((const unsigned short*)X, s, h, L, capc, vec_ok, idx, cap,
+                                                              opad_of(cap), count, status, cx, Xo, Xq, KT, 0, zc);
+        return hipGetLastError();
+    }
+    scan_small_kernel<false><<<nscan, 256, 0, st>>>((const unsigned short*)X, s, h, thr, vec_ok, L, capc, nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t shm = ((size_t)(h + 31) / 32) * sizeof(unsigned);
-    quantize_small_kernel<<<(KT * 32 + 255) / 256, 256, shm, st>>>((const unsigned short*)X, s, h, L, capc, vec_ok, idx,
-                                                                   cap, opad_of(cap), count, status, cx, Xo, Xq, KT,
-                                                                   shared_cx);
+    quantize_small_kernel<false><<<nquant, 256, shm, st>>>((const unsigned short*)X, s, h, L, capc, vec_ok, idx, cap,
+                                                           opad_of(cap), count, status, cx, Xo, Xq, KT, shared_cx,
+                                                           nullptr);
     return hipGetLastError();
 }
 

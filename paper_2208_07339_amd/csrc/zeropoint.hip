@@ -20,48 +20,7 @@ typedef unsigned short us8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 
-// Order-preserving key of a finite fp16 bit pattern: keys compare as unsigned integers the way
-// the values compare as numbers (-0 directly below +0).
-__device__ inline unsigned f16_key(unsigned b) { return (b & 0x8000u) ? (~b & 0xffffu) : (b | 0x8000u); }
-__device__ inline unsigned key_f16(unsigned k)
-{
-    const unsigned b = (k & 0x8000u) ? (k & 0x7fffu) : (~k & 0xffffu);
-    return (b & 0x7fffu) ? b : 0u;  // a zero is reported as +0
-}
-
-// u(x) for D > 0.  254 x and D are exact in double, the division is correctly rounded, and a
-// quotient that is not a tie lies at least 2^-50 (relative) from the nearest half-integer, so
-// rint() of the double quotient is the exact answer.  |u| <= 254 * 2^11.
-__device__ __forceinline__ int zp_u(unsigned short xb, double D)
-{
-    return (int)__builtin_rint(254.0 * (double)f16_bits_to_float(xb) / D);
-}
-
-// The same u(x) without a division per element: with rD = the correctly rounded reciprocal of D (one
-// division per vector, by the caller), q = a rD is within an ulp of a / D (a = 254 x, exact), the fused
-// multiply-add gives the remainder a - q D exactly, and q + r rD rounds to the correctly rounded quotient
-// (Markstein's correction step; its one exception, a divisor whose significand is all ones, cannot occur:
-// D is a difference of two fp16 values and has at most 41 significant bits).  rint() then sees the same
-// double as in zp_u.
-__device__ __forceinline__ int zp_u_rcp(unsigned short xb, double D, double rD)
-{
-    const double a = 254.0 * (double)f16_bits_to_float(xb);
-    const double q = a * rD;
-    const double r = __builtin_fma(-q, D, a);
-    return (int)__builtin_rint(__builtin_fma(r, rD, q));
-}
-
-__device__ inline int4 make_const(unsigned kmin, unsigned kmax)
-{
-    const unsigned lo = key_f16(kmin), hi = key_f16(kmax);
-    const double D = zp_range(lo | (hi << 16));
-    int4 r;
-    r.x = (int)(lo | (hi << 16));
-    r.y = D > 0.0 ? zp_u((unsigned short)lo, D) + 127 : 0;
-    r.z = 0;  // the sum of the codes is accumulated by the quantizer
-    r.w = 0;
-    return r;
-}
+// f16_key / key_f16, zp_u / zp_u_rcp and make_const live in common.h (the short-X pre-pass uses them too).
 
 // ---------------------------------------------------------------------------
 // Weights: column ranges over slabs of rows, constants, codes + column sums.

@@ -71,6 +71,7 @@ def zp_compare(X, W, alpha, cap=32):
         out2 = L.zp_linear(Xd, qw, alpha, outl2, rows2, ws)
     torch.cuda.synchronize()
     assert int(outl2.count.item()) == n and int(outl2.status.item()) == 0
+    assert torch.equal(outl2.idx[:n], outl.idx[:n]) and torch.equal(rows2.Xo, rows.Xo)
     assert torch.equal(rows2.zc, rows.zc) and torch.equal(rows2.Xq, rows.Xq)
     assert_out_close(out2.cpu().numpy(), ref["Out"])
     return ref
@@ -207,6 +208,47 @@ def test_more_outlier_columns_than_cap():
     ri, ci = np.repeat(np.arange(90), 128), np.tile(np.arange(128), 90)
     _, Os = oracle.zp_sampled(X, W, O, ri, ci)
     assert_out_close(out.cpu().numpy().reshape(-1), Os)
+
+
+@pytest.mark.parametrize("s", [7, 32])
+def test_short_x_in_one_call_with_more_outlier_columns_than_cap(s):
+    """The two-kernel pre-pass of a short X (s <= 32) inside llmint8_zp_linear, when more columns qualify
+    than the buffer takes: the row ranges are taken again over everything but the first cap columns.  Every
+    output of the call against the staged calls (which the test above pins to the oracle), Out against the
+    oracle."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    h, o, cap = 520, 136, 4
+    d = wl.make_custom(s, h, o, 9, seed=62 + s)
+    X, W = one_sided(d, shift=0.5), d["W"]
+    full = oracle.find_outliers(X, 6.0)
+    assert len(full) > cap
+    O = full[:cap]
+    Xd, Wd = upload(X, W)
+    ws = L.Workspace.allocate(s, h, o, cap)
+    qw = L.zp_quantize_weight(Wd, ws)
+    outl = L.find_outliers(Xd, 6.0, cap, ws)
+    rows = L.zp_quantize_rows(Xd, outl)
+    torch.cuda.synchronize()
+    x = oracle.zp_quantize_rows(X, O)
+    lo, hi, zp, rs = unpack(rows.zc)
+    assert np.array_equal(lo, bits(x["lo"])) and np.array_equal(zp, x["zp"]) and np.array_equal(rs, x["rowsum"])
+    outl2 = L.Outliers(torch.full((cap,), -7, dtype=torch.int32, device="cuda"),
+                       torch.full((1,), -7, dtype=torch.int32, device="cuda"),
+                       torch.full((1,), -7, dtype=torch.int32, device="cuda"), cap)
+    rows2 = L.ZpRows(torch.full((L.xq_bytes(s, h),), 99, dtype=torch.int8, device="cuda"),
+                     torch.full((s, 4), 12345, dtype=torch.int32, device="cuda"),
+                     torch.full((s, L.opad(cap)), 7.0, dtype=torch.float16, device="cuda"), s, h)
+    for _ in range(2):
+        out2 = L.zp_linear(Xd, qw, 6.0, outl2, rows2, ws)
+    torch.cuda.synchronize()
+    assert int(outl2.count.item()) == cap and int(outl2.status.item()) == 1
+    assert outl2.idx.cpu().numpy().tolist() == O.tolist()
+    assert torch.equal(rows2.zc, rows.zc) and torch.equal(rows2.Xq, rows.Xq) and torch.equal(rows2.Xo, rows.Xo)
+    ri, ci = np.repeat(np.arange(s), o), np.tile(np.arange(o), s)
+    _, Os = oracle.zp_sampled(X, W, O, ri, ci)
+    assert_out_close(out2.cpu().numpy().reshape(-1), Os)
 
 
 def test_argument_errors_are_reported_not_executed():
