@@ -378,10 +378,12 @@ int llmint8_zp_quantize_rows(const void* X_f16, int s, int h, const int32_t* idx
                                               (hipStream_t)stream));
 }
 
-int llmint8_zp_matmul(const int8_t* Xq, const int32_t* zc_x, const void* Xo_f16, const int32_t* idx,
-                      const int32_t* count, int cap, const int8_t* Wq, const int32_t* zc_w, const void* W_f16, int s,
-                      int h, int o, void* Out_f16, int32_t* C_i32_debug, void* ws, size_t ws_bytes,
-                      llmint8_stream_t stream)
+// have_factors: the per-column factors of Eq. 5 are in the workspace already (the short-X pre-pass of
+// llmint8_zp_linear makes them)
+static int zp_matmul_impl(const int8_t* Xq, const int32_t* zc_x, const void* Xo_f16, const int32_t* idx,
+                          const int32_t* count, int cap, const int8_t* Wq, const int32_t* zc_w, const void* W_f16, int s,
+                          int h, int o, void* Out_f16, int32_t* C_i32_debug, void* ws, size_t ws_bytes,
+                          llmint8_stream_t stream, bool have_factors)
 {
     if (!Xq || !zc_x || !Xo_f16 || !idx || !count || !Wq || !zc_w || !W_f16 || !Out_f16 || !ws || s < 1 || h < 1 ||
         o < 1 || cap < 1)
@@ -394,7 +396,8 @@ int llmint8_zp_matmul(const int8_t* Xq, const int32_t* zc_x, const void* Xo_f16,
     if (ws_bytes < llmint8_workspace_bytes(s, h, o, cap)) return LLMINT8_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     double* kcol = (double*)((char*)ws_base(ws) + scan_ws(s, h, o, cap) + rows_ws(o, cap));
-    hipError_t e = launch_zp_kcol(Wq, (const int4*)zc_w, h, o, idx, count, cap, kcol, st);
+    hipError_t e = hipSuccess;
+    if (!have_factors) e = launch_zp_kcol(Wq, (const int4*)zc_w, h, o, idx, count, cap, kcol, st);
     if (e != hipSuccess) return hip_status(e);
     const ZpArgs zp = {(const int4*)zc_x, kcol, zp_col_pitch(o)};
     if (s <= 32)
@@ -406,6 +409,15 @@ int llmint8_zp_matmul(const int8_t* Xq, const int32_t* zc_x, const void* Xo_f16,
                                 (const unsigned short*)W_f16, 0, idx, s, h, o, (unsigned short*)Out_f16, C_i32_debug,
                                 st, &zp);
     return hip_status(e);
+}
+
+int llmint8_zp_matmul(const int8_t* Xq, const int32_t* zc_x, const void* Xo_f16, const int32_t* idx,
+                      const int32_t* count, int cap, const int8_t* Wq, const int32_t* zc_w, const void* W_f16, int s,
+                      int h, int o, void* Out_f16, int32_t* C_i32_debug, void* ws, size_t ws_bytes,
+                      llmint8_stream_t stream)
+{
+    return zp_matmul_impl(Xq, zc_x, Xo_f16, idx, count, cap, Wq, zc_w, W_f16, s, h, o, Out_f16, C_i32_debug, ws,
+                          ws_bytes, stream, false);
 }
 
 int llmint8_zp_linear(const void* X_f16, int s, int h, float alpha, const int8_t* Wq, const int32_t* zc_w,
@@ -424,17 +436,20 @@ int llmint8_zp_linear(const void* X_f16, int s, int h, float alpha, const int8_t
     int r;
     if (s <= 32) {
         // short X: outlier scan, records, codes and gathered columns in two kernels (the same results as the
-        // two calls below)
+        // two calls below); the second one also makes the per-column factors the matmul kernel needs
         const OutlierLists L = carve_outlier_lists((char*)ws_base(ws), h, cap);
+        const ZpColumnJob job = {Wq, (const int4*)zc_w,
+                                 (double*)((char*)ws_base(ws) + scan_ws(s, h, o, cap) + rows_ws(o, cap)), o,
+                                 zp_col_pitch(o)};
         r = hip_status(launch_prepass_small(X_f16, s, h, threshold_bits(alpha), L, idx, cap, count, status, nullptr,
-                                            (unsigned short*)Xo_f16, Xq, 0, (hipStream_t)stream, (int4*)zc_x));
+                                            (unsigned short*)Xo_f16, Xq, 0, (hipStream_t)stream, (int4*)zc_x, &job));
     } else {
         r = llmint8_find_outliers(X_f16, s, h, alpha, idx, cap, count, status, ws, ws_bytes, stream);
         if (r == LLMINT8_OK) r = llmint8_zp_quantize_rows(X_f16, s, h, idx, count, cap, Xq, zc_x, Xo_f16, stream);
     }
     if (r == LLMINT8_OK)
-        r = llmint8_zp_matmul(Xq, zc_x, Xo_f16, idx, count, cap, Wq, zc_w, W_f16, s, h, o, Out_f16, nullptr, ws,
-                              ws_bytes, stream);
+        r = zp_matmul_impl(Xq, zc_x, Xo_f16, idx, count, cap, Wq, zc_w, W_f16, s, h, o, Out_f16, nullptr, ws, ws_bytes,
+                           stream, s <= 32);
     return r;
 }
 

@@ -219,9 +219,8 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
     const int wrows = rows_are_slots ? opad_of(cap) : h;
     const ZpArgs none = {nullptr, nullptr, 0};
     if (zp) {
-        gemm_decode_kernel<2, 4, true><<<(JT + 1) / 2, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows,
-                                                                    idx, Xo, count, cap, opad_of(cap), (_Float16*)Out,
-                                                                    Cdbg, s, h, o, *zp);
+        gemm_decode_kernel<1, 8, true><<<JT, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo,
+                                                           count, cap, opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, *zp);
         return hipGetLastError();
     }
 #define LAUNCH_DECODE(NJ, U)                                                                                     \

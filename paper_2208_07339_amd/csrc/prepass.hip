@@ -492,7 +492,7 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
                                                              unsigned short* __restrict__ cx,
                                                              unsigned short* __restrict__ Xo,
                                                              int8_t* __restrict__ Xq, int KT, int shared_cx,
-                                                             int4* __restrict__ zc)
+                                                             int4* __restrict__ zc, ZpColumnJob cj)
 {
     extern __shared__ unsigned fullmap[];  // ceil(h / 32) words, used only when |O| > cap
     __shared__ __attribute__((aligned(16))) int8_t stage[8 * TILE_BYTES];
@@ -507,6 +507,45 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int k0 = blockIdx.x * 256;
     const int nl = (h + 255) / 256, nwg = (h + 511) / 512;
+
+    if constexpr (ZP) {
+        // Zeropoint, one-call path: the workgroups past those of the quantizer make the per-column factors of
+        // Eq. 5 for the matmul kernel that follows (what zp_kcol_kernel does from idx / count), straight from
+        // the lists: p = D_w / 254, q = zp_w p, r = K p, K = (sum of the column's codes outside the outlier
+        // rows) + (h - |O|) zp_w; zero for the padding columns j >= o.
+        const int nquant = (KT * 32 + 255) / 256;
+        if ((int)blockIdx.x >= nquant) {
+            const int total = scan_lists(L.count, nl, s_cnt, s_base);
+            (void)total;
+            __syncthreads();
+            const int j = ((int)blockIdx.x - nquant) * 256 + tid;
+            if (j >= cj.pitch) return;
+            double p = 0.0, q = 0.0, r = 0.0;
+            if (j < cj.o) {
+                const int4 rec = cj.zcw[j];
+                long long sum = rec.z;
+                int used = 0;
+                const int8_t* col = cj.Wq + (size_t)(j >> 5) * KT * TILE_BYTES;
+                for (int b = 0; b < nl; b++) {
+                    const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+                    for (int e = 0; e < n && s_base[b] + e < cap; e++) {
+                        const unsigned k = (unsigned)L.cand[(size_t)b * capc + e];
+                        if (k < (unsigned)h) {
+                            sum -= col[(size_t)(k >> 5) * TILE_BYTES + tile_byte(j & 31, (int)(k & 31))];
+                            used++;
+                        }
+                    }
+                }
+                p = zp_range((unsigned)rec.x) * (1.0 / 254.0);
+                q = (double)rec.y * p;
+                r = (double)(sum + (long long)(h - used) * rec.y) * p;
+            }
+            cj.colc[j] = p;
+            cj.colc[(size_t)cj.pitch + j] = q;
+            cj.colc[2 * (size_t)cj.pitch + j] = r;
+            return;
+        }
+    }
 
     // Everything whose address is known is requested first, so that the latencies overlap: this
     // thread's 8 features of 4 rows, and its share of the partial row maxima.
@@ -718,7 +757,7 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
 
 hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
                                 int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,
-                                int shared_cx, hipStream_t st, int4* zc)
+                                int shared_cx, hipStream_t st, int4* zc, const ZpColumnJob* cj)
 {
     const int capc = list_capacity(cap);
     const int vec_ok = (h % 8 == 0) && aligned16(X);
@@ -729,8 +768,10 @@ hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, Outli
         scan_small_kernel<true><<<nscan, 256, 0, st>>>((const unsigned short*)X, s, h, thr, vec_ok, L, capc, zc);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        quantize_small_kernel<true><<<nquant, 256, shm, st>>>((const unsigned short*)X, s, h, L, capc, vec_ok, idx, cap,
-                                                              opad_of(cap), count, status, cx, Xo, Xq, KT, 0, zc);
+        const ZpColumnJob job = cj ? *cj : ZpColumnJob{nullptr, nullptr, nullptr, 0, 0};
+        quantize_small_kernel<true><<<nquant + job.pitch / 256, 256, shm, st>>>(
+            (const unsigned short*)X, s, h, L, capc, vec_ok, idx, cap, opad_of(cap), count, status, cx, Xo, Xq, KT, 0, zc,
+            job);
         return hipGetLastError();
     }
     scan_small_kernel<false><<<nscan, 256, 0, st>>>((const unsigned short*)X, s, h, thr, vec_ok, L, capc, nullptr);
@@ -738,7 +779,7 @@ hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, Outli
     if (e != hipSuccess) return e;
     quantize_small_kernel<false><<<nquant, 256, shm, st>>>((const unsigned short*)X, s, h, L, capc, vec_ok, idx, cap,
                                                            opad_of(cap), count, status, cx, Xo, Xq, KT, shared_cx,
-                                                           nullptr);
+                                                           nullptr, ZpColumnJob{nullptr, nullptr, nullptr, 0, 0});
     return hipGetLastError();
 }
 
