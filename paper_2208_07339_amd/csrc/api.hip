@@ -198,10 +198,12 @@ int llmint8_dequantize_rows(const int8_t* Wq, const void* cw_f16, int h, int o, 
                                           (unsigned short*)Wo_f16, (hipStream_t)stream));
 }
 
-int llmint8_matmul(const int8_t* Xq, const void* cx_f16, const void* Xo_f16, const int32_t* idx,
-                   const int32_t* count, int cap, const int8_t* Wq, const void* cw_f16, const void* W_f16, int s,
-                   int h, int o, void* Out_f16, int32_t* C_i32_debug, void* ws, size_t ws_bytes,
-                   llmint8_stream_t stream)
+// have_rows: with no 16-bit weights, the rebuilt outlier rows are in the workspace already (the short-X
+// pre-pass of llmint8_linear makes them)
+static int matmul_impl(const int8_t* Xq, const void* cx_f16, const void* Xo_f16, const int32_t* idx,
+                       const int32_t* count, int cap, const int8_t* Wq, const void* cw_f16, const void* W_f16, int s,
+                       int h, int o, void* Out_f16, int32_t* C_i32_debug, void* ws, size_t ws_bytes,
+                       llmint8_stream_t stream, bool have_rows)
 {
     if (!Xq || !cx_f16 || !Xo_f16 || !idx || !count || !Wq || !cw_f16 || !Out_f16 || s < 1 || h < 1 || o < 1 ||
         cap < 1)
@@ -220,7 +222,7 @@ int llmint8_matmul(const int8_t* Xq, const void* cx_f16, const void* Xo_f16, con
         if (!ws) return LLMINT8_INVALID_ARG;
         if (ws_bytes < llmint8_workspace_bytes(s, h, o, cap)) return LLMINT8_WORKSPACE;
         unsigned short* Wo = (unsigned short*)((char*)ws_base(ws) + scan_ws(s, h, o, cap));
-        e = launch_dequant_rows(Wq, (const unsigned short*)cw_f16, h, o, idx, count, cap, Wo, st);
+        if (!have_rows) e = launch_dequant_rows(Wq, (const unsigned short*)cw_f16, h, o, idx, count, cap, Wo, st);
         if (e != hipSuccess) return hip_status(e);
         Wrows = Wo;
         rows_are_slots = 1;
@@ -234,6 +236,15 @@ int llmint8_matmul(const int8_t* Xq, const void* cx_f16, const void* Xo_f16, con
                                 (const unsigned short*)cw_f16, Wrows, rows_are_slots, idx, s, h, o,
                                 (unsigned short*)Out_f16, C_i32_debug, st);
     return hip_status(e);
+}
+
+int llmint8_matmul(const int8_t* Xq, const void* cx_f16, const void* Xo_f16, const int32_t* idx,
+                   const int32_t* count, int cap, const int8_t* Wq, const void* cw_f16, const void* W_f16, int s,
+                   int h, int o, void* Out_f16, int32_t* C_i32_debug, void* ws, size_t ws_bytes,
+                   llmint8_stream_t stream)
+{
+    return matmul_impl(Xq, cx_f16, Xo_f16, idx, count, cap, Wq, cw_f16, W_f16, s, h, o, Out_f16, C_i32_debug, ws,
+                       ws_bytes, stream, false);
 }
 
 static int linear_impl(const void* X_f16, int s, int h, float alpha, int granularity, const int8_t* Wq, const void* cw_f16,
@@ -260,8 +271,11 @@ static int linear_impl(const void* X_f16, int s, int h, float alpha, int granula
     const int shared_cx = granularity == LLMINT8_TENSORWISE;
     hipError_t e;
     if (s <= 32) {
+        // without 16-bit weights the second kernel also rebuilds the outlier rows of W from the codes
+        const ColumnJob job = {Wq, cw_f16, base + scan_ws(s, h, o, cap), o, (o + 255) & ~255};
         e = launch_prepass_small(X_f16, s, h, threshold_bits(alpha), L, idx, cap, count, status,
-                                 (unsigned short*)cx_f16, (unsigned short*)Xo_f16, Xq, shared_cx, st);
+                                 (unsigned short*)cx_f16, (unsigned short*)Xo_f16, Xq, shared_cx, st, nullptr,
+                                 W_f16 ? nullptr : &job);
     } else {
         if (std::isinf(alpha) && alpha > 0.0f) {
             // no decomposition (the baselines of Table 1 without it): O is empty, X need not be scanned
@@ -293,8 +307,8 @@ static int linear_impl(const void* X_f16, int s, int h, float alpha, int granula
     }
     if (e == hipSuccess && ev_before) e = hipEventRecord(ev_before, st);
     if (e != hipSuccess) return hip_status(e);
-    const int r = llmint8_matmul(Xq, cx_f16, Xo_f16, idx, count, cap, Wq, cw_f16, W_f16, s, h, o, Out_f16, nullptr,
-                                 ws, ws_bytes, stream);
+    const int r = matmul_impl(Xq, cx_f16, Xo_f16, idx, count, cap, Wq, cw_f16, W_f16, s, h, o, Out_f16, nullptr, ws,
+                              ws_bytes, stream, s <= 32 && cap <= JOB_MAX_CAP);
     if (r == LLMINT8_OK && ev_after) return hip_status(hipEventRecord(ev_after, st));
     return r;
 }
@@ -438,9 +452,8 @@ int llmint8_zp_linear(const void* X_f16, int s, int h, float alpha, const int8_t
         // short X: outlier scan, records, codes and gathered columns in two kernels (the same results as the
         // two calls below); the second one also makes the per-column factors the matmul kernel needs
         const OutlierLists L = carve_outlier_lists((char*)ws_base(ws), h, cap);
-        const ZpColumnJob job = {Wq, (const int4*)zc_w,
-                                 (double*)((char*)ws_base(ws) + scan_ws(s, h, o, cap) + rows_ws(o, cap)), o,
-                                 zp_col_pitch(o)};
+        const ColumnJob job = {Wq, zc_w, (char*)ws_base(ws) + scan_ws(s, h, o, cap) + rows_ws(o, cap), o,
+                               zp_col_pitch(o)};
         r = hip_status(launch_prepass_small(X_f16, s, h, threshold_bits(alpha), L, idx, cap, count, status, nullptr,
                                             (unsigned short*)Xo_f16, Xq, 0, (hipStream_t)stream, (int4*)zc_x, &job));
     } else {
@@ -449,7 +462,7 @@ int llmint8_zp_linear(const void* X_f16, int s, int h, float alpha, const int8_t
     }
     if (r == LLMINT8_OK)
         r = zp_matmul_impl(Xq, zc_x, Xo_f16, idx, count, cap, Wq, zc_w, W_f16, s, h, o, Out_f16, nullptr, ws, ws_bytes,
-                           stream, s <= 32);
+                           stream, s <= 32 && cap <= JOB_MAX_CAP);
     return r;
 }
 

@@ -195,17 +195,21 @@ hipError_t launch_quantize_rows_rowpart(const void* X, int s, int h, OutlierList
                                         const unsigned short* rowpart, int32_t* idx, int32_t* count, int32_t* status,
                                         int cap, int8_t* Xq, unsigned short* cx, unsigned short* Xo, hipStream_t st);
 // whole pre-pass of a short X (s <= 32): outlier scan, row constants, codes, gathered columns.
-// zc != NULL: zeropoint records [s] in place of cx (which is then not written), codes u(x) - zp; with a
-// column job the second kernel also makes the per-column factors of launch_zp_kcol (pitch = zp_col_pitch(o)).
-struct ZpColumnJob {
-    const int8_t* Wq;  // tiled W_i8
-    const int4* zcw;   // [o] records of the columns of W
-    double* colc;      // three planes of pitch doubles
-    int o, pitch;      // pitch 0: no job
+// zc != NULL: zeropoint records [s] in place of cx (which is then not written), codes u(x) - zp.
+// With a column job the second kernel gets pitch / 256 more workgroups that do, from the column lists, what
+// would otherwise take a kernel of its own before the matmul kernel: zeropoint: the per-column factors of
+// launch_zp_kcol (pitch = zp_col_pitch(o)); absmax: the outlier rows of W rebuilt from the codes as
+// launch_dequant_rows writes them (pitch = o rounded up to 256).
+constexpr int JOB_MAX_CAP = 256;  // a column job is taken for outlier buffers up to this size (the set sits in LDS)
+struct ColumnJob {
+    const int8_t* Wq;    // tiled W_i8
+    const void* wconst;  // zeropoint: [o] records of the columns of W; absmax: [o] c_w, fp16 bits
+    void* out;           // zeropoint: three planes of pitch doubles; absmax: [opad][o] fp16
+    int o, pitch;        // pitch 0: no job
 };
 hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
                                 int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,
-                                int shared_cx, hipStream_t st, int4* zc = nullptr, const ZpColumnJob* cj = nullptr);
+                                int shared_cx, hipStream_t st, int4* zc = nullptr, const ColumnJob* cj = nullptr);
 hipError_t launch_colmax_final(const unsigned short* part, int nslab, int cols, unsigned short* out,
                                hipStream_t st);
 hipError_t launch_quantize_weight(const void* W, int h, int o, const unsigned short* cw, int8_t* Wq,

@@ -492,7 +492,7 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
                                                              unsigned short* __restrict__ cx,
                                                              unsigned short* __restrict__ Xo,
                                                              int8_t* __restrict__ Xq, int KT, int shared_cx,
-                                                             int4* __restrict__ zc, ZpColumnJob cj)
+                                                             int4* __restrict__ zc, ColumnJob cj)
 {
     extern __shared__ unsigned fullmap[];  // ceil(h / 32) words, used only when |O| > cap
     __shared__ __attribute__((aligned(16))) int8_t stage[8 * TILE_BYTES];
@@ -508,43 +508,77 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
     const int k0 = blockIdx.x * 256;
     const int nl = (h + 255) / 256, nwg = (h + 511) / 512;
 
-    if constexpr (ZP) {
-        // Zeropoint, one-call path: the workgroups past those of the quantizer make the per-column factors of
-        // Eq. 5 for the matmul kernel that follows (what zp_kcol_kernel does from idx / count), straight from
-        // the lists: p = D_w / 254, q = zp_w p, r = K p, K = (sum of the column's codes outside the outlier
-        // rows) + (h - |O|) zp_w; zero for the padding columns j >= o.
-        const int nquant = (KT * 32 + 255) / 256;
-        if ((int)blockIdx.x >= nquant) {
-            const int total = scan_lists(L.count, nl, s_cnt, s_base);
-            (void)total;
-            __syncthreads();
-            const int j = ((int)blockIdx.x - nquant) * 256 + tid;
-            if (j >= cj.pitch) return;
+    // One-call paths: the workgroups past those of the quantizer take a column job (see ColumnJob).  They read
+    // the outlier set straight from the lists (slot t of the set is entry t of their concatenation) into LDS
+    // first, so that a thread's loads of its column's codes in those rows do not wait for one another.
+    const int nquant = (KT * 32 + 255) / 256;
+    if ((int)blockIdx.x >= nquant) {
+        __shared__ int s_idx[JOB_MAX_CAP];
+        const int total = scan_lists(L.count, nl, s_cnt, s_base);
+        const int cnt = total < cap ? total : cap;  // cap <= JOB_MAX_CAP (checked by the launcher)
+        __syncthreads();
+        for (int b = tid; b < nl; b += 256) {
+            const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+            for (int e = 0; e < n && s_base[b] + e < cap; e++) s_idx[s_base[b] + e] = L.cand[(size_t)b * capc + e];
+        }
+        __syncthreads();
+        const int j = ((int)blockIdx.x - nquant) * 256 + tid;
+        if (j >= cj.pitch) return;
+        const int8_t* col = cj.Wq + (size_t)(j >> 5) * KT * TILE_BYTES;  // column j of W: row j & 31 of these tiles
+        // codes of column j in outlier rows t0 .. t0+7 (0 and not valid where there is none)
+        auto codes8 = [&](int t0, int* q, bool* ok) {
+#pragma unroll
+            for (int u = 0; u < 8; u++) {
+                const unsigned k = (t0 + u < cnt) ? (unsigned)s_idx[t0 + u] : 0xffffffffu;
+                ok[u] = k < (unsigned)h;
+                q[u] = ok[u] ? col[(size_t)(k >> 5) * TILE_BYTES + tile_byte(j & 31, (int)(k & 31))] : 0;
+            }
+        };
+        if constexpr (ZP) {
+            // the per-column factors of Eq. 5, as zp_kcol_kernel makes them from idx / count: p = D_w / 254,
+            // q = zp_w p, r = K p, K = (sum of the column's codes outside the outlier rows) + (h - |O|) zp_w;
+            // zero for the padding columns j >= o
             double p = 0.0, q = 0.0, r = 0.0;
             if (j < cj.o) {
-                const int4 rec = cj.zcw[j];
+                const int4 rec = ((const int4*)cj.wconst)[j];
                 long long sum = rec.z;
                 int used = 0;
-                const int8_t* col = cj.Wq + (size_t)(j >> 5) * KT * TILE_BYTES;
-                for (int b = 0; b < nl; b++) {
-                    const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
-                    for (int e = 0; e < n && s_base[b] + e < cap; e++) {
-                        const unsigned k = (unsigned)L.cand[(size_t)b * capc + e];
-                        if (k < (unsigned)h) {
-                            sum -= col[(size_t)(k >> 5) * TILE_BYTES + tile_byte(j & 31, (int)(k & 31))];
-                            used++;
-                        }
+                for (int t0 = 0; t0 < cnt; t0 += 8) {
+                    int c8[8];
+                    bool ok[8];
+                    codes8(t0, c8, ok);
+#pragma unroll
+                    for (int u = 0; u < 8; u++) {
+                        sum -= c8[u];
+                        used += ok[u] ? 1 : 0;
                     }
                 }
                 p = zp_range((unsigned)rec.x) * (1.0 / 254.0);
                 q = (double)rec.y * p;
                 r = (double)(sum + (long long)(h - used) * rec.y) * p;
             }
-            cj.colc[j] = p;
-            cj.colc[(size_t)cj.pitch + j] = q;
-            cj.colc[2 * (size_t)cj.pitch + j] = r;
-            return;
+            double* colc = (double*)cj.out;
+            colc[j] = p;
+            colc[(size_t)cj.pitch + j] = q;
+            colc[2 * (size_t)cj.pitch + j] = r;
+        } else {
+            // the outlier rows of W rebuilt from the codes, as dequant_rows_kernel writes them: slot t holds
+            // row idx[t], zeros from |O| to opad
+            if (j >= cj.o) return;
+            const unsigned cwb = ((const unsigned short*)cj.wconst)[j];
+            unsigned short* Wo = (unsigned short*)cj.out;
+            for (int t0 = 0; t0 < cnt; t0 += 8) {
+                int c8[8];
+                bool ok[8];
+                codes8(t0, c8, ok);
+#pragma unroll
+                for (int u = 0; u < 8; u++)
+                    if (t0 + u < cnt)  // the same for every thread: no arithmetic for the empty slots
+                        Wo[(size_t)(t0 + u) * cj.o + j] = ok[u] ? dequant_bits(c8[u], cwb) : (unsigned short)0;
+            }
+            for (int t = cnt; t < opad; t++) Wo[(size_t)t * cj.o + j] = 0;
         }
+        return;
     }
 
     // Everything whose address is known is requested first, so that the latencies overlap: this
@@ -757,18 +791,18 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
 
 hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, OutlierLists L, int32_t* idx, int cap,
                                 int32_t* count, int32_t* status, unsigned short* cx, unsigned short* Xo, int8_t* Xq,
-                                int shared_cx, hipStream_t st, int4* zc, const ZpColumnJob* cj)
+                                int shared_cx, hipStream_t st, int4* zc, const ColumnJob* cj)
 {
     const int capc = list_capacity(cap);
     const int vec_ok = (h % 8 == 0) && aligned16(X);
     const int KT = k_tiles(h);
     const int nscan = (h + 511) / 512, nquant = (KT * 32 + 255) / 256;
     const size_t shm = ((size_t)(h + 31) / 32) * sizeof(unsigned);
+    const ColumnJob job = (cj && cap <= JOB_MAX_CAP) ? *cj : ColumnJob{nullptr, nullptr, nullptr, 0, 0};
     if (zc) {
         scan_small_kernel<true><<<nscan, 256, 0, st>>>((const unsigned short*)X, s, h, thr, vec_ok, L, capc, zc);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        const ZpColumnJob job = cj ? *cj : ZpColumnJob{nullptr, nullptr, nullptr, 0, 0};
         quantize_small_kernel<true><<<nquant + job.pitch / 256, 256, shm, st>>>(
             (const unsigned short*)X, s, h, L, capc, vec_ok, idx, cap, opad_of(cap), count, status, cx, Xo, Xq, KT, 0, zc,
             job);
@@ -777,9 +811,9 @@ hipError_t launch_prepass_small(const void* X, int s, int h, unsigned thr, Outli
     scan_small_kernel<false><<<nscan, 256, 0, st>>>((const unsigned short*)X, s, h, thr, vec_ok, L, capc, nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    quantize_small_kernel<false><<<nquant, 256, shm, st>>>((const unsigned short*)X, s, h, L, capc, vec_ok, idx, cap,
-                                                           opad_of(cap), count, status, cx, Xo, Xq, KT, shared_cx,
-                                                           nullptr, ZpColumnJob{nullptr, nullptr, nullptr, 0, 0});
+    quantize_small_kernel<false><<<nquant + job.pitch / 256, 256, shm, st>>>(
+        (const unsigned short*)X, s, h, L, capc, vec_ok, idx, cap, opad_of(cap), count, status, cx, Xo, Xq, KT, shared_cx,
+        nullptr, job);
     return hipGetLastError();
 }
 

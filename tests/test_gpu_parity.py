@@ -428,7 +428,10 @@ def int8_rows_compare(d, cap=32, via_linear=False):
     g = run_hip(X, W, d["alpha"], cap, want_c=False)
     qw = dataclasses.replace(g["qw"], W=None)
     if via_linear:
+        # (for s <= 32 the second pre-pass kernel rebuilds the rows itself: the same bits as the staged call)
+        staged = L.matmul(g["rows"], g["outl"], qw, g["ws"]).clone()
         out = L.linear(g["Xd"], qw, d["alpha"], g["outl"], g["rows"], g["ws"])
+        assert torch.equal(out.view(torch.int16), staged.view(torch.int16))
     else:
         out = L.matmul(g["rows"], g["outl"], qw, g["ws"])
     torch.cuda.synchronize()
@@ -438,6 +441,31 @@ def int8_rows_compare(d, cap=32, via_linear=False):
     # and it is a different result from the fp16-rows one wherever outliers contribute
     if len(r["idx"]):
         assert not np.array_equal(bits(out.cpu().numpy()), bits(g["Out"]))
+
+
+def test_int8_rows_one_call_equals_staged_calls_when_more_columns_qualify_than_fit():
+    """Short X, no 16-bit weights, |O| > cap: the second pre-pass kernel of llmint8_linear rebuilds the rows of
+    the first cap outlier columns from the column lists; llmint8_matmul gets them from llmint8_dequantize_rows
+    via idx / count.  Same bits, and the rows are those of the oracle."""
+    import dataclasses
+
+    import torch
+
+    import paper_2208_07339_amd as L
+    d = wl.make_custom(20, 520, 136, 9, seed=56)
+    cap = 4
+    g = run_hip(d["X"], d["W"], d["alpha"], cap, want_c=False)
+    assert int(g["outl"].status.item()) == 1
+    qw = dataclasses.replace(g["qw"], W=None)
+    staged = L.matmul(g["rows"], g["outl"], qw, g["ws"]).clone()
+    out = L.linear(g["Xd"], qw, d["alpha"], g["outl"], g["rows"], g["ws"])
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), staged.view(torch.int16))
+    O = oracle.find_outliers(d["X"], d["alpha"])[:cap]
+    Xq, cx = oracle.quantize_rows(d["X"], O)
+    Wq, cw = oracle.quantize_weight(d["W"])
+    ref = oracle.output_dq(oracle.igemm(Xq, Wq), cx, cw, d["X"], Wq, O)
+    assert_out_close(out.cpu().numpy(), ref)
 
 
 @pytest.mark.parametrize("via_linear", [False, True])
