@@ -324,11 +324,15 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
             FENCE();
 #pragma unroll
             for (int q = (i < OPSPAN ? i : OPSPAN) * NOPS / OPSPAN; q < (i + 1 < OPSPAN ? i + 1 : OPSPAN) * NOPS / OPSPAN; q++) {
-                if (q < PIECES) {
-                    if (MODE == 0) dma_k(vo, slot, q);
-                    if (MODE == 1 || MODE == 2) dma_e(MODE - 1, slot, q);
+                // Four waves: the requests first, then the reads (with the reads first 192 x 256 loses a quarter
+                // of its speed).  Eight waves: the reads first (0.5 % faster: the next stage's wait is for them).
+                const bool is_req = WQ == 4 ? q >= NRD : q < PIECES;
+                const int qr = WQ == 4 ? q - NRD : q, qd = WQ == 4 ? q : q - PIECES;
+                if (is_req) {
+                    if (MODE == 0) dma_k(vo, slot, qr);
+                    if (MODE == 1 || MODE == 2) dma_e(MODE - 1, slot, qr);
                 } else if (MODE != 4) {
-                    rd(std::integral_constant<int, 1 - SS>{}, nslot, q - PIECES);
+                    rd(std::integral_constant<int, 1 - SS>{}, nslot, qd);
                 }
             }
             FENCE();
