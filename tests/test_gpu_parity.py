@@ -443,19 +443,20 @@ def int8_rows_compare(d, cap=32, via_linear=False):
         assert not np.array_equal(bits(out.cpu().numpy()), bits(g["Out"]))
 
 
-def test_int8_rows_one_call_equals_staged_calls_when_more_columns_qualify_than_fit():
-    """Short X, no 16-bit weights, |O| > cap: the second pre-pass kernel of llmint8_linear rebuilds the rows of
-    the first cap outlier columns from the column lists; llmint8_matmul gets them from llmint8_dequantize_rows
-    via idx / count.  Same bits, and the rows are those of the oracle."""
+@pytest.mark.parametrize("cap", [4, 300])
+def test_int8_rows_one_call_equals_staged_calls_when_more_columns_qualify_than_fit(cap):
+    """Short X, no 16-bit weights: the second pre-pass kernel of llmint8_linear rebuilds the rows of the first
+    cap outlier columns from the column lists (cap = 4 < |O| = 9); with an outlier buffer of more than 256
+    columns (cap = 300) it leaves that to llmint8_dequantize_rows, as llmint8_matmul always does via idx /
+    count.  Same bits, and the rows are those of the oracle."""
     import dataclasses
 
     import torch
 
     import paper_2208_07339_amd as L
     d = wl.make_custom(20, 520, 136, 9, seed=56)
-    cap = 4
     g = run_hip(d["X"], d["W"], d["alpha"], cap, want_c=False)
-    assert int(g["outl"].status.item()) == 1
+    assert int(g["outl"].status.item()) == (1 if cap == 4 else 0)
     qw = dataclasses.replace(g["qw"], W=None)
     staged = L.matmul(g["rows"], g["outl"], qw, g["ws"]).clone()
     out = L.linear(g["Xd"], qw, d["alpha"], g["outl"], g["rows"], g["ws"])

@@ -210,6 +210,13 @@ def test_more_outlier_columns_than_cap():
     assert_out_close(out.cpu().numpy().reshape(-1), Os)
 
 
+def test_short_x_in_one_call_with_an_outlier_buffer_too_large_for_the_column_job():
+    """cap > 256: the per-column factors come from zp_kcol_kernel as in the staged calls, not from the second
+    pre-pass kernel.  Same outputs as the staged calls, Out against the oracle."""
+    d = wl.make_custom(12, 264, 72, 5, seed=91)
+    zp_compare(one_sided(d), d["W"], 6.0, cap=300)
+
+
 @pytest.mark.parametrize("s", [7, 32])
 def test_short_x_in_one_call_with_more_outlier_columns_than_cap(s):
     """The two-kernel pre-pass of a short X (s <= 32) inside llmint8_zp_linear, when more columns qualify
