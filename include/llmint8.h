@@ -133,7 +133,8 @@ int llmint8_matmul(const int8_t *Xq, const void *cx_f16, const void *Xo_f16, con
                    void *ws, size_t ws_bytes, llmint8_stream_t stream);
 
 /* The per-call sequence find_outliers -> quantize_rows -> matmul on one stream (W_f16 may be NULL
- * as for llmint8_matmul).
+ * as for llmint8_matmul): the same outputs as the three calls, bit for bit, from fewer kernels
+ * (two for the whole pre-pass when s <= 32, the rebuilt rows of W included).
  * Xq, cx_f16, Xo_f16, idx, count, status are caller-provided scratch/outputs
  * of the sizes given above.                                                   */
 int llmint8_linear(const void *X_f16, int s, int h, float alpha, const int8_t *Wq, const void *cw_f16,
@@ -209,6 +210,8 @@ int llmint8_zp_matmul(const int8_t *Xq, const int32_t *zc_x, const void *Xo_f16,
                       const int32_t *count, int cap, const int8_t *Wq, const int32_t *zc_w, const void *W_f16,
                       int s, int h, int o, void *Out_f16, int32_t *C_i32_debug, void *ws, size_t ws_bytes,
                       llmint8_stream_t stream);
+/* find_outliers -> zp_quantize_rows -> zp_matmul on one stream; the same outputs as the three calls, bit
+ * for bit (for s <= 32 from three kernels in all). */
 int llmint8_zp_linear(const void *X_f16, int s, int h, float alpha, const int8_t *Wq, const int32_t *zc_w,
                       const void *W_f16, int o, int32_t *idx, int cap, int32_t *count, int32_t *status,
                       int8_t *Xq, int32_t *zc_x, void *Xo_f16, void *Out_f16, void *ws, size_t ws_bytes,
