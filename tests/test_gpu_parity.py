@@ -88,6 +88,38 @@ def test_every_prefill_tile_shape_through_the_one_call_path(cfg, forced_tile):
     linear_compare(wl.make_custom(512, 1152, 576, 30, seed=67))             # nearly full 32-slot buffer
 
 
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+def test_workgroups_walk_interior_and_edge_tiles_in_turn(cfg, forced_tile):
+    """A tile grid larger than the chip with ragged edges in both directions (2300 tokens, 10 008 columns:
+    360 to 1 422 tiles on 256 workgroups), so that a persistent workgroup goes from an interior tile
+    (epilogue fed from LDS, its stores still in flight when the next tile starts) to an edge tile (guarded
+    epilogue) and back, for every tile shape.  Every output of llmint8_linear against the staged calls with the
+    accumulator export (every tile through the guarded epilogue), and samples of both against the oracle."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    d = wl.make_custom(2300, 384, 10008, 7, seed=71)
+    X, W = d["X"], d["W"]
+    s, o = 2300, 10008
+    forced_tile(cfg)
+    g = run_hip(X, W, d["alpha"], cap=32)
+    idx = oracle.find_outliers(X, d["alpha"])
+    assert g["idx"].tolist() == idx.tolist()
+    for _ in range(2):
+        out = L.linear(g["Xd"], g["qw"], d["alpha"], g["outl"], g["rows"], g["ws"])
+    torch.cuda.synchronize()
+    lin = out.cpu().numpy()
+    scale = float(np.abs(g["Out"].astype(np.float64)).max())
+    assert_out_close(lin, g["Out"], scale)
+    rng = np.random.default_rng(5)
+    ri = np.concatenate([rng.integers(0, s, 600), np.full(40, s - 1), rng.integers(2048, s, 100)])
+    ci = np.concatenate([rng.integers(0, o, 600), rng.integers(0, o, 40), rng.integers(9984, o, 100)])
+    Cs, Os = oracle.sampled(X, W, idx, ri, ci)
+    assert np.array_equal(g["C"][ri, ci], Cs)
+    assert_out_close(lin[ri, ci], Os, scale)
+    assert_out_close(g["Out"][ri, ci], Os, scale)
+
+
 @pytest.mark.parametrize("s,o", [(8, 64), (40, 96), (300, 264)])
 def test_accumulator_at_the_int32_bound(s, o):
     """Section 2.1: the int8 products are accumulated as 32-bit integers.  At the largest feature dimension
