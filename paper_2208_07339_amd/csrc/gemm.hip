@@ -65,16 +65,17 @@ struct GemmArgs {
 // (two per SIMD, 128 / 64 accumulator registers each), 192 x 256 and 128 x 128
 // with four.  Eight waves read each X tile from LDS twice as often, but two
 // waves per SIMD cover each other's waits in the epilogue, which takes 7.5 k
-// clocks instead of 13 k at 256 x 256 (the K loop is the same: 1 150-1 170
-// clocks per stage); measured A/B on one box: 338.5 against 344.7 us on a
-// 4096 x 5120 x 20480 product, 38.1 against 39.3 us on 2048 x 4096 x 4096.
-// 192 x 256 does not split evenly over eight waves (14 row tiles).
+// to 9 k clocks instead of 13 k at 256 x 256 (the K loop is fed by the same
+// loads: 1 100-1 170 clocks per stage either way); measured A/B on one box:
+// 338.5 against 344.7 us on a 4096 x 5120 x 20480 product, 38.1 against
+// 39.3 us on 2048 x 4096 x 4096.  192 x 256 does not split evenly over eight
+// waves (14 row tiles).
 //
 // K pipeline.  A stage is 64 features (2 MFMA k-steps) of all 2*WA + WQ*WB row
 // tiles; NB = 4 stages form a ring in LDS.  Tiles go global -> LDS with
 // 16-byte direct loads (one 1 KiB tile piece per wave instruction, the pieces
-// of a stage dealt evenly to the waves) and come back with one ds_read_b128 per operand (linear,
-// conflict free).  The operands of a whole stage sit in registers, double
+// of a stage dealt evenly to the waves) and come back with one ds_read_b128
+// per operand (linear, conflict free).  The operands of a whole stage sit in registers, double
 // buffered: while the MFMAs of stage st run from one register set, stage st+1
 // is read from LDS into the other and stage st+4 is requested from memory.
 // One barrier per stage, at its top: it publishes stage st+1 (every wave
@@ -94,11 +95,13 @@ struct GemmArgs {
 // pipeline.  Ring slots are addressed relative to a per-tile base for that.
 // ---------------------------------------------------------------------------
 // Measurement build (-DLLMINT8_GEMM_STAMPS, a library of its own: see build.py): every wave of one workgroup
-// records the shader clock at the phase boundaries of its second tile (its only tile, if it has one).  Stamp k of wave w is g_stamps[w][k]:
+// records the shader clock at the phase boundaries of its second tile (its only tile, if it has one).
+// Stamp k of wave w is g_stamps[w][k]:
 //   0 tile start, 1 first stage in LDS, 2 K loop done, 3 epilogue operands in LDS, 4 next tile's first two
 //   stages requested, 5 row constants / outlier columns of X in registers, then per pass over two column
-//   tiles (p = 0, 1): 6+6p column constants / outlier rows of W in registers, and per 64 x 64 block (q = 0, 1)
-//   7+6p+2q dequantized and staged, 8+6p+2q written out; 20 tile done.
+//   tiles (p = 0, 1): 6+6p column constants / outlier rows of W in registers, and per staged block of 64
+//   columns (q = 0, 1; 64 tokens with four waves, 32 with eight) 7+6p+2q dequantized and staged, 8+6p+2q
+//   written out; 20 tile done.
 // In the product build the macro is empty.
 #ifdef LLMINT8_GEMM_STAMPS
 __device__ long long g_stamps[8][32];
