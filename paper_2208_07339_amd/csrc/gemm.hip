@@ -101,13 +101,17 @@ struct GemmArgs {
 //   stages requested, 5 row constants / outlier columns of X in registers, then per pass over two column
 //   tiles (p = 0, 1): 6+6p column constants / outlier rows of W in registers, and per staged block of 64
 //   columns (q = 0, 1; 64 tokens with four waves, 32 with eight) 7+6p+2q dequantized and staged, 8+6p+2q
-//   written out; 20 tile done.
+//   written out; 20 tile done; 21 kernel entry; 22 / 23 the constant 100 MHz counter at stamps 0 / 20 (the
+//   shader clock inside the tile follows from the two pairs).
 // In the product build the macro is empty.
 #ifdef LLMINT8_GEMM_STAMPS
 __device__ long long g_stamps[8][32];
-#define STAMP(k)                                                                                  \
-    do {                                                                                          \
-        if (blockIdx.x == 9 && lane == 0 && pos == stamp_pos) g_stamps[w][k] = clock64();                   \
+#define STAMP(k)                                                                                   \
+    do {                                                                                           \
+        if (blockIdx.x == 9 && lane == 0 && pos == stamp_pos) {                                    \
+            g_stamps[w][k] = clock64();                                                            \
+            if ((k) == 0 || (k) == 20) g_stamps[w][(k) == 0 ? 22 : 23] = wall_clock64();           \
+        }                                                                                          \
     } while (0)
 #else
 #define STAMP(k) do { } while (0)
@@ -162,18 +166,14 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     const int stamp_pos = pos + (pos + gx < n_x ? gx : 0);
 #endif
 
-    int cnt = *g.count;
-    cnt = cnt < 0 ? 0 : (cnt > g.cap ? g.cap : cnt);
-    // lane t < 32 keeps the weight row of outlier slot t (row 0 for unused slots: finite values that
-    // meet the zeros of Xo)
+#ifdef LLMINT8_GEMM_STAMPS
+    if (blockIdx.x == 9 && lane == 0) g_stamps[w][21] = clock64();  // kernel entry
+#endif
+    // The number of outlier columns, and in lane t < 32 the weight row of outlier slot t (row 0 for unused
+    // slots: finite values that meet the zeros of Xo).  Both are loaded below, behind the requests of the
+    // first tile's first two stages: two dependent round trips that would otherwise sit in front of them.
+    int cnt = 0;
     int myk = 0;
-    if ((lane & 31) < cnt) {
-        const unsigned k = g.rows_are_slots ? (unsigned)(lane & 31) : (unsigned)g.idx[lane & 31];
-        myk = k < (unsigned)g.wrows ? (int)k : 0;
-    }
-    // once per kernel: with this load known to be complete, the compiler has no reason to drain the
-    // direct-to-LDS loads in flight when myk is used later in the K pipeline
-    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
 
     // ---- loader state: the tile whose stages are being requested.
     // Piece p = w*PIECES + k of a stage is k-half (p & 1) of row tile p >> 1 (W tiles first, then
@@ -347,6 +347,23 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     // stages 0 and 1 of the first tile (later tiles get theirs before the epilogue of the tile before)
     issue_stage(0, 0);
     issue_stage(1, 1);
+    FENCE();
+    {
+        // idx is read up to the buffer's size, not up to the count, so that the two loads do not wait for
+        // one another (entries past the count hold whatever the caller left there and are not used)
+        unsigned kraw = 0;
+        if (!g.rows_are_slots && (lane & 31) < g.cap) kraw = (unsigned)g.idx[lane & 31];
+        cnt = *g.count;
+        cnt = cnt < 0 ? 0 : (cnt > g.cap ? g.cap : cnt);
+        if ((lane & 31) < cnt) {
+            const unsigned k = g.rows_are_slots ? (unsigned)(lane & 31) : kraw;
+            myk = k < (unsigned)g.wrows ? (int)k : 0;
+        }
+    }
+    // once per kernel: with this load known to be complete, the compiler has no reason to drain the
+    // direct-to-LDS loads in flight when myk is used later in the K pipeline
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    FENCE();
 
     // Memory operations of a wave complete in the order they were issued, and the requests of a tile's first two
     // stages are issued before the epilogue of the tile before it.  After an unguarded epilogue exactly NST

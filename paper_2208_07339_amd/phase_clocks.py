@@ -60,6 +60,12 @@ def main():
     kloop = t[:, 2] - t[:, 1]
     print(f"  {'whole tile':62s} " + " ".join(f"{int(v):7d}" for v in total))
     print(f"  {'start of the tile relative to wave 0':62s} " + " ".join(f"{int(t[w, 0] - t[0, 0]):7d}" for w in range(nw)))
+    if (t[:, 0] > t[:, 21]).all() and int((t[:, 0] - t[:, 21]).max()) < 60000:  # the stamped tile is the workgroup's first
+        print(f"  {'kernel entry to the start of the tile':62s} " + " ".join(f"{int(t[w, 0] - t[w, 21]):7d}" for w in range(nw)))
+    ticks = (t[:, 23] - t[:, 22]).astype(np.float64)  # 100 MHz counter over the same tile
+    if (ticks > 0).all():
+        print(f"  shader clock inside the tile: {float((total / ticks).mean()) * 0.1:.2f} GHz "
+              f"({float(ticks.mean()) / 100:.1f} us per tile)")
     print(f"  K loop per stage: {kloop.mean() / stages:.0f} clocks; share of the tile outside the K loop: "
           f"{100 * (1 - kloop.mean() / total.mean()):.1f} %")
 
