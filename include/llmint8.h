@@ -231,13 +231,15 @@ int llmint8_probe_mfma(const int8_t *A_tiles, size_t a_bytes, const int8_t *B_ti
 int llmint8_probe_read(const void *buf, size_t bytes, int32_t *sink, llmint8_stream_t stream);
 
 /* Test/support: force the workgroup tile of the prefill GEMM (output columns x tokens):
- * 0 = 256 x 256, 1 = 192 x 256, 2 = 128 x 256, 3 = 128 x 128; -1 = choose from the shape (default).
+ * 0 = 256 x 256, 1 = 192 x 256, 2 = 128 x 256, 3 = 128 x 128, 4 = 192 x 128, 5 = 192 x 64; -1 = choose
+ * from the shape (default).
  * Process-wide; results do not depend on it.                                  */
-#define LLMINT8_PREFILL_TILES 4
+#define LLMINT8_PREFILL_TILES 6
 int llmint8_debug_prefill_tile(int cfg);
 
 /* Test/support: force the work split of the decode kernel (column tiles per workgroup, k-tiles per
- * load batch): 1 = 1 x 8 (the default), 2 = 2 x 4, 3 = 2 x 8, 4 = 3 x 4, 5 = 1 x 4; -1 = not forced.
+ * load batch): 1 = 1 x 8, 2 = 2 x 4, 3 = 2 x 8, 4 = 3 x 4, 5 = 1 x 4; -1 = not forced (1 x 8; 2 x 4 above
+ * 16 tokens when W has enough column tiles to fill the chip that way).
  * Anything else is LLMINT8_INVALID_ARG.  Process-wide; results do not depend on it.   */
 #define LLMINT8_DECODE_SHAPES 5
 int llmint8_debug_decode_shape(int cfg);

@@ -218,9 +218,21 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
     const int KT = k_tiles(h), JT = row_tiles(o);
     const int wrows = rows_are_slots ? opad_of(cap) : h;
     const ZpArgs none = {nullptr, nullptr, 0};
+    // Work split: one column tile per workgroup up to 16 tokens; above that every workgroup re-reads twice as
+    // much of X_i8 from L2 per weight tile, and two column tiles per workgroup (half the re-reads) are faster:
+    // 113.5 against 120.9 us at 32 tokens, 109.8 against 110.5 at 24, 107.4 against 104.6 at 16 (175B-shaped
+    // decode size) - as long as the halved grid still fills the chip with two workgroups per compute unit
+    // (at 5 120 x 20 480, 320 instead of 640 workgroups: 42.2 against 39.5 us at 32 tokens).
+    int cus = 0;
+    if (prefill_device_setup(&cus) != hipSuccess) cus = 256;
+    const bool wide = s > 16 && (JT + 1) / 2 >= 2 * cus;
     if (zp) {
-        gemm_decode_kernel<1, 8, true><<<JT, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo,
-                                                           count, cap, opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, *zp);
+        if (wide)
+            gemm_decode_kernel<2, 4, true><<<(JT + 1) / 2, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo,
+                                                                        count, cap, opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, *zp);
+        else
+            gemm_decode_kernel<1, 8, true><<<JT, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo,
+                                                               count, cap, opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, *zp);
         return hipGetLastError();
     }
 #define LAUNCH_DECODE(NJ, U)                                                                                     \
@@ -231,10 +243,15 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
         case 4: LAUNCH_DECODE(3, 4); break;
         case 5: LAUNCH_DECODE(1, 4); break;
         case 2: LAUNCH_DECODE(2, 4); break;
-        default: LAUNCH_DECODE(1, 8); break;  // 1, and -1 = not forced: twice as many workgroups as 2 x 4, three full
-                                              // rounds of two per CU at the 175B-shaped decode size (96.2 against
-                                              // 98.0 us there; 1 x 4: 97.4, 1 x 6: 98.0, 1 x 12 and 1 x 16: 109.6,
-                                              // 2 x 4 with eight waves per workgroup, one workgroup per CU: 111)
+        case 1: LAUNCH_DECODE(1, 8); break;
+        default:  // not forced.  1 x 8: twice as many workgroups as 2 x 4, three full rounds of two per CU at the
+                  // 175B-shaped decode size (16 tokens: 96.2 against 98.0 us; 1 x 4: 97.4, 1 x 6: 98.0, 1 x 12 and
+                  // 1 x 16: 109.6, 2 x 4 with eight waves per workgroup, one workgroup per CU: 111)
+            if (wide)
+                LAUNCH_DECODE(2, 4);
+            else
+                LAUNCH_DECODE(1, 8);
+            break;
     }
 #undef LAUNCH_DECODE
     return hipGetLastError();

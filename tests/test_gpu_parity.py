@@ -57,7 +57,7 @@ def forced_tile():
     L.debug_prefill_tile(-1)
 
 
-@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
 def test_every_prefill_tile_shape(cfg, forced_tile):
     """Each workgroup tile of the prefill GEMM on: interior + edge tiles with the outlier operands staged
     through LDS (7 and 20 columns), a 16-slot outlier buffer, more outlier columns than are staged (40),
@@ -71,7 +71,7 @@ def test_every_prefill_tile_shape(cfg, forced_tile):
     full_compare(wl.make_custom(330, 128, 264, 0, seed=6))
 
 
-@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
 def test_every_prefill_tile_shape_through_the_one_call_path(cfg, forced_tile):
     """llmint8_linear exports no accumulators, so interior tiles take the epilogue that is fed from LDS and
     stores without guards: the code the bench times.  Every workgroup tile, vector-wise constants (a wrong
@@ -88,7 +88,7 @@ def test_every_prefill_tile_shape_through_the_one_call_path(cfg, forced_tile):
     linear_compare(wl.make_custom(512, 1152, 576, 30, seed=67))             # nearly full 32-slot buffer
 
 
-@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
 def test_workgroups_walk_interior_and_edge_tiles_in_turn(cfg, forced_tile):
     """A tile grid larger than the chip with ragged edges in both directions (2300 tokens, 10 008 columns:
     360 to 1 422 tiles on 256 workgroups), so that a persistent workgroup goes from an interior tile

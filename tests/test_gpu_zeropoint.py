@@ -98,7 +98,7 @@ def test_zeropoint_on_one_sided_inputs(s, h, o, ncol, alpha):
         assert (ref["zp_x"] != 0).all()  # these rows are far from symmetric
 
 
-@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
 def test_every_prefill_tile_shape(cfg):
     """Each workgroup tile of the prefill GEMM in its zeropoint form, on grids with interior tiles (records and
     column factors staged through LDS, stores without guards) next to edge tiles: 7 and 20 outlier columns, a
