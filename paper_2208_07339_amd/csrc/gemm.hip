@@ -62,8 +62,8 @@ struct GemmArgs {
 // register quad.
 //
 // Shapes built: 256 x 256 and 128 x 256 (columns x tokens) with eight waves
-// (two per SIMD, 128 / 64 accumulator registers each), 192 x 256 and 128 x 128
-// with four.  Eight waves read each X tile from LDS twice as often, but two
+// (two per SIMD, 128 / 64 accumulator registers each), 192 x 256, 128 x 128,
+// 192 x 128 and 192 x 64 with four.  Eight waves read each X tile from LDS twice as often, but two
 // waves per SIMD cover each other's waits in the epilogue, which takes 7.5 k
 // to 9 k clocks instead of 13 k at 256 x 256 (the K loop is fed by the same
 // loads: 1 100-1 170 clocks per stage either way); measured A/B on one box:
