@@ -1,6 +1,7 @@
-// Decode path of Eq. 7 + Eq. 8 for s <= 32 tokens: the int8 weights are
-// streamed from HBM exactly once; the few tokens ride along as the second MFMA
-// operand.  Bandwidth bound (h * o bytes of W_i8 dominate).
+// Decode path of Eq. 7 + Eq. 8 for few tokens (s <= 32, and up to 64 against a
+// wide W): the int8 weights are streamed from HBM exactly once; the tokens ride
+// along as the second MFMA operand.  Bandwidth bound (h * o bytes of W_i8
+// dominate).
 #include <type_traits>
 
 #include "common.h"
@@ -14,19 +15,23 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int DSLOTS = 16;  // outlier slots whose operands are fetched before the weight stream starts
 
-// One workgroup = 4 waves owns NJ tiles of 32 output columns.  The waves split
-// K four ways; each streams its quarter of the W tiles (1 KiB contiguous per
-// wave load) in batches of U k-tiles, two batches in flight, and multiplies
-// them with the matching X tiles (row tile 0 of Xq: tokens 0..31, zero
-// padded).  The four partial accumulators meet in LDS; int32 sums are exact in
-// any order.  What the epilogue needs (c_w, c_x, the outlier columns of X and
+// One workgroup = 4 waves owns NJ tiles of 32 output columns and NI tiles of 32
+// tokens.  The waves split K four ways; each streams its quarter of the W tiles
+// (1 KiB contiguous per wave load) in batches of U k-tiles, two batches in
+// flight, and multiplies them with the matching X tiles (row tiles 0 .. NI-1 of
+// Xq, zero padded, from L2).  The four partial accumulators meet in LDS, one
+// token tile after the other; int32 sums are exact in any order.  With one
+// token tile, what the epilogue needs (c_w, c_x, the outlier columns of X and
 // the matching rows of the fp16 weights) is requested before the stream starts,
-// so that no workgroup ends with a chain of dependent loads.
+// so that no workgroup ends with a chain of dependent loads; with more, only
+// the per-column part is (the per-token part would take too many registers) and
+// the rest is loaded in the epilogue, under the stream of the compute unit's
+// other workgroup.
 //
 // ZP: zeropoint constants (Eq. 1-5) in place of c_x / c_w: the epilogue adds the three correction
 // terms of the unrolled product of Eq. 5 to the accumulator (in double: with zeropoints far from 0
 // they are large and cancel) and divides by nd_x nd_w.
-template <int NJ, int U, bool ZP>
+template <int NJ, int NI, int U, bool ZP>
 __global__ void __launch_bounds__(256)
 gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq, int KT, int JT,
                    const unsigned short* __restrict__ cw, const unsigned short* __restrict__ cx,
@@ -45,6 +50,7 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     int cnt = *count;
     cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
     const int jj = tid & 31, ig = tid >> 5;
+    constexpr bool EARLY = NI == 1;  // per-token epilogue operands fetched before the stream
     float cwj[NJ], sxi[4];
     unsigned wo[NJ][DSLOTS / 2];  // fp16 pairs: slots 2q (low half) and 2q+1 of this thread's columns
     uint4 xo[4][DSLOTS / 8];      // slots 0..15 of this thread's tokens (Xo holds zeros past |O|)
@@ -61,27 +67,31 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
             cwj[n] = (j < o) ? f16_bits_to_float(cw[j]) : 0.0f;
         }
     }
+    // the per-token operands of token tile ti: this thread's tokens 32 ti + ig + 8 m
+    auto token_operands = [&](int ti) {
 #pragma unroll
-    for (int m = 0; m < 4; m++) {
-        const int i = ig + 8 * m;
-        if constexpr (ZP) {
-            const int4 r = (i < s) ? zp.zcx[i] : make_int4(0, 0, 0, 0);
-            zsa[m] = zp_range((unsigned)r.x) * (1.0 / 254.0);
-            zza[m] = (double)r.y;
-            zrs[m] = (double)r.z;
-        } else {
-            sxi[m] = (i < s) ? f16_bits_to_float(cx[i]) * (1.0f / 16129.0f) : 0.0f;
+        for (int m = 0; m < 4; m++) {
+            const int i = 32 * ti + ig + 8 * m;
+            if constexpr (ZP) {
+                const int4 r = (i < s) ? zp.zcx[i] : make_int4(0, 0, 0, 0);
+                zsa[m] = zp_range((unsigned)r.x) * (1.0 / 254.0);
+                zza[m] = (double)r.y;
+                zrs[m] = (double)r.z;
+            } else {
+                sxi[m] = (i < s) ? f16_bits_to_float(cx[i]) * (1.0f / 16129.0f) : 0.0f;
+            }
         }
-    }
 #pragma unroll
-    for (int m = 0; m < 4; m++) {
-        const int i = ig + 8 * m;
+        for (int m = 0; m < 4; m++) {
+            const int i = 32 * ti + ig + 8 * m;
 #pragma unroll
-        for (int q = 0; q < DSLOTS / 8; q++) {
-            xo[m][q] = make_uint4(0, 0, 0, 0);
-            if (cnt > 0 && i < s) xo[m][q] = *(const uint4*)(Xo + (size_t)i * opad + 8 * q);
+            for (int q = 0; q < DSLOTS / 8; q++) {
+                xo[m][q] = make_uint4(0, 0, 0, 0);
+                if (cnt > 0 && i < s) xo[m][q] = *(const uint4*)(Xo + (size_t)i * opad + 8 * q);
+            }
         }
-    }
+    };
+    if constexpr (EARLY) token_operands(0);
 #pragma unroll
     for (int t = 0; t < DSLOTS; t++) {
         unsigned k = 0;
@@ -107,24 +117,32 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
         jt = jt < JT ? jt : JT - 1;  // tiles past the matrix re-read the last one, results unused
         wp[n] = (const v4i*)(Wq + ((size_t)jt * KT + (size_t)w * kq) * TILE_BYTES) + lane;
     }
-    const v4i* xp = (const v4i*)(Xq + (size_t)w * kq * TILE_BYTES) + lane;
-    // a lane holds token (lane % 32) of the X tile; tokens >= s are zero padding and need not be fetched
-    const bool xrow = (lane & 31) < s;
+    // a lane holds token (lane % 32) of an X tile; tokens >= s are zero padding and need not be fetched
+    const v4i* xp[NI];
+    bool xrow[NI];
+#pragma unroll
+    for (int ti = 0; ti < NI; ti++) {
+        xp[ti] = (const v4i*)(Xq + ((size_t)ti * KT + (size_t)w * kq) * TILE_BYTES) + lane;
+        xrow[ti] = 32 * ti + (lane & 31) < s;
+    }
 
-    v16i acc[NJ];
+    v16i acc[NJ][NI];
 #pragma unroll
     for (int n = 0; n < NJ; n++)
 #pragma unroll
-        for (int r = 0; r < 16; r++) acc[n][r] = 0;
+        for (int ti = 0; ti < NI; ti++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[n][ti][r] = 0;
 
-    v4i wv[2][NJ][U], xv[2][U];
+    v4i wv[2][NJ][U], xv[2][NI][U];
     auto load = [&](auto B, int kt) {
         constexpr int BB = decltype(B)::value;
 #pragma unroll
         for (int u = 0; u < U; u++) {
 #pragma unroll
             for (int n = 0; n < NJ; n++) wv[BB][n][u] = __builtin_nontemporal_load(wp[n] + (size_t)(kt + u) * 64);
-            xv[BB][u] = xrow ? xp[(size_t)(kt + u) * 64] : v4i{0, 0, 0, 0};
+#pragma unroll
+            for (int ti = 0; ti < NI; ti++) xv[BB][ti][u] = xrow[ti] ? xp[ti][(size_t)(kt + u) * 64] : v4i{0, 0, 0, 0};
         }
     };
     auto mm = [&](auto B) {
@@ -133,7 +151,9 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
         for (int u = 0; u < U; u++)
 #pragma unroll
             for (int n = 0; n < NJ; n++)
-                acc[n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv[BB][n][u], xv[BB][u], acc[n], 0, 0, 0);
+#pragma unroll
+                for (int ti = 0; ti < NI; ti++)
+                    acc[n][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv[BB][n][u], xv[BB][ti][u], acc[n][ti], 0, 0, 0);
     };
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
@@ -153,32 +173,40 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     }
     if (b < nb) mm(B0{});  // odd number of batches: the last one is already in flight in buffer 0
     for (int kt = nb * U; kt < kq; kt++) {
-        const v4i x1 = xrow ? xp[(size_t)kt * 64] : v4i{0, 0, 0, 0};
+        v4i x1[NI];
+#pragma unroll
+        for (int ti = 0; ti < NI; ti++) x1[ti] = xrow[ti] ? xp[ti][(size_t)kt * 64] : v4i{0, 0, 0, 0};
 #pragma unroll
         for (int n = 0; n < NJ; n++) {
             const v4i w1 = __builtin_nontemporal_load(wp[n] + (size_t)kt * 64);
-            acc[n] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1, x1, acc[n], 0, 0, 0);
+#pragma unroll
+            for (int ti = 0; ti < NI; ti++)
+                acc[n][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w1, x1[ti], acc[n][ti], 0, 0, 0);
         }
     }
+
+    // ---- reduction over the four waves and epilogue, token tile by token tile.  Accumulator element (token
+    // i of the tile, column jj) lives in register r = 4*(jj/8) + jj%4 of lane l = i + 32*((jj/4)%2).
+    const int r = 4 * (jj >> 3) + (jj & 3);
+    const int lsel = 32 * ((jj >> 2) & 1);
+#pragma unroll
+    for (int ti = 0; ti < NI; ti++) {
+    if (ti > 0) __syncthreads();  // every thread is done reading the tile before
 #pragma unroll
     for (int n = 0; n < NJ; n++)
 #pragma unroll
-        for (int r = 0; r < 16; r++) red[w][n][r][lane] = acc[n][r];
+        for (int q = 0; q < 16; q++) red[w][n][q][lane] = acc[n][ti][q];
+    if constexpr (!EARLY) token_operands(ti);
     __syncthreads();
-
-    // ---- epilogue.  Accumulator element (token i, column jj) of a tile lives in register
-    // r = 4*(jj/8) + jj%4 of lane l = i + 32*((jj/4)%2).
-    const int r = 4 * (jj >> 3) + (jj & 3);
-    const int lsel = 32 * ((jj >> 2) & 1);
 #pragma unroll
     for (int n = 0; n < NJ; n++) {
         const int j = (jt0 + n) * 32 + jj;
         if (j >= o) continue;
 #pragma unroll
         for (int m = 0; m < 4; m++) {
-            const int i = ig + 8 * m;
+            const int il = ig + 8 * m, i = 32 * ti + il;
             if (i >= s) continue;
-            const int l = i + lsel;
+            const int l = il + lsel;
             const int c = red[0][n][r][l] + red[1][n][r][l] + red[2][n][r][l] + red[3][n][r][l];
             if (Cdbg) Cdbg[(size_t)i * o + j] = c;
             // Eq. 7 dequantization, then the outlier product of Eq. 8 accumulated in fp32
@@ -206,9 +234,25 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
             Out[(size_t)i * o + j] = (_Float16)d;
         }
     }
+    }  // token tiles
 }
 
 std::atomic<int> g_decode_cfg{-1};  // test hook, as g_force_cfg
+
+// Which token counts take this kernel: up to 32 always; 33 to 48 (two token tiles per workgroup) when W is
+// wide enough for its halved grid to fill the chip with two workgroups per compute unit, where the call is
+// bound by the weight stream and the tiled GEMM gets less out of it: 119.4 against 133.3 us at 33 tokens,
+// 127.6 against 134.5 at 48, but 142.7 against 123.5 at 64, where the X tiles that every workgroup re-reads
+// from L2 are as many bytes as W (175B-shaped decode size).  Absmax only: with the zeropoint epilogue that
+// instantiation needs more registers than two workgroups per compute unit leave.
+bool decode_kernel_takes(int s, int o, bool zeropoint)
+{
+    if (s <= 32) return true;
+    if (s > 48 || zeropoint) return false;
+    int cus = 0;
+    if (prefill_device_setup(&cus) != hipSuccess) cus = 256;
+    return (row_tiles(o) + 1) / 2 >= 2 * cus;
+}
 
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
@@ -226,17 +270,23 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
     int cus = 0;
     if (prefill_device_setup(&cus) != hipSuccess) cus = 256;
     const bool wide = s > 16 && (JT + 1) / 2 >= 2 * cus;
+    if (s > 32) {  // two token tiles (decode_kernel_takes said so)
+        if (zp || s > 64) return hipErrorInvalidValue;
+        gemm_decode_kernel<2, 2, 4, false><<<(JT + 1) / 2, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx,
+                                                                        Xo, count, cap, opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, none);
+        return hipGetLastError();
+    }
     if (zp) {
         if (wide)
-            gemm_decode_kernel<2, 4, true><<<(JT + 1) / 2, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo,
+            gemm_decode_kernel<2, 1, 4, true><<<(JT + 1) / 2, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo,
                                                                         count, cap, opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, *zp);
         else
-            gemm_decode_kernel<1, 8, true><<<JT, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo,
+            gemm_decode_kernel<1, 1, 8, true><<<JT, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo,
                                                                count, cap, opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, *zp);
         return hipGetLastError();
     }
 #define LAUNCH_DECODE(NJ, U)                                                                                     \
-    gemm_decode_kernel<NJ, U, false><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo, count, cap, \
+    gemm_decode_kernel<NJ, 1, U, false><<<(JT + NJ - 1) / NJ, 256, 0, st>>>(Wq, Xq, KT, JT, cw, cx, Wf, rows_are_slots, wrows, idx, Xo, count, cap, \
                                                                  opad_of(cap), (_Float16*)Out, Cdbg, s, h, o, none)
     switch (g_decode_cfg.load(std::memory_order_relaxed)) {
         case 3: LAUNCH_DECODE(2, 8); break;

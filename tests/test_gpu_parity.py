@@ -157,6 +157,18 @@ def test_accumulator_at_the_int32_bound(s, o):
     assert_out_close(out.cpu().numpy(), closed.astype(np.float16))
 
 
+@pytest.mark.parametrize("s,h,o,ncol", [(33, 384, 32768, 3), (48, 200, 32800, 5), (41, 520, 40960, 20), (47, 64, 33000, 0),
+                                        (49, 128, 32768, 2)])
+def test_two_token_tiles_through_the_weight_streaming_kernel(s, h, o, ncol):
+    """33 to 48 tokens against a weight matrix of at least 32 736 columns take the weight-streaming kernel with
+    two token tiles per workgroup (narrower ones, and 49 tokens, go to the tiled kernel).  Every stage against
+    the oracle, staged with the accumulator export and through the one-call path; the last column tiles are
+    ragged."""
+    d = wl.make_custom(s, h, o, ncol, seed=3 * s + ncol)
+    full_compare(d)
+    linear_compare(d)
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_every_decode_work_split(cfg):
     import paper_2208_07339_amd as L
