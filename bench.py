@@ -36,7 +36,7 @@ TRAFFIC_SOURCE = "profiles/bench_default_ffn13b_decode_hbm_traffic.txt"
 MEASURED_TRAFFIC = {
     # FETCH_SIZE / 0.5001 + WRITE_SIZE / 1.0 (KiB -> bytes; factors from the copy probe of the same runs)
     "ffn13b": 635.20e6 + 168.35e6,   # gemm_prefill_kernel<4,2,4>: operand panels re-fetched per XCD and round + Out
-    "decode": 607.20e6 + 1.57e6,     # gemm_decode_kernel<1,8>
+    "decode": 607.20e6 + 1.57e6,     # gemm_decode_kernel<1,1,8>
 }
 
 
