@@ -236,6 +236,9 @@ int llmint8_probe_read(const void *buf, size_t bytes, int32_t *sink, llmint8_str
  * Process-wide; results do not depend on it.                                  */
 #define LLMINT8_PREFILL_TILES 6
 int llmint8_debug_prefill_tile(int cfg);
+/* Test/support: the tile (0 .. LLMINT8_PREFILL_TILES - 1) the library chooses by itself for a product of
+ * [s x h] by [h x o]; -1 for a dimension < 1.  Host arithmetic only: needs no GPU.             */
+int llmint8_debug_prefill_tile_for(int s, int h, int o);
 
 /* Test/support: force the work split of the decode kernel (column tiles per workgroup, k-tiles per
  * load batch): 1 = 1 x 8, 2 = 2 x 4, 3 = 2 x 8, 4 = 3 x 4, 5 = 1 x 4; -1 = not forced (1 x 8; 2 x 4 above

@@ -8,7 +8,7 @@ HIP library is missing, loading fails.
 from .binding import (  # noqa: F401
     LIB_PATH, Llmint8Error, QuantizedWeight, Outliers, QuantizedRows, Workspace,
     lib, find_outliers, quantize_rows, quantize_weight, matmul, linear, export_rows, export_weight,
-    workspace_bytes, wq_bytes, xq_bytes, opad, debug_prefill_tile, debug_decode_shape, dequantize_rows,
+    workspace_bytes, wq_bytes, xq_bytes, opad, debug_prefill_tile, debug_prefill_tile_for, debug_decode_shape, dequantize_rows,
     init, linear_static, STATIC_SCRATCH_BYTES, probe_mfma, probe_read,
     GRANULARITY, ZpWeight, ZpRows, zp_quantize_weight, zp_quantize_rows, zp_matmul, zp_linear,
 )

@@ -15,7 +15,7 @@ SYMBOLS = [
     "llmint8_quantize_weight_granular", "llmint8_quantize_rows_granular", "llmint8_linear_granular",
     "llmint8_zp_quantize_weight", "llmint8_zp_quantize_rows", "llmint8_zp_matmul", "llmint8_zp_linear",
     "llmint8_export_weight",
-    "llmint8_export_rows", "llmint8_debug_prefill_tile",
+    "llmint8_export_rows", "llmint8_debug_prefill_tile", "llmint8_debug_prefill_tile_for",
     "llmint8_debug_decode_shape",
 ]
 
@@ -94,6 +94,8 @@ def lib():
     L.llmint8_export_rows.argtypes = [vp, i32, i32, vp, vp]
     L.llmint8_debug_prefill_tile.restype = i32
     L.llmint8_debug_prefill_tile.argtypes = [i32]
+    L.llmint8_debug_prefill_tile_for.restype = i32
+    L.llmint8_debug_prefill_tile_for.argtypes = [i32, i32, i32]
     L.llmint8_debug_decode_shape.restype = i32
     L.llmint8_debug_decode_shape.argtypes = [i32]
     _lib = L
@@ -300,6 +302,11 @@ def probe_read(buf, sink):
 def debug_prefill_tile(cfg):
     """llmint8_debug_prefill_tile: force the prefill GEMM's workgroup tile (-1 = automatic)."""
     _check(lib().llmint8_debug_prefill_tile(int(cfg)))
+
+
+def debug_prefill_tile_for(s, h, o):
+    """llmint8_debug_prefill_tile_for: the tile the library chooses for [s x h] by [h x o] (no GPU needed)."""
+    return int(lib().llmint8_debug_prefill_tile_for(int(s), int(h), int(o)))
 
 
 def debug_decode_shape(cfg):

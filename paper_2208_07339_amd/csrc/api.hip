@@ -473,6 +473,12 @@ int llmint8_debug_prefill_tile(int cfg)
     return LLMINT8_OK;
 }
 
+int llmint8_debug_prefill_tile_for(int s, int h, int o)
+{
+    if (s < 1 || h < 1 || o < 1) return -1;
+    return pick_cfg(s, h, o);
+}
+
 int llmint8_debug_decode_shape(int cfg)
 {
     if (cfg != -1 && (cfg < 1 || cfg > LLMINT8_DECODE_SHAPES)) return LLMINT8_INVALID_ARG;

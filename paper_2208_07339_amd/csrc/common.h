@@ -254,6 +254,8 @@ hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const 
 hipError_t launch_dequant_rows(const int8_t* Wq, const unsigned short* cw, int h, int o, const int32_t* idx,
                                const int32_t* count, int cap, unsigned short* Wo, hipStream_t st);
 
+// tile shape the prefill GEMM chooses for a product of s x h by h x o (host arithmetic only)
+int pick_cfg(int s, int h, int o);
 // tile shape of the prefill GEMM forced by llmint8_debug_prefill_tile (-1: chosen from the shape)
 extern std::atomic<int> g_force_cfg;
 // work split of the decode kernel forced by llmint8_debug_decode_shape (-1: default)

@@ -763,7 +763,7 @@ static inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 // five weight matrices at 33 to 1 024 tokens and to the three full-size workloads: the choice is then within
 // 1.2 % of the fastest shape on average and 26 % in the worst case (5 120 x 20 480 at 256 tokens).
 constexpr int NCFG = 6;
-static int pick_cfg(int s, int h, int o)
+int pick_cfg(int s, int h, int o)
 {
     static const int cols[NCFG] = {256, 192, 128, 128, 192, 192}, toks[NCFG] = {256, 256, 256, 128, 128, 64};
     static const double eff[NCFG] = {1.0, 0.96, 0.95, 0.85, 0.8, 0.5};  // relative MFMA rate of the main loop

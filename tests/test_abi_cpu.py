@@ -83,6 +83,25 @@ def test_argument_checks_of_the_variants_need_no_gpu(lib):
     assert b"static" in lib.llmint8_status_string(5)
 
 
+def test_tile_choice_of_the_prefill_gemm(lib):
+    """Host logic: the workgroup tile chosen from the shape (llmint8_debug_prefill_tile_for needs no GPU).
+    0 = 256 x 256, 1 = 192 x 256, 2 = 128 x 256, 3 = 128 x 128, 4 = 192 x 128, 5 = 192 x 64 (columns x tokens)."""
+    f = lib.llmint8_debug_prefill_tile_for
+    f.restype, f.argtypes = C.c_int, [C.c_int] * 3
+    # the three prefill workloads of the benchmark keep the shapes their figures were measured with
+    assert f(4096, 5120, 20480) == 0      # 13B FFN: 1 280 tiles = 5 full passes of 256 x 256
+    assert f(2048, 49152, 12288) == 1     # 175B FFN down: 512 tiles of 192 x 256 = 2 full passes (256 x 256: 1.5)
+    assert f(2048, 4096, 4096) == 2       # 6.7B attention: one 128 x 256 tile per compute unit
+    # short X against a wide W: one 192-column tile per compute unit, token tile as small as covers X
+    assert f(64, 12288, 49152) == 5 and f(33, 12288, 49152) == 5
+    assert f(128, 12288, 49152) == 4 and f(96, 12288, 49152) == 4
+    assert f(256, 12288, 49152) == 1
+    # every answer is a valid tile, whatever the shape; nonsense is refused
+    for s, h, o in [(33, 1, 1), (33, 133144, 7), (100000, 64, 8), (4096, 4096, 1 << 20), (257, 129, 65)]:
+        assert 0 <= f(s, h, o) < 6
+    assert f(0, 4, 4) == -1 and f(4, 4, -1) == -1
+
+
 def test_benchmark_shapes_fit_the_static_scratch(lib):
     import paper_2208_07339_amd as L
     from paper_2208_07339_amd import workloads as wl
