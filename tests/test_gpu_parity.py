@@ -377,6 +377,36 @@ def test_linear_prefill_sizes():
     linear_compare(wl.make_custom(48, 256, 64, 0, seed=47), alpha=float("inf"))
 
 
+def test_linear_with_33_to_64_tokens():
+    """Two row tiles of X, the smallest prefill shapes (and, against a wide W, the weight-streaming kernel with
+    two token tiles).  Every stage of llmint8_linear against the oracle: ragged h, more qualifying columns than
+    the buffer takes, every column an outlier, none, a row of zeros in the second tile, a long outlier buffer,
+    and no 16-bit weights."""
+    import dataclasses
+
+    import torch
+
+    import paper_2208_07339_amd as L
+    linear_compare(wl.make_custom(33, 384, 96, 3, seed=81))
+    linear_compare(wl.make_custom(64, 1000, 264, 5, seed=82))
+    linear_compare(wl.make_custom(47, 4160, 64, 20, seed=83))
+    linear_compare(wl.make_custom(50, 1536, 64, 9, seed=84), cap=4)       # |O| > cap
+    linear_compare(wl.make_custom(40, 96, 64, 2, seed=85), alpha=0.0, cap=96)
+    linear_compare(wl.make_custom(48, 256, 64, 0, seed=86), alpha=float("inf"))
+    linear_compare(wl.make_custom(64, 600, 64, 300, seed=87, frac=0.3), cap=300)
+    linear_compare(wl.make_custom(65, 512, 96, 3, seed=88))
+    d = wl.make_custom(45, 512, 96, 2, seed=89)
+    d["X"][37] = 0
+    linear_compare(d)
+    d = wl.make_custom(40, 520, 136, 6, seed=90)
+    g = run_hip(d["X"], d["W"], d["alpha"], 32, want_c=False)
+    qw = dataclasses.replace(g["qw"], W=None)
+    staged = L.matmul(g["rows"], g["outl"], qw, g["ws"]).clone()
+    out = L.linear(g["Xd"], qw, d["alpha"], g["outl"], g["rows"], g["ws"])
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), staged.view(torch.int16))
+
+
 def test_linear_prefill_branches_of_the_prepass():
     """llmint8_linear for s > 32 on shapes that take every branch of its pre-pass: several row slabs, a single
     512-column block, ragged K, |O| > cap, every column an outlier, thousands of outlier columns (with and

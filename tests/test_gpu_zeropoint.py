@@ -86,7 +86,8 @@ def one_sided(d, shift=0.0):
 
 
 SHAPES = [(8, 256, 512, 2), (16, 1024, 2048, 5), (13, 200, 61, 2), (32, 4160, 96, 6),   # weight-streaming path
-          (33, 64, 32, 1), (100, 300, 200, 3), (256, 1024, 512, 4), (333, 520, 260, 5)]  # tiled path
+          (33, 64, 32, 1), (100, 300, 200, 3), (256, 1024, 512, 4), (333, 520, 260, 5),  # tiled path
+          (48, 1000, 264, 4), (64, 384, 96, 7)]                       # ... with two row tiles of X
 
 
 @pytest.mark.parametrize("alpha", [6.0, INF])
@@ -217,7 +218,7 @@ def test_short_x_in_one_call_with_an_outlier_buffer_too_large_for_the_column_job
     zp_compare(one_sided(d), d["W"], 6.0, cap=300)
 
 
-@pytest.mark.parametrize("s", [7, 32])
+@pytest.mark.parametrize("s", [7, 32, 33, 57, 64])
 def test_short_x_in_one_call_with_more_outlier_columns_than_cap(s):
     """The two-kernel pre-pass of a short X (s <= 32) inside llmint8_zp_linear, when more columns qualify
     than the buffer takes: the row ranges are taken again over everything but the first cap columns.  Every
