@@ -49,7 +49,8 @@ struct GemmArgs {
     _Float16* Out;               // [s x o]
     int32_t* Cdbg;               // NULL or [s x o]
     int s, h, o;
-    int fast_ok;                 // o % 8 == 0 and every epilogue operand 16-byte aligned
+    int fast_ok;                 // o % 8 == 0, o < 2^21 and every epilogue operand 16-byte aligned
+    int ragged_ok;               // a tile that reaches past the last token may take the unguarded epilogue too
     ZpArgs zp;                   // zeropoint constants (ZP kernels only)
 };
 
@@ -193,7 +194,8 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
         const int qi = q0 + inband - pj * bh;
         J0w = pj * 64 * WA;
         I0w = qi * 32 * TX;
-        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 32 * TX <= s);
+        // (a tile that reaches past the last token qualifies if its operands can be clamped: see esrc)
+        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 32 * TX <= s || g.ragged_ok);
 #pragma unroll
         for (int k = 0; k < PIECES; k++) {
             const int p = w * PIECES + k;
@@ -223,7 +225,10 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     // the tile's 64*WA columns repeat chunk 0); then 2*TX pieces of Xo, [32*TX tokens][opad slots] as it lies in
     // memory; then one piece with c_w (lanes 0-31) and c_x (lanes 32-63).  Zeropoint: that piece is idle, and
     // TX/2 pieces with the records of the tile's tokens and 3 x NZP pieces with the planes of column factors
-    // follow.  Whatever is left of the two stages re-reads a harmless piece.
+    // follow.  Whatever is left of the two stages re-reads a harmless piece.  Where a ragged tile reaches past the
+    // last token, the lanes re-read a token that exists (the last one; for c_x, whose 16-byte chunks hold eight
+    // tokens, the tile's first chunk: such tiles come here only when s is a multiple of 8); nothing computed
+    // from those values is stored.
     auto esrc = [&](int n) -> const void* {
         // The addresses depend on the tile only; the opaque copy of the lane number keeps the compiler from
         // computing all of them at the start of the tile and carrying them through the K loop in registers.
@@ -238,11 +243,17 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
         }
         if (n < NEW + NEX) {
             const int pn = (n - NEW) * 32 < NEX * opad ? (n - NEW) : 0;  // opad == 16: half as many pieces
-            return g.Xo + ((size_t)I0w * opad + pn * 512 + ln * 8);
+            const int e = pn * 512 + ln * 8;                              // element within the tile's rows of Xo
+            int i = I0w + (opad == 32 ? e >> 5 : e >> 4);
+            i = i < s ? i : s - 1;
+            return g.Xo + ((size_t)i * opad + (e & (opad - 1)));
         }
         if constexpr (ZP) {
             const int m = n - (NEW + NEX + 1);
-            if (m >= 0 && m < NZX) return g.zp.zcx + (I0w + m * 64 + ln);
+            if (m >= 0 && m < NZX) {
+                const int i = I0w + m * 64 + ln;
+                return g.zp.zcx + (i < s ? i : s - 1);
+            }
             if (m >= NZX && m < NZX + 3 * NZP) {
                 const int q = (m - NZX) / NZP, pp = (m - NZX) % NZP;
                 const int c = pp * 128 + 2 * ln;  // columns past the tile (odd WA) re-read the tile's first two
@@ -252,7 +263,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
         } else {
             if (n > NEW + NEX) return g.Xq + ln * 16;
             if (ln < 32) return g.cw + (J0w + wchunk);
-            const int c = (ln - 32) < 4 * TX ? (ln - 32) : 0;
+            const int c = (ln - 32) < 4 * TX && I0w + (ln - 32) * 8 < s ? (ln - 32) : 0;
             return g.cx + (I0w + c * 8);
         }
     };
@@ -473,8 +484,14 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
             return xb;
         };
 
-        // FAST: interior tile, operands from the LDS image of the epilogue stages, no guards.
+        // FAST: interior tile, operands from the LDS image of the epilogue stages, no guards.  Its stores go
+        // through a buffer descriptor that spans the tile's existing tokens (rows of Out from the tile's first
+        // token on): where a ragged tile reaches past the last token the hardware drops them, so a wave issues
+        // the same NST store instructions whatever the tile.
         // Otherwise: operands from memory, every access guarded; also exports the raw accumulators.
+        const int trows = s - cI0w < 32 * TX ? s - cI0w : 32 * TX;
+        const __amdgpu_buffer_rsrc_t obuf =
+            __builtin_amdgcn_make_buffer_rsrc(g.Out + (size_t)cI0w * o, 0, trows * o * 2, 0x00020000);
         auto epilogue = [&](auto F) {
             constexpr bool FAST = decltype(F)::value;
             if (!FAST && g.Cdbg) {
@@ -653,7 +670,8 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
                         const int i = I0 + b0 * 32 + tl;
                         const int j = J0 + a0 * 32 + q * 8;
                         if (FAST) {
-                            if (na == 2 || q < 4) __builtin_nontemporal_store(v, (u4*)(g.Out + (size_t)i * o + j));
+                            if (na == 2 || q < 4)  // byte offset < 2^31: o is bounded for this path; 2 = non-temporal
+                                __builtin_amdgcn_raw_buffer_store_b128(v, obuf, ((i - cI0w) * o + j) * 2, 0, 2);
                         } else if ((tl < 32 || b0 + 1 < WB) && i < s && q < 4 * na) {
                             if (g.fast_ok && j + 8 <= o) {
                                 *(u4*)(g.Out + (size_t)i * o + j) = v;
@@ -761,7 +779,7 @@ static inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 // units without a tile waste their share of that stream (with 192-column tiles a 49 152-column weight matrix
 // is exactly one tile per compute unit).  The constants are fitted to the kernel times of all six shapes on
 // five weight matrices at 33 to 1 024 tokens and to the three full-size workloads: the choice is then within
-// 1.2 % of the fastest shape on average and 26 % in the worst case (5 120 x 20 480 at 256 tokens).
+// 1.3 % of the fastest shape on average and 26 % in the worst case (5 120 x 20 480 at 256 tokens).
 constexpr int NCFG = 6;
 int pick_cfg(int s, int h, int o)
 {
@@ -801,8 +819,9 @@ hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const
     g.cap = cap; g.opad = opad_of(cap);
     g.Out = (_Float16*)Out; g.Cdbg = Cdbg;
     g.s = s; g.h = h; g.o = o;
-    g.fast_ok = (o % 8 == 0) && al16(cw) && al16(cx) && al16(Wf) && al16(Xo) && al16(Out) && al16(g.zp.zcx) &&
+    g.fast_ok = (o % 8 == 0) && o < (1 << 21) && al16(cw) && al16(cx) && al16(Wf) && al16(Xo) && al16(Out) && al16(g.zp.zcx) &&
                 al16(g.zp.colc);
+    g.ragged_ok = zp != nullptr || s % 8 == 0;  // c_x travels in chunks of eight tokens; zeropoint records one by one
     const int forced = g_force_cfg.load(std::memory_order_relaxed);
     const int c = forced >= 0 ? forced : pick_cfg(s, h, o);
     if (zp) {

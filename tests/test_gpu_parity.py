@@ -86,21 +86,27 @@ def test_every_prefill_tile_shape_through_the_one_call_path(cfg, forced_tile):
     linear_compare(wl.make_custom(384, 512, 768, 0, seed=65))               # no outlier product
     linear_compare(wl.make_custom(320, 256, 640, 9, seed=66), cap=4)        # |O| > cap: the first four only
     linear_compare(wl.make_custom(512, 1152, 576, 30, seed=67))             # nearly full 32-slot buffer
+    linear_compare(wl.make_custom(72, 256, 768, 5, seed=68))                # a ragged tile takes the unguarded epilogue
+    linear_compare(wl.make_custom(200, 320, 384, 18, seed=69))              # ... when s is a multiple of 8
+    linear_compare(wl.make_custom(325, 256, 640, 9, seed=70))               # and the guarded one otherwise
 
 
+@pytest.mark.parametrize("s", [2300, 2296])
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
-def test_workgroups_walk_interior_and_edge_tiles_in_turn(cfg, forced_tile):
+def test_workgroups_walk_interior_and_edge_tiles_in_turn(cfg, s, forced_tile):
     """A tile grid larger than the chip with ragged edges in both directions (2300 tokens, 10 008 columns:
     360 to 1 422 tiles on 256 workgroups), so that a persistent workgroup goes from an interior tile
     (epilogue fed from LDS, its stores still in flight when the next tile starts) to an edge tile (guarded
-    epilogue) and back, for every tile shape.  Every output of llmint8_linear against the staged calls with the
-    accumulator export (every tile through the guarded epilogue), and samples of both against the oracle."""
+    epilogue) and back, for every tile shape; with 2296 tokens (a multiple of 8) the tiles that reach past the
+    last token take the unguarded epilogue with guarded stores, between full tiles of the same band.  Every
+    output of llmint8_linear against the staged calls with the accumulator export (every tile through the
+    guarded epilogue), and samples of both against the oracle."""
     import torch
 
     import paper_2208_07339_amd as L
-    d = wl.make_custom(2300, 384, 10008, 7, seed=71)
+    d = wl.make_custom(s, 384, 10008, 7, seed=71)
     X, W = d["X"], d["W"]
-    s, o = 2300, 10008
+    o = 10008
     forced_tile(cfg)
     g = run_hip(X, W, d["alpha"], cap=32)
     idx = oracle.find_outliers(X, d["alpha"])

@@ -116,6 +116,8 @@ def test_every_prefill_tile_shape(cfg):
         zp_compare(one_sided(d), d["W"], 6.0, cap=8)
         d = wl.make_custom(384, 512, 768, 0, seed=94)
         zp_compare(one_sided(d, shift=-2.0), d["W"], INF)
+        d = wl.make_custom(443, 384, 768, 12, seed=95)  # the last tile of tokens is ragged, s odd
+        zp_compare(one_sided(d, shift=0.75), d["W"], 6.0)
     finally:
         L.debug_prefill_tile(-1)
 
