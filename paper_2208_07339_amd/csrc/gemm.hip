@@ -194,8 +194,9 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
         const int qi = q0 + inband - pj * bh;
         J0w = pj * 64 * WA;
         I0w = qi * 32 * TX;
-        // (a tile that reaches past the last token qualifies if its operands can be clamped: see esrc)
-        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS && (J0w + 64 * WA <= o) && (I0w + 32 * TX <= s || g.ragged_ok);
+        // (a tile that reaches past the last column qualifies too, one past the last token if the requests for
+        // its operands can be clamped: see esrc)
+        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS && (I0w + 32 * TX <= s || g.ragged_ok);
 #pragma unroll
         for (int k = 0; k < PIECES; k++) {
             const int p = w * PIECES + k;
@@ -227,15 +228,17 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     // TX/2 pieces with the records of the tile's tokens and 3 x NZP pieces with the planes of column factors
     // follow.  Whatever is left of the two stages re-reads a harmless piece.  Where a ragged tile reaches past the
     // last token, the lanes re-read a token that exists (the last one; for c_x, whose 16-byte chunks hold eight
-    // tokens, the tile's first chunk: such tiles come here only when s is a multiple of 8); nothing computed
-    // from those values is stored.
+    // tokens, the tile's first chunk: such tiles come here only when s is a multiple of 8); where it reaches past
+    // the last column, the tile's first columns (o is a multiple of 8 here).  Nothing computed from those values
+    // is stored.
     auto esrc = [&](int n) -> const void* {
         // The addresses depend on the tile only; the opaque copy of the lane number keeps the compiler from
         // computing all of them at the start of the tile and carrying them through the K loop in registers.
         int ln = lane;
         asm volatile("" : "+v"(ln));
         if (!interior) return g.Xq + ln * 16;  // edge tiles read their epilogue operands from memory later
-        const int wchunk = ((ln & 31) < 8 * WA ? (ln & 31) : 0) * 8;  // column offset of this lane in a W row
+        int wchunk = ((ln & 31) < 8 * WA ? (ln & 31) : 0) * 8;  // column offset of this lane in a W row
+        wchunk = J0w + wchunk < o ? wchunk : 0;
         if (n < NEW) {
             const int k0 = __builtin_amdgcn_readlane(myk, 2 * n), k1 = __builtin_amdgcn_readlane(myk, 2 * n + 1);
             const int k = (ln >> 5) ? k1 : k0;  // the piece holds slots 2n (lanes 0-31) and 2n+1 (lanes 32-63)
@@ -256,8 +259,8 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
             }
             if (m >= NZX && m < NZX + 3 * NZP) {
                 const int q = (m - NZX) / NZP, pp = (m - NZX) % NZP;
-                const int c = pp * 128 + 2 * ln;  // columns past the tile (odd WA) re-read the tile's first two
-                return g.zp.colc + ((size_t)q * g.zp.pitch + J0w + (c < 64 * WA ? c : 0));
+                const int c = pp * 128 + 2 * ln;  // columns past the tile (odd WA) or past o re-read the tile's first two
+                return g.zp.colc + ((size_t)q * g.zp.pitch + J0w + (c < 64 * WA && J0w + c < o ? c : 0));
             }
             return g.Xq + ln * 16;
         } else {
@@ -486,8 +489,9 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
 
         // FAST: interior tile, operands from the LDS image of the epilogue stages, no guards.  Its stores go
         // through a buffer descriptor that spans the tile's existing tokens (rows of Out from the tile's first
-        // token on): where a ragged tile reaches past the last token the hardware drops them, so a wave issues
-        // the same NST store instructions whatever the tile.
+        // token on): where a ragged tile reaches past the last token the hardware drops them, and lanes whose
+        // columns do not exist offer an offset past the buffer's end, so a wave issues the same NST store
+        // instructions whatever the tile.
         // Otherwise: operands from memory, every access guarded; also exports the raw accumulators.
         const int trows = s - cI0w < 32 * TX ? s - cI0w : 32 * TX;
         const __amdgpu_buffer_rsrc_t obuf =
@@ -671,7 +675,8 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
                         const int j = J0 + a0 * 32 + q * 8;
                         if (FAST) {
                             if (na == 2 || q < 4)  // byte offset < 2^31: o is bounded for this path; 2 = non-temporal
-                                __builtin_amdgcn_raw_buffer_store_b128(v, obuf, ((i - cI0w) * o + j) * 2, 0, 2);
+                                __builtin_amdgcn_raw_buffer_store_b128(v, obuf, j < o ? ((i - cI0w) * o + j) * 2 : 0x7fffffff,
+                                                                       0, 2);
                         } else if ((tl < 32 || b0 + 1 < WB) && i < s && q < 4 * na) {
                             if (g.fast_ok && j + 8 <= o) {
                                 *(u4*)(g.Out + (size_t)i * o + j) = v;
