@@ -784,7 +784,7 @@ static inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 // units without a tile waste their share of that stream (with 192-column tiles a 49 152-column weight matrix
 // is exactly one tile per compute unit).  The constants are fitted to the kernel times of all six shapes on
 // five weight matrices at 33 to 1 024 tokens and to the three full-size workloads: the choice is then within
-// 1.3 % of the fastest shape on average and 26 % in the worst case (5 120 x 20 480 at 256 tokens).
+// 0.8 % of the fastest shape on average and 9 % in the worst case (5 120 x 20 480 at 1 024 tokens).
 constexpr int NCFG = 6;
 int pick_cfg(int s, int h, int o)
 {
