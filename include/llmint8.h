@@ -125,6 +125,10 @@ int llmint8_dequantize_rows(const int8_t *Wq, const void *cw_f16, int h, int o, 
  * accumulated in fp32.  Token counts s <= 32 take a weight-streaming path.
  *   W_f16       in   the original weights; only rows O are read.  NULL: the rows rebuilt from
  *                    the codes (llmint8_dequantize_rows, done here into ws) take their place
+ *   cx_f16      in   [s] fp16.  If the array starts on a 16-byte boundary it is read in aligned
+ *                    16-byte pieces, the one that holds c_x[s-1] included: when s is not a multiple
+ *                    of 8, up to 14 bytes behind the array (never beyond that aligned piece, so
+ *                    never in another page) are read and ignored
  *   Out_f16     out  [s x o] fp16
  *   C_i32_debug out  NULL, or [s x o] int32 receiving the raw accumulators   */
 int llmint8_matmul(const int8_t *Xq, const void *cx_f16, const void *Xo_f16, const int32_t *idx,

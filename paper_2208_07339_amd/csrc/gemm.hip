@@ -50,7 +50,6 @@ struct GemmArgs {
     int32_t* Cdbg;               // NULL or [s x o]
     int s, h, o;
     int fast_ok;                 // o % 8 == 0, o < 2^21 and every epilogue operand 16-byte aligned
-    int ragged_ok;               // a tile that reaches past the last token may take the unguarded epilogue too
     ZpArgs zp;                   // zeropoint constants (ZP kernels only)
 };
 
@@ -194,9 +193,8 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
         const int qi = q0 + inband - pj * bh;
         J0w = pj * 64 * WA;
         I0w = qi * 32 * TX;
-        // (a tile that reaches past the last column qualifies too, one past the last token if the requests for
-        // its operands can be clamped: see esrc)
-        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS && (I0w + 32 * TX <= s || g.ragged_ok);
+        // (a tile that reaches past the last column or token qualifies too: esrc clamps its requests)
+        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS;
 #pragma unroll
         for (int k = 0; k < PIECES; k++) {
             const int p = w * PIECES + k;
@@ -228,9 +226,10 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     // TX/2 pieces with the records of the tile's tokens and 3 x NZP pieces with the planes of column factors
     // follow.  Whatever is left of the two stages re-reads a harmless piece.  Where a ragged tile reaches past the
     // last token, the lanes re-read a token that exists (the last one; for c_x, whose 16-byte chunks hold eight
-    // tokens, the tile's first chunk: such tiles come here only when s is a multiple of 8); where it reaches past
-    // the last column, the tile's first columns (o is a multiple of 8 here).  Nothing computed from those values
-    // is stored.
+    // tokens, the tile's first chunk); where it reaches past the last column, the tile's first columns (o is a
+    // multiple of 8 here).  Nothing computed from those values is stored.  The chunk of c_x that holds the last
+    // token is read whole: when s is not a multiple of 8 that is up to 14 bytes past the array, inside the same
+    // aligned 16 bytes (c_x is 16-byte aligned here), hence inside the same page as c_x[s-1].
     auto esrc = [&](int n) -> const void* {
         // The addresses depend on the tile only; the opaque copy of the lane number keeps the compiler from
         // computing all of them at the start of the tile and carrying them through the K loop in registers.
@@ -826,7 +825,6 @@ hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const
     g.s = s; g.h = h; g.o = o;
     g.fast_ok = (o % 8 == 0) && o < (1 << 21) && al16(cw) && al16(cx) && al16(Wf) && al16(Xo) && al16(Out) && al16(g.zp.zcx) &&
                 al16(g.zp.colc);
-    g.ragged_ok = zp != nullptr || s % 8 == 0;  // c_x travels in chunks of eight tokens; zeropoint records one by one
     const int forced = g_force_cfg.load(std::memory_order_relaxed);
     const int c = forced >= 0 ? forced : pick_cfg(s, h, o);
     if (zp) {
