@@ -125,7 +125,11 @@ constexpr int OSLOTS = 32;  // outlier slots staged through LDS; more are read f
 // the unrolled product of Eq. 5 to the accumulators (in double: with zeropoints far from 0 they are
 // large and cancel) and divides by nd_x nd_w.  The records of the tile's tokens and the three planes
 // of column factors travel through the epilogue stages like the absmax constants do.
-template <int WA, int WB, int WQ, bool ZP>
+//
+// GUARDED: the epilogue reads its operands from memory with every access guarded and can export the raw
+// accumulators (o not a multiple of 8, unaligned operands, more than 32 outlier columns, or the export asked
+// for).  Otherwise the epilogue is fed from LDS by the two epilogue stages and nothing in it is guarded.
+template <int WA, int WB, int WQ, bool ZP, bool GUARDED>
 __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArgs g)
 {
     constexpr int NWAVES = 2 * WQ;               // waves: 2 along the columns x WQ along the tokens
@@ -181,7 +185,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     const unsigned voff = lane * 16;
     const int8_t* gpp[PIECES];
     int J0w, I0w;   // first column / token of the tile
-    bool interior;  // its epilogue is fed from LDS and needs no guards
+    constexpr bool interior = !GUARDED;  // the epilogue is fed from LDS and needs no guards
     auto set_loader = [&](int logical) {
         constexpr int BAND = 4;
         const int nP = g.nP, nQ = g.nQ;
@@ -193,8 +197,6 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
         const int qi = q0 + inband - pj * bh;
         J0w = pj * 64 * WA;
         I0w = qi * 32 * TX;
-        // (a tile that reaches past the last column or token qualifies too: esrc clamps its requests)
-        interior = g.fast_ok && !g.Cdbg && opad <= OSLOTS;
 #pragma unroll
         for (int k = 0; k < PIECES; k++) {
             const int p = w * PIECES + k;
@@ -386,7 +388,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     bool after_fast = false;
     for (;;) {  // tiles of this workgroup
         const int cJ0w = J0w, cI0w = I0w;  // the tile being computed (the loader moves on before its epilogue)
-        const bool cinterior = interior;
+        constexpr bool cinterior = interior;
 #pragma unroll
         for (int a = 0; a < WA; a++)
 #pragma unroll
@@ -692,10 +694,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
                 }
             }
         };
-        if (cinterior)
-            epilogue(std::true_type{});
-        else
-            epilogue(std::false_type{});
+        epilogue(std::integral_constant<bool, !GUARDED>{});
 
         STAMP(20);
         if (!has_next) break;
@@ -720,11 +719,15 @@ constexpr int prefill_lds_bytes()
 template <int WA, int WB, int WQ>
 static hipError_t raise_lds_limit()
 {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, WQ, false>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<WA, WB, WQ>());
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void*)gemm_prefill_kernel<WA, WB, WQ, true>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<WA, WB, WQ>());
+    const void* k[4] = {(const void*)gemm_prefill_kernel<WA, WB, WQ, false, false>,
+                        (const void*)gemm_prefill_kernel<WA, WB, WQ, false, true>,
+                        (const void*)gemm_prefill_kernel<WA, WB, WQ, true, false>,
+                        (const void*)gemm_prefill_kernel<WA, WB, WQ, true, true>};
+    for (const void* f : k) {
+        const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<WA, WB, WQ>());
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 constexpr int MAX_DEVICES = 64;
@@ -768,7 +771,11 @@ static hipError_t launch_cfg(GemmArgs& g, hipStream_t st)
     const hipError_t e = prefill_device_setup(&ncu);
     if (e != hipSuccess) return e;
     const int total = g.nP * g.nQ;
-    gemm_prefill_kernel<WA, WB, WQ, ZP><<<total < ncu ? total : ncu, 128 * WQ, shm, st>>>(g);
+    // the unguarded epilogue: outputs and epilogue operands in 16-byte pieces, the outlier slots that fit LDS
+    if (g.fast_ok && !g.Cdbg && g.opad <= OSLOTS)
+        gemm_prefill_kernel<WA, WB, WQ, ZP, false><<<total < ncu ? total : ncu, 128 * WQ, shm, st>>>(g);
+    else
+        gemm_prefill_kernel<WA, WB, WQ, ZP, true><<<total < ncu ? total : ncu, 128 * WQ, shm, st>>>(g);
     return hipGetLastError();
 }
 
