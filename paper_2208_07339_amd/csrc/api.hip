@@ -227,7 +227,7 @@ static int matmul_impl(const int8_t* Xq, const void* cx_f16, const void* Xo_f16,
         Wrows = Wo;
         rows_are_slots = 1;
     }
-    if (decode_kernel_takes(s, o, false))
+    if (decode_kernel_takes(s, h, o, false))
         e = launch_gemm_decode(Xq, (const unsigned short*)cx_f16, (const unsigned short*)Xo_f16, count, cap, Wq,
                                (const unsigned short*)cw_f16, Wrows, rows_are_slots, idx, s, h, o,
                                (unsigned short*)Out_f16, C_i32_debug, st);
@@ -414,7 +414,7 @@ static int zp_matmul_impl(const int8_t* Xq, const int32_t* zc_x, const void* Xo_
     if (!have_factors) e = launch_zp_kcol(Wq, (const int4*)zc_w, h, o, idx, count, cap, kcol, st);
     if (e != hipSuccess) return hip_status(e);
     const ZpArgs zp = {(const int4*)zc_x, kcol, zp_col_pitch(o)};
-    if (decode_kernel_takes(s, o, true))
+    if (decode_kernel_takes(s, h, o, true))
         e = launch_gemm_decode(Xq, nullptr, (const unsigned short*)Xo_f16, count, cap, Wq, nullptr,
                                (const unsigned short*)W_f16, 0, idx, s, h, o, (unsigned short*)Out_f16, C_i32_debug,
                                st, &zp);
@@ -481,7 +481,7 @@ int llmint8_debug_prefill_tile_for(int s, int h, int o)
 
 int llmint8_debug_decode_shape(int cfg)
 {
-    if (cfg != -1 && (cfg < 1 || cfg > LLMINT8_DECODE_SHAPES)) return LLMINT8_INVALID_ARG;
+    if (cfg < -1 || cfg > LLMINT8_DECODE_SHAPES) return LLMINT8_INVALID_ARG;
     g_decode_cfg.store(cfg, std::memory_order_relaxed);
     return LLMINT8_OK;
 }

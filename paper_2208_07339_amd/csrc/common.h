@@ -246,7 +246,7 @@ hipError_t launch_gemm_prefill(const int8_t* Xq, const unsigned short* cx, const
                                const unsigned short* Wf, int rows_are_slots, const int32_t* idx, int s, int h, int o,
                                unsigned short* Out, int32_t* Cdbg, hipStream_t st, const ZpArgs* zp = nullptr);
 // token counts that the weight-streaming kernel takes (the others go to the tiled kernel)
-bool decode_kernel_takes(int s, int o, bool zeropoint);
+bool decode_kernel_takes(int s, int h, int o, bool zeropoint);
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,
                               const int32_t* count, int cap, const int8_t* Wq, const unsigned short* cw,
                               const unsigned short* Wf, int rows_are_slots, const int32_t* idx, int s, int h, int o,

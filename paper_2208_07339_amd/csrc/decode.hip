@@ -245,13 +245,29 @@ std::atomic<int> g_decode_cfg{-1};  // test hook, as g_force_cfg
 // 127.6 against 134.5 at 48, but 142.7 against 123.5 at 64, where the X tiles that every workgroup re-reads
 // from L2 are as many bytes as W (175B-shaped decode size).  Absmax only: with the zeropoint epilogue that
 // instantiation needs more registers than two workgroups per compute unit leave.
-bool decode_kernel_takes(int s, int o, bool zeropoint)
+bool decode_kernel_takes(int s, int h, int o, bool zeropoint)
 {
-    if (s <= 32) return true;
-    if (s > 48 || zeropoint) return false;
+    const int forced = g_decode_cfg.load(std::memory_order_relaxed);
+    if (forced == 0) return false;  // test hook: every token count through the tiled kernel
+    if (s > 48 || (s > 32 && zeropoint)) return false;
     int cus = 0;
     if (prefill_device_setup(&cus) != hipSuccess) cus = 256;
-    return (row_tiles(o) + 1) / 2 >= 2 * cus;
+    const int JT = row_tiles(o);
+    if (s <= 32) {
+        // Two workgroups of this kernel fit a compute unit, so a W of 2 to 4 column tiles per compute unit is
+        // taken in two rounds, the second one part empty, while the tiled kernel has one 128 x 128 tile for
+        // each of more than half of the compute units.  Per call at 8 / 16 / 32 tokens: 30.5 / 32.5 / 34.9 us
+        // tiled against 32.3 / 34.4 / 39.5 on 5 120 x 20 480, 40.6 / 42.0 / 44.6 against 44.1 / 45.7 / 51.6 on
+        // 8 192 x 22 016, 49.0 / 51.3 / 54.5 against 54.6 / 56.6 / 65.1 on 12 288 x 20 480.  One tile per compute
+        // unit streams its 128 columns at what one compute unit can pull, which costs more the longer K is:
+        // with the second round at least half full and K above 8 192 this kernel stays ahead (58.2 / 60.2 /
+        // 68.4 against 70.5 / 73.6 / 75.7 us on 12 288 x 24 576), as it does outside the range (25.7 against
+        // 29.6 us at 15 360 columns, 66.8 against 71.0 at 36 864).
+        const int second = JT - 2 * cus;  // workgroups of the second round
+        if (!zeropoint && forced < 0 && second > 0 && (o + 127) / 128 <= cus && (second < cus || h <= 8192)) return false;
+        return true;
+    }
+    return (JT + 1) / 2 >= 2 * cus;
 }
 
 hipError_t launch_gemm_decode(const int8_t* Xq, const unsigned short* cx, const unsigned short* Xo,

@@ -13,6 +13,7 @@ event-instrumented loop, after the warm-up and the timed loop, so that is the pa
 """
 import collections
 import csv
+import re
 import sys
 
 COPY_KIB = 256 * 1024  # bench.py COPY_PROBE_BYTES in KiB
@@ -20,6 +21,11 @@ COPY_KERNEL = "__amd_rocclr_copyBuffer"
 
 
 def short(name):
+    # rocprofv3 leaves names with _Float16 parameters mangled: spell the template arguments out
+    m = re.match(r"_ZN7llmint8\d+(\w+?)I((?:L[ib]-?\d+E)+)E", name)
+    if m:
+        args = [("true" if v == "1" else "false") if k == "b" else v for k, v in re.findall(r"L([ib])(-?\d+)E", m.group(2))]
+        return f"{m.group(1)}<{', '.join(args)}>"[:48]
     name = name.replace("llmint8::", "").replace("void ", "")
     return name.split("(")[0][:48]
 

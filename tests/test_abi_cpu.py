@@ -74,7 +74,8 @@ def test_argument_checks_of_the_variants_need_no_gpu(lib):
     assert lib.llmint8_dequantize_rows(None, None, 4, 4, None, None, 4, None, None) == 1
     assert lib.llmint8_debug_prefill_tile(99) == 1 and lib.llmint8_debug_prefill_tile(-1) == 0
     assert lib.llmint8_debug_decode_shape(99) == 1 and lib.llmint8_debug_decode_shape(-1) == 0
-    assert lib.llmint8_debug_decode_shape(0) == 1 and lib.llmint8_debug_decode_shape(6) == 1
+    assert lib.llmint8_debug_decode_shape(0) == 0 and lib.llmint8_debug_decode_shape(-1) == 0
+    assert lib.llmint8_debug_decode_shape(-2) == 1 and lib.llmint8_debug_decode_shape(6) == 1
     # the entry point on the static scratch: sizes are checked before anything touches a device
     f = C.c_float(6.0)
     assert lib.llmint8_linear_static(None, 0, 4, f, None, None, None, 4, None, 4, *([None] * 7)) == 1

@@ -188,6 +188,53 @@ def test_every_decode_work_split(cfg):
         L.debug_decode_shape(-1)
 
 
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
+def test_short_x_through_the_tiled_kernel(cfg, forced_tile):
+    """32 tokens and fewer normally go to the weight-streaming kernel; for some shapes of W the library sends
+    them to the tiled kernel instead (one 128 x 128 tile per compute unit beats two part-filled rounds of the
+    other).  With the weight-streaming kernel switched off, every tile shape on 1 to 32 tokens: a single row
+    tile of X repeated across the token tiles of a workgroup, all of them ragged; the staged calls with the
+    accumulator export (guarded epilogue) and the one-call path (unguarded)."""
+    import paper_2208_07339_amd as L
+    forced_tile(cfg)
+    L.debug_decode_shape(0)
+    try:
+        full_compare(wl.make_custom(16, 1024, 2048, 5, seed=1))
+        full_compare(wl.make_custom(13, 200, 61, 2, seed=2))
+        full_compare(wl.make_custom(1, 640, 520, 3, seed=5))
+        linear_compare(wl.make_custom(32, 1152, 776, 20, seed=3))
+        linear_compare(wl.make_custom(7, 512, 1544, 0, seed=4))
+        linear_compare(wl.make_custom(1, 256, 264, 1, seed=6))
+        linear_compare(wl.make_custom(24, 384, 768, 9, seed=7), cap=4)       # more columns qualify than fit
+        int8_rows_compare(wl.make_custom(16, 512, 520, 6, seed=8), via_linear=True)
+    finally:
+        L.debug_decode_shape(-1)
+
+
+def test_short_x_goes_to_the_tiled_kernel_where_w_has_two_to_four_column_tiles_per_compute_unit():
+    """The library's own choice on such a W (640 column tiles, K = 256) and the weight-streaming kernel forced
+    on the same buffers: both within tolerance of the oracle."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    s, h, o = 16, 256, 20480
+    d = wl.make_custom(s, h, o, 3, seed=9)
+    g = run_hip(d["X"], d["W"], d["alpha"], cap=32, want_c=False)
+    outs = []
+    try:
+        for route in (-1, 1):
+            L.debug_decode_shape(route)
+            out = torch.zeros((s, o), dtype=torch.float16, device="cuda")
+            L.linear(g["Xd"], g["qw"], d["alpha"], g["outl"], g["rows"], g["ws"], out)
+            torch.cuda.synchronize()
+            outs.append(out.cpu().numpy())
+    finally:
+        L.debug_decode_shape(-1)
+    ref = oracle.linear(d["X"], d["W"], d["alpha"])
+    assert_out_close(outs[0], ref["Out"])
+    assert_out_close(outs[1], ref["Out"])
+
+
 def test_alpha_zero_is_pure_fp16_matmul_on_both_paths():
     d = wl.make("tiny")
     g, r = full_compare(d, alpha=0.0, cap=256)
