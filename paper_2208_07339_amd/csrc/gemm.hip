@@ -185,7 +185,6 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     const unsigned voff = lane * 16;
     const int8_t* gpp[PIECES];
     int J0w, I0w;   // first column / token of the tile
-    constexpr bool interior = !GUARDED;  // the epilogue is fed from LDS and needs no guards
     auto set_loader = [&](int logical) {
         constexpr int BAND = 4;
         const int nP = g.nP, nQ = g.nQ;
@@ -237,7 +236,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
         // computing all of them at the start of the tile and carrying them through the K loop in registers.
         int ln = lane;
         asm volatile("" : "+v"(ln));
-        if (!interior) return g.Xq + ln * 16;  // edge tiles read their epilogue operands from memory later
+        if constexpr (GUARDED) return g.Xq + ln * 16;  // the guarded epilogue reads its operands from memory itself
         int wchunk = ((ln & 31) < 8 * WA ? (ln & 31) : 0) * 8;  // column offset of this lane in a W row
         wchunk = J0w + wchunk < o ? wchunk : 0;
         if (n < NEW) {
@@ -388,7 +387,6 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     bool after_fast = false;
     for (;;) {  // tiles of this workgroup
         const int cJ0w = J0w, cI0w = I0w;  // the tile being computed (the loader moves on before its epilogue)
-        constexpr bool cinterior = interior;
 #pragma unroll
         for (int a = 0; a < WA; a++)
 #pragma unroll
@@ -488,7 +486,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
             return xb;
         };
 
-        // FAST: interior tile, operands from the LDS image of the epilogue stages, no guards.  Its stores go
+        // FAST: operands from the LDS image of the epilogue stages, no guards.  Its stores go
         // through a buffer descriptor that spans the tile's existing tokens (rows of Out from the tile's first
         // token on): where a ragged tile reaches past the last token the hardware drops them, and lanes whose
         // columns do not exist offer an offset past the buffer's end, so a wave issues the same NST store
@@ -547,7 +545,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
             // zeropoint: this wave's 32*WA columns of the three factor planes, copied once per tile into a
             // wave-private piece of the epilogue-stage slots (they hold nothing such tiles need, and are
             // not refilled before every wave has passed the barrier at the top of the next tile)
-            // (interior tiles find the planes of the whole workgroup tile in the epilogue stages instead)
+            // (the unguarded epilogue finds the planes of the whole workgroup tile in the epilogue stages instead)
             double* ZC = (double*)(lds + eslot * STAGE) + w * (3 * 32 * WA);
             const double* zc0 = FAST ? EZc + wp * 32 * WA : ZC;  // this wave's first column in plane 0
             const int zstride = FAST ? NZP * 128 : 32 * WA;     // doubles from plane to plane
@@ -698,7 +696,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
 
         STAMP(20);
         if (!has_next) break;
-        after_fast = cinterior;
+        after_fast = !GUARDED;
         sbase = (eslot + 2) % NB;
         pos += gx;
     }  // tiles

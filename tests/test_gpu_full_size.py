@@ -4,9 +4,9 @@ constant, every column constant and both int8 tensors are compared in full;
 the int32 accumulators and fp16 outputs are compared on whole rows at tile
 edges and on random samples the oracle computes one by one from the
 definition.  Two runs per size: the staged calls with the accumulator export
-(which sends every tile of the prefill GEMM through its guarded epilogue), and
+(which runs the prefill GEMM's instantiation with the guarded epilogue), and
 llmint8_linear exactly as bench.py calls it (automatic tile shape, no export:
-interior tiles take the epilogue fed from LDS), whose outputs and intermediate
+the instantiation whose epilogue is fed from LDS), whose outputs and intermediate
 buffers are held to the same comparisons."""
 import numpy as np
 import pytest

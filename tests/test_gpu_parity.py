@@ -59,9 +59,9 @@ def forced_tile():
 
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
 def test_every_prefill_tile_shape(cfg, forced_tile):
-    """Each workgroup tile of the prefill GEMM on: interior + edge tiles with the outlier operands staged
-    through LDS (7 and 20 columns), a 16-slot outlier buffer, more outlier columns than are staged (40),
-    and a shape where nothing is aligned."""
+    """Each workgroup tile of the prefill GEMM through the staged calls with the accumulator export, i.e. the
+    kernels with the guarded epilogue: full and ragged tiles, 7 and 20 outlier columns, a 16-slot outlier
+    buffer, more outlier columns than the unguarded kernels stage (40), and a shape where nothing is aligned."""
     forced_tile(cfg)
     full_compare(wl.make_custom(512, 2048, 1024, 7, seed=1))
     full_compare(wl.make_custom(600, 640, 776, 20, seed=2))
@@ -73,34 +73,34 @@ def test_every_prefill_tile_shape(cfg, forced_tile):
 
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
 def test_every_prefill_tile_shape_through_the_one_call_path(cfg, forced_tile):
-    """llmint8_linear exports no accumulators, so interior tiles take the epilogue that is fed from LDS and
-    stores without guards: the code the bench times.  Every workgroup tile, vector-wise constants (a wrong
-    index into the staged c_x / c_w / Xo / W rows would show), on shapes with o % 8 == 0 whose grids have
-    interior tiles next to edge tiles: 7 and 20 outlier columns (one and two fp16 k-steps), a 16-slot outlier
-    buffer (opad = 16), a wide ragged grid, no outlier column at all, and more columns than the buffer takes."""
+    """llmint8_linear exports no accumulators, so with o % 8 == 0 the kernels with the epilogue that is fed from
+    LDS and stores without guards run: the code the bench times.  Every workgroup tile, vector-wise constants
+    (a wrong index into the staged c_x / c_w / Xo / W rows would show), on grids with full tiles next to tiles
+    that reach past the last token or column (their operand requests clamped, their stores cut off by the
+    buffer bounds): 7 and 20 outlier columns (one and two fp16 k-steps), a 16-slot outlier buffer (opad = 16),
+    a wide ragged grid, no outlier column at all, and more columns than the buffer takes."""
     forced_tile(cfg)
-    linear_compare(wl.make_custom(512, 2048, 1024, 7, seed=61))             # every tile interior (cfg 0: 2 x 4)
-    linear_compare(wl.make_custom(600, 640, 776, 20, seed=62))              # interior + edge in both directions
+    linear_compare(wl.make_custom(512, 2048, 1024, 7, seed=61))             # every tile full (cfg 0: 2 x 4)
+    linear_compare(wl.make_custom(600, 640, 776, 20, seed=62))              # full + ragged in both directions
     linear_compare(wl.make_custom(256, 256, 512, 3, seed=63), cap=8)        # opad = 16
     linear_compare(wl.make_custom(520, 384, 1544, 12, seed=64), cap=16)     # opad = 16, wide grid, ragged edges
     linear_compare(wl.make_custom(384, 512, 768, 0, seed=65))               # no outlier product
     linear_compare(wl.make_custom(320, 256, 640, 9, seed=66), cap=4)        # |O| > cap: the first four only
     linear_compare(wl.make_custom(512, 1152, 576, 30, seed=67))             # nearly full 32-slot buffer
-    linear_compare(wl.make_custom(72, 256, 768, 5, seed=68))                # a ragged tile takes the unguarded epilogue
-    linear_compare(wl.make_custom(200, 320, 384, 18, seed=69))              # ... when s is a multiple of 8
-    linear_compare(wl.make_custom(325, 256, 640, 9, seed=70))               # and the guarded one otherwise
+    linear_compare(wl.make_custom(72, 256, 768, 5, seed=68))                # every token tile ragged
+    linear_compare(wl.make_custom(200, 320, 384, 18, seed=69))
+    linear_compare(wl.make_custom(325, 256, 640, 9, seed=70))               # s odd: the last piece of c_x is part empty
 
 
 @pytest.mark.parametrize("s", [2300, 2296])
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
-def test_workgroups_walk_interior_and_edge_tiles_in_turn(cfg, s, forced_tile):
-    """A tile grid larger than the chip with ragged edges in both directions (2300 tokens, 10 008 columns:
-    360 to 1 422 tiles on 256 workgroups), so that a persistent workgroup goes from an interior tile
-    (epilogue fed from LDS, its stores still in flight when the next tile starts) to an edge tile (guarded
-    epilogue) and back, for every tile shape; with 2296 tokens (a multiple of 8) the tiles that reach past the
-    last token take the unguarded epilogue with guarded stores, between full tiles of the same band.  Every
-    output of llmint8_linear against the staged calls with the accumulator export (every tile through the
-    guarded epilogue), and samples of both against the oracle."""
+def test_workgroups_walk_full_and_ragged_tiles_in_turn(cfg, s, forced_tile):
+    """A tile grid larger than the chip with ragged edges in both directions (2300 or 2296 tokens, 10 008
+    columns: 360 to 1 422 tiles on 256 workgroups), so that a persistent workgroup goes from a full tile (its
+    stores still in flight when the next tile starts) to one that reaches past the last token or column
+    (operand requests clamped, stores cut off by the buffer bounds; with 2300 tokens the last piece of c_x is
+    part empty) and back, for every tile shape.  Every output of llmint8_linear (unguarded epilogue) against
+    the staged calls with the accumulator export (guarded epilogue), and samples of both against the oracle."""
     import torch
 
     import paper_2208_07339_amd as L
@@ -156,7 +156,7 @@ def test_accumulator_at_the_int32_bound(s, o):
     # closed form for all rows: Out = h * c_x * c_w with the signs, exactly representable products
     closed = want / 16129.0 * cx.astype(np.float64)[:, None] * cw.astype(np.float64)[None, :]
     assert_out_close(g["Out"], closed.astype(np.float16))
-    # and through the one-call path (no accumulator export: the LDS-fed epilogue where tiles are interior)
+    # and through the one-call path (no accumulator export: the LDS-fed epilogue where o % 8 == 0)
     import torch
     out = L.linear(g["Xd"], g["qw"], 6.0, g["outl"], g["rows"], g["ws"])
     torch.cuda.synchronize()

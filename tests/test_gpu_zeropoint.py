@@ -101,8 +101,9 @@ def test_zeropoint_on_one_sided_inputs(s, h, o, ncol, alpha):
 
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
 def test_every_prefill_tile_shape(cfg):
-    """Each workgroup tile of the prefill GEMM in its zeropoint form, on grids with interior tiles (records and
-    column factors staged through LDS, stores without guards) next to edge tiles: 7 and 20 outlier columns, a
+    """Each workgroup tile of the prefill GEMM in its zeropoint form (staged calls with the accumulator export:
+    guarded epilogue; one call: records and column factors staged through LDS, stores without guards), on grids
+    with full tiles next to ragged ones: 7 and 20 outlier columns, a
     16-slot outlier buffer, one-sided and shifted inputs (zeropoints far from 0: the correction terms of Eq. 5
     are large and cancel)."""
     import paper_2208_07339_amd as L
