@@ -123,6 +123,20 @@ def test_every_prefill_tile_shape(cfg):
         L.debug_prefill_tile(-1)
 
 
+def test_short_x_through_the_tiled_kernel():
+    """The zeropoint form of the tiled kernel on 32 tokens and fewer (the library itself keeps those on the
+    weight-streaming kernel; the test hook switches that kernel off): column factors from the short-X
+    pre-pass, a single ragged token tile."""
+    import paper_2208_07339_amd as L
+    L.debug_decode_shape(0)
+    try:
+        for s, h, o, ncol, seed in [(16, 512, 776, 5, 41), (1, 256, 264, 1, 42), (32, 1152, 520, 20, 43)]:
+            d = wl.make_custom(s, h, o, ncol, seed=seed)
+            zp_compare(one_sided(d, shift=0.5), d["W"], 6.0)
+    finally:
+        L.debug_decode_shape(-1)
+
+
 @pytest.mark.parametrize("s,h,o", [(16, 512, 256), (150, 384, 320)])
 def test_zeropoint_on_the_symmetric_recipe_and_a_shifted_one(s, h, o):
     d = wl.make_custom(s, h, o, 3, seed=77)
