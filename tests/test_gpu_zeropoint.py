@@ -124,9 +124,9 @@ def test_every_prefill_tile_shape(cfg):
 
 
 def test_short_x_through_the_tiled_kernel():
-    """The zeropoint form of the tiled kernel on 32 tokens and fewer (the library itself keeps those on the
-    weight-streaming kernel; the test hook switches that kernel off): column factors from the short-X
-    pre-pass, a single ragged token tile."""
+    """The zeropoint form of the tiled kernel on 32 tokens and fewer (the library sends them there only for
+    some shapes of W; the test hook switches the weight-streaming kernel off): column factors from the
+    short-X pre-pass, a single ragged token tile.  Then a W for which the library makes that choice itself."""
     import paper_2208_07339_amd as L
     L.debug_decode_shape(0)
     try:
@@ -135,6 +135,8 @@ def test_short_x_through_the_tiled_kernel():
             zp_compare(one_sided(d, shift=0.5), d["W"], 6.0)
     finally:
         L.debug_decode_shape(-1)
+    d = wl.make_custom(16, 128, 20480, 2, seed=44)  # 640 column tiles
+    zp_compare(one_sided(d), d["W"], 6.0)
 
 
 @pytest.mark.parametrize("s,h,o", [(16, 512, 256), (150, 384, 320)])
