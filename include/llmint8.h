@@ -39,9 +39,9 @@
  *     device (|O| > cap) set bit 0 of the device status word and clamp.
  *   - Speed, not results, depends on a few properties of the arguments: the
  *     fastest kernels of llmint8_matmul / llmint8_linear* need o % 8 == 0,
- *     16-byte aligned Out, c_x, c_w, X_o and W_f16, cap <= 32 (the choice is
- *     made before the number of outlier columns is known) and no accumulator
- *     export; anything else runs a guarded variant of the same kernels.
+ *     16-byte aligned Out, c_x, c_w, X_o and W_f16, at most 32 outlier
+ *     columns found (whatever cap is) and no accumulator export; anything
+ *     else runs a guarded variant of the same kernels.
  */
 #ifndef LLMINT8_H
 #define LLMINT8_H

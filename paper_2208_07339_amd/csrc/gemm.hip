@@ -50,6 +50,7 @@ struct GemmArgs {
     int32_t* Cdbg;               // NULL or [s x o]
     int s, h, o;
     int fast_ok;                 // o % 8 == 0, o < 2^21 and every epilogue operand 16-byte aligned
+    int many_only;               // guarded kernel launched behind the unguarded one: it runs only if *count > OSLOTS
     ZpArgs zp;                   // zeropoint constants (ZP kernels only)
 };
 
@@ -153,6 +154,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int s = g.s, o = g.o, KT = g.KT, opad = g.opad;
+    const int lpad = opad < OSLOTS ? opad : OSLOTS;  // slots per token in the LDS image of Xo (16 or 32)
     const int wp = w / WQ, wq = w % WQ;  // wave position: column half, token part
 
     // ---- this workgroup's tiles.  Hardware deals consecutive workgroup ids round-robin to the 8
@@ -245,11 +247,11 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
             return g.Wf + ((size_t)k * o + J0w + wchunk);
         }
         if (n < NEW + NEX) {
-            const int pn = (n - NEW) * 32 < NEX * opad ? (n - NEW) : 0;  // opad == 16: half as many pieces
-            const int e = pn * 512 + ln * 8;                              // element within the tile's rows of Xo
-            int i = I0w + (opad == 32 ? e >> 5 : e >> 4);
+            const int pn = (n - NEW) * 32 < NEX * lpad ? (n - NEW) : 0;  // 16 slots: half as many pieces
+            const int e = pn * 512 + ln * 8;                              // element of the image [32*TX tokens][lpad]
+            int i = I0w + (lpad == 32 ? e >> 5 : e >> 4);
             i = i < s ? i : s - 1;
-            return g.Xo + ((size_t)i * opad + (e & (opad - 1)));
+            return g.Xo + ((size_t)i * opad + (e & (lpad - 1)));
         }
         if constexpr (ZP) {
             const int m = n - (NEW + NEX + 1);
@@ -378,6 +380,14 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
     // direct-to-LDS loads in flight when myk is used later in the K pipeline
     __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
     FENCE();
+    // An outlier buffer of more than OSLOTS columns: the launcher cannot know how many columns were found, so
+    // it launches this kernel and its guarded instantiation behind it; the one whose case it is not leaves
+    // here (every wave alike, nothing of its in flight any more).
+    if constexpr (!GUARDED) {
+        if (cnt > OSLOTS) return;
+    } else {
+        if (g.many_only && cnt <= OSLOTS) return;
+    }
 
     // Memory operations of a wave complete in the order they were issued, and the requests of a tile's first two
     // stages are issued before the epilogue of the tile before it.  After an unguarded epilogue exactly NST
@@ -455,7 +465,7 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
 
         const int8_t* E = lds + eslot * STAGE;
         const unsigned short* EW = (const unsigned short*)E;                               // [32][256]
-        const int8_t* EX = E + NEW * TILE_BYTES;                                           // [64*WB][opad] fp16
+        const int8_t* EX = E + NEW * TILE_BYTES;                                           // [64*WB][lpad] fp16
         const unsigned short* ECw = (const unsigned short*)(E + (NEW + NEX) * TILE_BYTES); // [64*WA]
         const unsigned short* ECx = ECw + 256;                                             // [64*WB]
         const int4* EZx = (const int4*)(E + (NEW + NEX + 1) * TILE_BYTES);                 // zeropoint: [64*WB] records
@@ -526,9 +536,9 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
                     } else {
                         sx[b] = f16_bits_to_float(ECx[il]) * (1.0f / 16129.0f);
                     }
-                    xb[b][0] = *(const v8h*)(EX + il * (2 * opad) + gl * 16);
+                    xb[b][0] = *(const v8h*)(EX + il * (2 * lpad) + gl * 16);
                     xb[b][1] = (v8h)(0);
-                    if (cnt > 16) xb[b][1] = *(const v8h*)(EX + il * (2 * opad) + (2 + gl) * 16);  // then opad == 32
+                    if (cnt > 16) xb[b][1] = *(const v8h*)(EX + il * (2 * lpad) + (2 + gl) * 16);  // then lpad == 32
                 } else {
                     if constexpr (ZP) {
                         const int4 rec = (i < s) ? g.zp.zcx[i] : make_int4(0, 0, 0, 0);
@@ -769,11 +779,19 @@ static hipError_t launch_cfg(GemmArgs& g, hipStream_t st)
     const hipError_t e = prefill_device_setup(&ncu);
     if (e != hipSuccess) return e;
     const int total = g.nP * g.nQ;
-    // the unguarded epilogue: outputs and epilogue operands in 16-byte pieces, the outlier slots that fit LDS
-    if (g.fast_ok && !g.Cdbg && g.opad <= OSLOTS)
-        gemm_prefill_kernel<WA, WB, WQ, ZP, false><<<total < ncu ? total : ncu, 128 * WQ, shm, st>>>(g);
-    else
-        gemm_prefill_kernel<WA, WB, WQ, ZP, true><<<total < ncu ? total : ncu, 128 * WQ, shm, st>>>(g);
+    const int grid = total < ncu ? total : ncu;
+    // The unguarded epilogue takes outputs and epilogue operands in 16-byte pieces and up to OSLOTS outlier
+    // columns.  With a larger outlier buffer both instantiations are launched; each looks at the count and the
+    // one whose case it is not returns at once (about 3 us for the empty launch).
+    g.many_only = 0;
+    if (g.fast_ok && !g.Cdbg) {
+        gemm_prefill_kernel<WA, WB, WQ, ZP, false><<<grid, 128 * WQ, shm, st>>>(g);
+        if (g.opad <= OSLOTS) return hipGetLastError();
+        const hipError_t e1 = hipGetLastError();
+        if (e1 != hipSuccess) return e1;
+        g.many_only = 1;
+    }
+    gemm_prefill_kernel<WA, WB, WQ, ZP, true><<<grid, 128 * WQ, shm, st>>>(g);
     return hipGetLastError();
 }
 

@@ -90,6 +90,11 @@ def test_every_prefill_tile_shape_through_the_one_call_path(cfg, forced_tile):
     linear_compare(wl.make_custom(72, 256, 768, 5, seed=68))                # every token tile ragged
     linear_compare(wl.make_custom(200, 320, 384, 18, seed=69))
     linear_compare(wl.make_custom(325, 256, 640, 9, seed=70))               # s odd: the last piece of c_x is part empty
+    # an outlier buffer of more than 32 columns: the unguarded and the guarded kernel are both launched, the count
+    # decides on the device which of them runs
+    linear_compare(wl.make_custom(320, 384, 520, 5, seed=72), cap=64)       # 5 columns found: the unguarded one
+    linear_compare(wl.make_custom(300, 320, 776, 29, seed=73), cap=48)      # 29: two fp16 k-steps from a 48-slot row
+    linear_compare(wl.make_custom(320, 384, 520, 40, seed=74), cap=64)      # 40: the guarded one
 
 
 @pytest.mark.parametrize("s", [2300, 2296])

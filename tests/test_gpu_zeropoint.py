@@ -119,6 +119,10 @@ def test_every_prefill_tile_shape(cfg):
         zp_compare(one_sided(d, shift=-2.0), d["W"], INF)
         d = wl.make_custom(443, 384, 768, 12, seed=95)  # the last tile of tokens is ragged, s odd
         zp_compare(one_sided(d, shift=0.75), d["W"], 6.0)
+        d = wl.make_custom(320, 384, 520, 6, seed=96)   # 64-slot outlier buffer, 6 columns: the unguarded kernel
+        zp_compare(one_sided(d), d["W"], 6.0, cap=64)
+        d = wl.make_custom(320, 384, 520, 40, seed=97)  # ... 40 columns: the guarded one, launched behind it
+        zp_compare(one_sided(d), d["W"], 6.0, cap=64)
     finally:
         L.debug_prefill_tile(-1)
 
