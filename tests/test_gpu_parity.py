@@ -649,6 +649,47 @@ def test_random_shapes_through_the_one_call_path():
             raise AssertionError(f"case {case}: s={s} h={h} o={o} ncol={ncol} cap={cap} alpha={alpha}: {e}") from e
 
 
+def test_every_tile_shape_gives_the_same_bits(forced_tile):
+    """The accumulation is exact and every tile shape runs the same epilogue arithmetic per output, so the outputs
+    of llmint8_linear must not depend on the tile shape, on the guarded or unguarded epilogue (o % 8, outlier
+    buffer size), or on the number of columns found: seeded random shapes, every tile shape against the first,
+    bit for bit; short X also through the tiled kernel with the weight-streaming kernel switched off."""
+    import torch
+
+    import paper_2208_07339_amd as L
+    rng = np.random.default_rng(77)
+    try:
+        for case in range(10):
+            s = int(rng.choice([rng.integers(1, 33), rng.integers(33, 700)]))
+            h = int(8 * rng.integers(4, 200))
+            o = int(rng.choice([8 * rng.integers(8, 200), rng.integers(60, 1500)]))
+            ncol = int(rng.integers(0, 36))
+            cap = int(rng.choice([32, 16, 64]))
+            d = wl.make_custom(s, h, o, min(ncol, cap), seed=2000 + case)
+            g = run_hip(d["X"], d["W"], d["alpha"], cap=cap, want_c=False)
+            L.debug_decode_shape(0)
+            ref = None
+            for cfg in range(6):
+                forced_tile(cfg)
+                out = torch.zeros((s, o), dtype=torch.float16, device="cuda")
+                L.linear(g["Xd"], g["qw"], d["alpha"], g["outl"], g["rows"], g["ws"], out)
+                torch.cuda.synchronize()
+                if ref is None:
+                    ref = out
+                    assert_out_close(out.cpu().numpy(), oracle.linear(d["X"], d["W"], d["alpha"])["Out"])
+                else:
+                    assert torch.equal(out.view(torch.int16), ref.view(torch.int16)), \
+                        f"case {case}: s={s} h={h} o={o} ncol={ncol} cap={cap}: tile {cfg} differs from tile 0"
+                if cfg in (0, 3):  # the guarded epilogue (accumulator export) of two of the shapes as well
+                    out2, _ = L.matmul(g["rows"], g["outl"], g["qw"], g["ws"], want_c_i32=True)
+                    torch.cuda.synchronize()
+                    assert torch.equal(out2.view(torch.int16), ref.view(torch.int16)), \
+                        f"case {case}: s={s} h={h} o={o} ncol={ncol} cap={cap}: guarded epilogue of tile {cfg} differs"
+            L.debug_decode_shape(-1)
+    finally:
+        L.debug_decode_shape(-1)
+
+
 @pytest.mark.parametrize("s,h,o", [(16, 1024, 768), (200, 640, 384)])  # weight-streaming path, tiled path
 def test_linear_replayed_from_a_captured_graph(s, h, o):
     """The one-call entry point allocates nothing and enqueues kernels only, so a caller may capture it
