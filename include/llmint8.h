@@ -128,7 +128,9 @@ int llmint8_dequantize_rows(const int8_t *Wq, const void *cw_f16, int h, int o, 
 /* Eq. 7 + Eq. 8: C_i32 = X_i8 W_i8 (int32 accumulation),
  * Out = fp16( C_i32 * c_x (x) c_w / 127^2 + Xo W_f16[O,:] ), the outlier product
  * accumulated in fp32.  Token counts s <= 32 (up to 48 against a wide W) take a weight-streaming
- * kernel unless the shape of W suits the tiled kernel better; the results do not depend on the choice.
+ * kernel unless the shape of W suits the tiled kernel better.  The two kernels add the outlier product
+ * up in fp32 in different orders: an output may differ in its last fp16 bit between them (not
+ * between the tile shapes or work splits of one kernel).
  *   W_f16       in   the original weights; only rows O are read.  NULL: the rows rebuilt from
  *                    the codes (llmint8_dequantize_rows, done here into ws) take their place
  *   cx_f16      in   [s] fp16.  If the array starts on a 16-byte boundary it is read in aligned
@@ -254,7 +256,8 @@ int llmint8_debug_prefill_tile_for(int s, int h, int o);
  * load batch): 1 = 1 x 8, 2 = 2 x 4, 3 = 2 x 8, 4 = 3 x 4, 5 = 1 x 4; 0 = no weight-streaming kernel at all
  * (every token count through the tiled kernel); -1 = not forced (1 x 8; 2 x 4 above 16 tokens when W has
  * enough column tiles to fill the chip that way; the tiled kernel where the shape of W suits it better).
- * Anything else is LLMINT8_INVALID_ARG.  Process-wide; results do not depend on it.   */
+ * Anything else is LLMINT8_INVALID_ARG.  Process-wide; results do not depend on the work split (0 moves
+ * short X to the other kernel: see llmint8_matmul).                                */
 #define LLMINT8_DECODE_SHAPES 5
 int llmint8_debug_decode_shape(int cfg);
 
