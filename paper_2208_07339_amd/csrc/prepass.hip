@@ -141,13 +141,13 @@ __global__ void __launch_bounds__(256) colmax_rowmax_kernel(const unsigned short
         us8 v[4];
         unsigned short x[4];
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
-            v[u] = (us8)(0);
-            if (in && r + 4 * u < r1) v[u] = *(const us8*)(p + (size_t)(r + 4 * u) * cols);
+        for (int u = 0; u < 4; u++) {  // unconditional loads, so that all four are in flight together: a row past
+            const int rr = r + 4 * u < r1 ? r + 4 * u : r1 - 1;  // the slab repeats its last one (the maxima do
+            v[u] = *(const us8*)(p + (size_t)rr * cols);         // not change, its row maximum is not stored)
         }
 #pragma unroll
         for (int u = 0; u < 4; u++) {
-            v[u] &= (unsigned short)0x7fff;
+            v[u] = in ? v[u] & (unsigned short)0x7fff : (us8)(0);  // lanes past the last column read column 0
             m = __builtin_elementwise_max(m, v[u]);
             const us8 below = v[u] & __builtin_convertvector(v[u] < thrv, us8);  // lanes that reach the threshold drop out
             x[u] = hmax8(below);
@@ -394,20 +394,33 @@ __global__ void __launch_bounds__(256) scan_small_kernel(const unsigned short* _
     const int c0 = blockIdx.x * 512 + lane * 8;
     us8 v[8];
     us8 m = (us8)(0);
+    if (vec_ok) {
+        // unconditional loads (a row or column that does not exist: row 0 / column 0 again, zeroed afterwards), so
+        // that all eight are in flight together: each under its own bounds check was waited for before the next
+        // was issued, eight round trips to memory in a row
 #pragma unroll
-    for (int r = 0; r < 8; r++) {
-        const int i = w + 4 * r;
-        v[r] = (us8)(0);
-        if (i < s && c0 < h) {
-            const unsigned short* p = X + (size_t)i * h + c0;
-            if (vec_ok) {
-                v[r] = *(const us8*)p;
-            } else {
+        for (int r = 0; r < 8; r++) {
+            const int i = w + 4 * r;
+            v[r] = *(const us8*)(X + (size_t)(i < s ? i : 0) * h + (c0 < h ? c0 : 0));
+        }
+#pragma unroll
+        for (int r = 0; r < 8; r++)
+            if (!(w + 4 * r < s && c0 < h)) v[r] = (us8)(0);
+    } else {
+#pragma unroll
+        for (int r = 0; r < 8; r++) {
+            const int i = w + 4 * r;
+            v[r] = (us8)(0);
+            if (i < s && c0 < h) {
+                const unsigned short* p = X + (size_t)i * h + c0;
 #pragma unroll
                 for (int e = 0; e < 8; e++)
                     if (c0 + e < h) v[r][e] = p[e];
             }
         }
+    }
+#pragma unroll
+    for (int r = 0; r < 8; r++) {
         if (!ZP) v[r] &= (unsigned short)0x7fff;
         m = __builtin_elementwise_max(m, v[r] & (unsigned short)0x7fff);
     }
@@ -586,15 +599,21 @@ __global__ void __launch_bounds__(256) quantize_small_kernel(const unsigned shor
     const int kseg = (tid & 31) * 8;
     const int k = k0 + kseg;
     us8 xv[4];
+    if (vec_ok && k + 8 <= h) {
+        // unconditional (a row that does not exist: row 0 again; its codes come out as 0 because its constant
+        // is 0), or the compiler waits for each load before it issues the next
 #pragma unroll
-    for (int q = 0; q < 4; q++) {
-        const int r = q * 8 + (tid >> 5);
-        xv[q] = (us8)(0);
-        if (r < s) {
-            const unsigned short* row = X + (size_t)r * h;
-            if (vec_ok && k + 8 <= h) {
-                xv[q] = *(const us8*)(row + k);
-            } else {
+        for (int q = 0; q < 4; q++) {
+            const int r = q * 8 + (tid >> 5);
+            xv[q] = *(const us8*)(X + (size_t)(r < s ? r : 0) * h + k);
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const int r = q * 8 + (tid >> 5);
+            xv[q] = (us8)(0);
+            if (r < s) {
+                const unsigned short* row = X + (size_t)r * h;
 #pragma unroll
                 for (int e = 0; e < 8; e++)
                     if (k + e < h) xv[q][e] = row[k + e];
@@ -1069,12 +1088,16 @@ __global__ void __launch_bounds__(256) row_const_kernel(const unsigned short* __
     if (s_slow) {  // uniform: the bitmap of all outlier columns, then the whole workgroup scans each such row again
         for (int q = tid; q < nw; q += 256) fullmap[q] = 0;
         __syncthreads();
-        for (int b = tid; b < nl; b += 256) {
-            const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
-            const int base = s_base[b];
-            for (int e = 0; e < n && base + e < cap; e++) {
-                const int j = L.cand[(size_t)b * capc + e];
-                atomicOr(&fullmap[j >> 5], 1u << (j & 31));
+        if (cnt <= RC_SLOTS) {  // the list is in LDS already
+            for (int t2 = tid; t2 < cnt; t2 += 256) atomicOr(&fullmap[s_idx[t2] >> 5], 1u << (s_idx[t2] & 31));
+        } else {
+            for (int b = tid; b < nl; b += 256) {
+                const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+                const int base = s_base[b];
+                for (int e = 0; e < n && base + e < cap; e++) {
+                    const int j = L.cand[(size_t)b * capc + e];
+                    atomicOr(&fullmap[j >> 5], 1u << (j & 31));
+                }
             }
         }
         __syncthreads();
@@ -1083,16 +1106,20 @@ __global__ void __launch_bounds__(256) row_const_kernel(const unsigned short* __
             const int i2 = blockIdx.x * 4 + r4;
             const unsigned short* row2 = X + (size_t)i2 * h;
             unsigned m = 0;
-            for (int c0 = tid * 8; c0 < h; c0 += 4 * 2048) {  // h is a multiple of 8 here; four 16-byte loads in flight
-                us8 v[4];
+            // h is a multiple of 8 here.  One slow row makes this workgroup the kernel's last, and every pass of
+            // this loop is a round trip to memory of its own: twelve 16-byte loads in flight per lane take a row
+            // of 49 152 features in two passes (24 in one pass are no faster and cost 65 more registers).  (With each load under its own bounds check the compiler waited
+            // for every one of them in turn: 16 us for the kernel instead of 5 whenever one row came here.)
+            constexpr int RU = 12;
+            for (int c0 = tid * 8; c0 < h; c0 += RU * 2048) {
+                us8 v[RU];
 #pragma unroll
-                for (int u = 0; u < 4; u++) {
-                    const int c = c0 + u * 2048;
-                    v[u] = (us8)(0);
-                    if (c < h) v[u] = *(const us8*)(row2 + c) & (unsigned short)0x7fff;
+                for (int u = 0; u < RU; u++) {  // unconditional loads (past the row: its start again, unused below),
+                    const int c = c0 + u * 2048;  // so that the compiler issues them together
+                    v[u] = *(const us8*)(row2 + (c < h ? c : 0)) & (unsigned short)0x7fff;
                 }
 #pragma unroll
-                for (int u = 0; u < 4; u++) {
+                for (int u = 0; u < RU; u++) {
                     const int c = c0 + u * 2048;
                     if (c < h) {
                         const unsigned bits = (fullmap[c >> 5] >> (c & 31)) & 0xffu;
@@ -1181,22 +1208,32 @@ __global__ void __launch_bounds__(256) quantize_rows_kernel(const unsigned short
     const int kseg = (tid & 31) * 8;
     const int k = k0 + kseg;
     const unsigned bits = (bitmap[kseg >> 5] >> (kseg & 31)) & 0xffu;
+    // The loads of the thread's four rows first, all of them unconditional (a row past the last one: the last
+    // one again, its constant taken as 0 below), so that they are in flight together: under a bounds check of
+    // its own each was waited for before the next was issued, four round trips to memory in a row.
+    us8 vq[4];
+    float cq[4];
+    const bool vec = vec_ok && k + 8 <= h;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int i = rt * 32 + q * 8 + (tid >> 5);
+        const int ii = i < s ? i : s - 1;
+        cq[q] = f16_bits_to_float(cx[ii]);
+        if (i >= s) cq[q] = 0.0f;
+        vq[q] = (us8)(0);
+        if (vec) vq[q] = *(const us8*)(X + (size_t)ii * h + k);
+    }
 #pragma unroll
     for (int q = 0; q < 4; q++) {
         const int r = q * 8 + (tid >> 5);
         const int i = rt * 32 + r;
-        us8 v = (us8)(0);
-        float c = 0.0f;
-        if (i < s) {
-            c = f16_bits_to_float(cx[i]);
+        us8 v = vq[q];
+        const float c = cq[q];
+        if (!vec && i < s) {
             const unsigned short* row = X + (size_t)i * h;
-            if (vec_ok && k + 8 <= h) {
-                v = *(const us8*)(row + k);
-            } else {
 #pragma unroll
-                for (int e = 0; e < 8; e++)
-                    if (k + e < h) v[e] = row[k + e];
-            }
+            for (int e = 0; e < 8; e++)
+                if (k + e < h) v[e] = row[k + e];
         }
         const float rc = c > 0.0f ? 1.0f / c : 0.0f;
         unsigned lo = 0, hi = 0;

@@ -246,21 +246,31 @@ __global__ void __launch_bounds__(256) zp_quantize_rows_kernel(const unsigned sh
     const int kseg = (tid & 31) * 8;
     const int k = k0 + kseg;
     const unsigned bits = (bitmap[kseg >> 5] >> (kseg & 31)) & 0xffu;
+    // the loads of the thread's four rows first and unconditional (a row past the last one: the last one again,
+    // its range taken as 0 below), so that they are in flight together, as in quantize_rows_kernel
+    us8 vq[4];
+    int4 recq[4];
+    const bool vec = vec_ok && k + 8 <= h;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int i = rt * 32 + q * 8 + (tid >> 5);
+        const int ii = i < s ? i : s - 1;
+        recq[q] = zc[ii];
+        vq[q] = (us8)(0);
+        if (vec) vq[q] = *(const us8*)(X + (size_t)ii * h + k);
+    }
 #pragma unroll
     for (int q = 0; q < 4; q++) {
         const int r = q * 8 + (tid >> 5);
         const int i = rt * 32 + r;
         double D = 0.0;
         int z = 0;
-        us8 v = (us8)(0);
+        us8 v = vq[q];
         if (i < s) {
-            const int4 rec = zc[i];
-            D = zp_range((unsigned)rec.x);
-            z = rec.y;
-            const unsigned short* row = X + (size_t)i * h;
-            if (vec_ok && k + 8 <= h) {
-                v = *(const us8*)(row + k);
-            } else {
+            D = zp_range((unsigned)recq[q].x);
+            z = recq[q].y;
+            if (!vec) {
+                const unsigned short* row = X + (size_t)i * h;
 #pragma unroll
                 for (int e = 0; e < 8; e++)
                     if (k + e < h) v[e] = row[k + e];
