@@ -47,6 +47,11 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     const int jt0 = blockIdx.x * NJ;
 
     // ---- epilogue operands, requested first.  Thread -> column jj of a tile, tokens ig, ig+8, ig+16, ig+24.
+    // Every load here is unconditional (an index that does not exist is replaced by one that does; the value is
+    // never used, because the epilogue skips tokens >= s, columns >= o and slots >= count), and nothing is done
+    // with a loaded value before the first batch of the weight stream has been requested: a load under a bounds
+    // check of its own is compiled as branch, load, wait, and the operands would arrive one round trip after the
+    // other (sixteen of them for the rows of Wf alone) before the stream could start.
     int cnt = *count;
     cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
     const int jj = tid & 31, ig = tid >> 5;
@@ -56,6 +61,12 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     uint4 xo[4][DSLOTS / 8];      // slots 0..15 of this thread's tokens (Xo holds zeros past |O|)
     double zp_[ZP ? NJ : 1], zq_[ZP ? NJ : 1], zr_[ZP ? NJ : 1];  // column factors p, q, r of zp_kcol_kernel
     double zsa[ZP ? 4 : 1], zza[ZP ? 4 : 1], zrs[ZP ? 4 : 1];     // D_x / 254, zp_x, row sums of the codes
+    // the rows of Wf that the outlier slots need: lanes 0 .. DSLOTS-1 fetch idx[lane] in one load (entries
+    // past the count hold whatever the caller left there and are not used)
+    unsigned kraw = (unsigned)lane;
+    if (!rows_are_slots) kraw = (unsigned)idx[(lane < DSLOTS && lane < cap) ? lane : 0];
+    unsigned short cw_raw[NJ], cx_raw[4];
+    int4 zx_raw[ZP ? 4 : 1];
 #pragma unroll
     for (int n = 0; n < NJ; n++) {
         const int j = (jt0 + n) * 32 + jj;
@@ -64,47 +75,44 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
             zq_[n] = zp.colc[(size_t)zp.pitch + j];
             zr_[n] = zp.colc[2 * (size_t)zp.pitch + j];
         } else {
-            cwj[n] = (j < o) ? f16_bits_to_float(cw[j]) : 0.0f;
+            cw_raw[n] = cw[j < o ? j : 0];
         }
     }
     // the per-token operands of token tile ti: this thread's tokens 32 ti + ig + 8 m
-    auto token_operands = [&](int ti) {
+    auto token_loads = [&](int ti) {
 #pragma unroll
         for (int m = 0; m < 4; m++) {
             const int i = 32 * ti + ig + 8 * m;
-            if constexpr (ZP) {
-                const int4 r = (i < s) ? zp.zcx[i] : make_int4(0, 0, 0, 0);
-                zsa[m] = zp_range((unsigned)r.x) * (1.0 / 254.0);
-                zza[m] = (double)r.y;
-                zrs[m] = (double)r.z;
-            } else {
-                sxi[m] = (i < s) ? f16_bits_to_float(cx[i]) * (1.0f / 16129.0f) : 0.0f;
-            }
+            const int ii = i < s ? i : s - 1;
+            if constexpr (ZP) zx_raw[m] = zp.zcx[ii]; else cx_raw[m] = cx[ii];
+#pragma unroll
+            for (int q = 0; q < DSLOTS / 8; q++) xo[m][q] = *(const uint4*)(Xo + (size_t)ii * opad + 8 * q);
         }
+    };
+    auto token_values = [&]() {
 #pragma unroll
         for (int m = 0; m < 4; m++) {
-            const int i = 32 * ti + ig + 8 * m;
-#pragma unroll
-            for (int q = 0; q < DSLOTS / 8; q++) {
-                xo[m][q] = make_uint4(0, 0, 0, 0);
-                if (cnt > 0 && i < s) xo[m][q] = *(const uint4*)(Xo + (size_t)i * opad + 8 * q);
+            if constexpr (ZP) {
+                zsa[m] = zp_range((unsigned)zx_raw[m].x) * (1.0 / 254.0);
+                zza[m] = (double)zx_raw[m].y;
+                zrs[m] = (double)zx_raw[m].z;
+            } else {
+                sxi[m] = f16_bits_to_float(cx_raw[m]) * (1.0f / 16129.0f);
             }
         }
     };
-    if constexpr (EARLY) token_operands(0);
+    if constexpr (EARLY) token_loads(0);
+    unsigned okmask = 0;  // slots whose row of Wf exists (uniform)
+    unsigned short wo_raw[NJ][DSLOTS];
 #pragma unroll
     for (int t = 0; t < DSLOTS; t++) {
-        unsigned k = 0;
-        bool ok = t < cnt;
-        if (ok) {
-            k = rows_are_slots ? (unsigned)t : (unsigned)idx[t];  // uniform: a scalar load
-            ok = k < (unsigned)wrows;
-        }
+        const unsigned k = (unsigned)__builtin_amdgcn_readlane((int)kraw, t);
+        const bool ok = k < (unsigned)wrows;
+        okmask |= ok ? 1u << t : 0u;
 #pragma unroll
         for (int n = 0; n < NJ; n++) {
             const int j = (jt0 + n) * 32 + jj;
-            const unsigned v = (ok && j < o) ? (unsigned)Wf[(size_t)k * o + j] : 0u;
-            if (t & 1) wo[n][t >> 1] |= v << 16; else wo[n][t >> 1] = v;
+            wo_raw[n][t] = Wf[(size_t)(ok ? k : 0u) * o + (j < o ? j : 0)];
         }
     }
     FENCE();
@@ -160,6 +168,15 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     const int nb = kq / U;  // full batches
     if (nb > 0) load(B0{}, 0);
     FENCE();
+    // the epilogue operands into the form the epilogue wants (their loads are older than the batch just requested)
+#pragma unroll
+    for (int n = 0; n < NJ; n++) {
+        if constexpr (!ZP) cwj[n] = f16_bits_to_float(cw_raw[n]);
+#pragma unroll
+        for (int t = 0; t < DSLOTS; t += 2) wo[n][t >> 1] = (unsigned)wo_raw[n][t] | ((unsigned)wo_raw[n][t + 1] << 16);
+    }
+    if constexpr (EARLY) token_values();
+    FENCE();
     int b = 0;
     for (; b + 2 <= nb; b += 2) {
         load(B1{}, (b + 1) * U);
@@ -196,7 +213,10 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     for (int n = 0; n < NJ; n++)
 #pragma unroll
         for (int q = 0; q < 16; q++) red[w][n][q][lane] = acc[n][ti][q];
-    if constexpr (!EARLY) token_operands(ti);
+    if constexpr (!EARLY) {
+        token_loads(ti);
+        token_values();
+    }
     __syncthreads();
 #pragma unroll
     for (int n = 0; n < NJ; n++) {
@@ -219,7 +239,7 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
             }
 #pragma unroll
             for (int t = 0; t < DSLOTS; t++)
-                if (t < cnt) {
+                if (t < cnt && ((okmask >> t) & 1u)) {
                     const unsigned xw = ((const unsigned*)&xo[m][t >> 3])[(t & 7) >> 1];
                     const unsigned short xh = (unsigned short)((t & 1) ? (xw >> 16) : (xw & 0xffff));
                     const unsigned short wh = (unsigned short)((t & 1) ? (wo[n][t >> 1] >> 16) : (wo[n][t >> 1] & 0xffff));
