@@ -980,13 +980,25 @@ __global__ void __launch_bounds__(256) row_absmax_kernel(const unsigned short* _
     __syncthreads();
     unsigned m = 0;
     if (vec_ok) {
-        for (int c0 = tid * 8; c0 < h; c0 += 2048) {
-            us8 v = *(const us8*)(row + c0) & (unsigned short)0x7fff;
-            unsigned bits = (bitmap[c0 >> 5] >> (c0 & 31)) & 0xffu;
+        // four unconditional loads in flight per pass (past the row: its start again, skipped below)
+        for (int c0 = tid * 8; c0 < h; c0 += 4 * 2048) {
+            us8 v[4];
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                unsigned x = ((bits >> e) & 1u) ? 0u : (unsigned)v[e];
-                m = x > m ? x : m;
+            for (int u = 0; u < 4; u++) {
+                const int c = c0 + u * 2048;
+                v[u] = *(const us8*)(row + (c < h ? c : 0)) & (unsigned short)0x7fff;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int c = c0 + u * 2048;
+                if (c < h) {
+                    const unsigned bits = (bitmap[c >> 5] >> (c & 31)) & 0xffu;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) {
+                        const unsigned x = ((bits >> e) & 1u) ? 0u : (unsigned)v[u][e];
+                        m = x > m ? x : m;
+                    }
+                }
             }
         }
     } else {

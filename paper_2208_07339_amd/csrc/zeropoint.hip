@@ -179,16 +179,28 @@ __global__ void __launch_bounds__(256) zp_row_range_kernel(const unsigned short*
     __syncthreads();
     unsigned kmin = 0xffffu, kmax = 0u;
     if (vec_ok) {
-        for (int c0 = tid * 8; c0 < h; c0 += 2048) {
-            const us8 v = *(const us8*)(row + c0);
-            const unsigned bits = (bitmap[c0 >> 5] >> (c0 & 31)) & 0xffu;
+        // four unconditional loads in flight per pass (past the row: its start again, skipped below)
+        for (int c0 = tid * 8; c0 < h; c0 += 4 * 2048) {
+            us8 v[4];
 #pragma unroll
-            for (int e = 0; e < 8; e++)
-                if (!((bits >> e) & 1u)) {
-                    const unsigned k = f16_key(v[e]);
-                    kmin = k < kmin ? k : kmin;
-                    kmax = k > kmax ? k : kmax;
+            for (int u = 0; u < 4; u++) {
+                const int c = c0 + u * 2048;
+                v[u] = *(const us8*)(row + (c < h ? c : 0));
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int c = c0 + u * 2048;
+                if (c < h) {
+                    const unsigned bits = (bitmap[c >> 5] >> (c & 31)) & 0xffu;
+#pragma unroll
+                    for (int e = 0; e < 8; e++)
+                        if (!((bits >> e) & 1u)) {
+                            const unsigned k = f16_key(v[u][e]);
+                            kmin = k < kmin ? k : kmin;
+                            kmax = k > kmax ? k : kmax;
+                        }
                 }
+            }
         }
     } else {
         for (int c = tid; c < h; c += 256)
