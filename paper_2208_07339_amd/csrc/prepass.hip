@@ -872,10 +872,22 @@ __global__ void __launch_bounds__(256) quantize_weight_kernel(const unsigned sho
     const int jt0 = blockIdx.x * 8;
     const int cg = tid & 31, sub = tid >> 5;
     const int j0 = jt0 * 32 + cg * 8;
+    // The vector path requests its column constants and the four rows of W without conditions (a row past h: the
+    // last one again, zeroed below), so that the loads are in flight together instead of one after the other.
+    const bool vec = vec_ok && j0 + 8 <= o;
+    us8 cv = (us8)(0), wv[4];
+    if (vec) {
+        cv = *(const us8*)(cw + j0);
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const int k = kt * 32 + q * 8 + sub;
+            wv[q] = *(const us8*)(W + (size_t)(k < h ? k : h - 1) * o + j0);
+        }
+    }
     float c[8], rc[8];
 #pragma unroll
     for (int e = 0; e < 8; e++) {
-        c[e] = (j0 + e < o) ? f16_bits_to_float(cw[j0 + e]) : 0.0f;
+        c[e] = vec ? f16_bits_to_float(cv[e]) : (j0 + e < o) ? f16_bits_to_float(cw[j0 + e]) : 0.0f;
         rc[e] = c[e] > 0.0f ? 1.0f / c[e] : 0.0f;
     }
 #pragma unroll
@@ -884,8 +896,8 @@ __global__ void __launch_bounds__(256) quantize_weight_kernel(const unsigned sho
         const int k = kt * 32 + kk;
         us8 v = (us8)(0);
         if (k < h) {
-            if (vec_ok && j0 + 8 <= o) {
-                v = *(const us8*)(W + (size_t)k * o + j0);
+            if (vec) {
+                v = wv[q];
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; e++)
@@ -913,7 +925,7 @@ hipError_t launch_quantize_weight(const void* W, int h, int o, const unsigned sh
                                   hipStream_t st)
 {
     const int KT = k_tiles(h), JT = row_tiles(o);
-    int vec_ok = (o % 8 == 0) && aligned16(W);
+    int vec_ok = (o % 8 == 0) && aligned16(W) && aligned16(cw);
     dim3 grid((JT + 7) / 8, KT);
     quantize_weight_kernel<<<grid, 256, 0, st>>>((const unsigned short*)W, h, o, cw, Wq, KT, JT, vec_ok);
     return hipGetLastError();
