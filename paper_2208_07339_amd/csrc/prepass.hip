@@ -137,14 +137,24 @@ __global__ void __launch_bounds__(256) colmax_rowmax_kernel(const unsigned short
     const unsigned short* p = M + (size_t)(in ? c0 : 0);
     const us8 thrv = (us8)((unsigned short)thr);
     us8 m = (us8)(0);
+    // Unconditional loads, so that all four of a pass are in flight together (a row past the slab repeats its last
+    // one: the maxima do not change, its row maximum is not stored), and the next pass's four are requested before
+    // this pass's reductions.
+    us8 nv[4];
+    auto request = [&](int r) {
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int rr = r + 4 * u < r1 ? r + 4 * u : r1 - 1;
+            nv[u] = *(const us8*)(p + (size_t)rr * cols);
+        }
+    };
+    if (r0 + w < r1) request(r0 + w);
     for (int r = r0 + w; r < r1; r += 16) {
         us8 v[4];
         unsigned short x[4];
 #pragma unroll
-        for (int u = 0; u < 4; u++) {  // unconditional loads, so that all four are in flight together: a row past
-            const int rr = r + 4 * u < r1 ? r + 4 * u : r1 - 1;  // the slab repeats its last one (the maxima do
-            v[u] = *(const us8*)(p + (size_t)rr * cols);         // not change, its row maximum is not stored)
-        }
+        for (int u = 0; u < 4; u++) v[u] = nv[u];
+        request(r + 16);
 #pragma unroll
         for (int u = 0; u < 4; u++) {
             v[u] = in ? v[u] & (unsigned short)0x7fff : (us8)(0);  // lanes past the last column read column 0
