@@ -102,19 +102,6 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
         }
     };
     if constexpr (EARLY) token_loads(0);
-    unsigned okmask = 0;  // slots whose row of Wf exists (uniform)
-    unsigned short wo_raw[NJ][DSLOTS];
-#pragma unroll
-    for (int t = 0; t < DSLOTS; t++) {
-        const unsigned k = (unsigned)__builtin_amdgcn_readlane((int)kraw, t);
-        const bool ok = k < (unsigned)wrows;
-        okmask |= ok ? 1u << t : 0u;
-#pragma unroll
-        for (int n = 0; n < NJ; n++) {
-            const int j = (jt0 + n) * 32 + jj;
-            wo_raw[n][t] = Wf[(size_t)(ok ? k : 0u) * o + (j < o ? j : 0)];
-        }
-    }
     FENCE();
 
     // ---- weight stream
@@ -168,14 +155,20 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
     const int nb = kq / U;  // full batches
     if (nb > 0) load(B0{}, 0);
     FENCE();
-    // the epilogue operands into the form the epilogue wants (their loads are older than the batch just requested)
+    // the rows of Wf, behind the first weight batch: they wait for the column indices, the batch does not
+    unsigned okmask = 0;  // slots whose row of Wf exists (uniform)
+    unsigned short wo_raw[NJ][DSLOTS];
 #pragma unroll
-    for (int n = 0; n < NJ; n++) {
-        if constexpr (!ZP) cwj[n] = f16_bits_to_float(cw_raw[n]);
+    for (int t = 0; t < DSLOTS; t++) {
+        const unsigned k = (unsigned)__builtin_amdgcn_readlane((int)kraw, t);
+        const bool ok = k < (unsigned)wrows;
+        okmask |= ok ? 1u << t : 0u;
 #pragma unroll
-        for (int t = 0; t < DSLOTS; t += 2) wo[n][t >> 1] = (unsigned)wo_raw[n][t] | ((unsigned)wo_raw[n][t + 1] << 16);
+        for (int n = 0; n < NJ; n++) {
+            const int j = (jt0 + n) * 32 + jj;
+            wo_raw[n][t] = Wf[(size_t)(ok ? k : 0u) * o + (j < o ? j : 0)];
+        }
     }
-    if constexpr (EARLY) token_values();
     FENCE();
     int b = 0;
     for (; b + 2 <= nb; b += 2) {
@@ -202,6 +195,16 @@ gemm_decode_kernel(const int8_t* __restrict__ Wq, const int8_t* __restrict__ Xq,
         }
     }
 
+    // ---- the epilogue operands into the form the epilogue wants (not earlier: their loads complete in the order
+    // of issue, and a use in front of the stream would wait for everything requested before them)
+#pragma unroll
+    for (int n = 0; n < NJ; n++) {
+        if constexpr (!ZP) cwj[n] = f16_bits_to_float(cw_raw[n]);
+#pragma unroll
+        for (int t = 0; t < DSLOTS; t += 2) wo[n][t >> 1] = (unsigned)wo_raw[n][t] | ((unsigned)wo_raw[n][t + 1] << 16);
+    }
+    if constexpr (EARLY) token_values();
+    FENCE();
     // ---- reduction over the four waves and epilogue, token tile by token tile.  Accumulator element (token
     // i of the tile, column jj) lives in register r = 4*(jj/8) + jj%4 of lane l = i + 32*((jj/4)%2).
     const int r = 4 * (jj >> 3) + (jj & 3);
