@@ -353,12 +353,24 @@ __global__ void __launch_bounds__(256) zp_kcol_kernel(const int8_t* __restrict__
         const int4 rec = zcw[j];
         long long sum = rec.z;
         int used = 0;
-        for (int t = 0; t < cnt; t++) {
-            const unsigned k = (unsigned)idx[t];
-            if (k < (unsigned)h) {
-                sum -= Wq[((size_t)(j >> 5) * KT + (k >> 5)) * TILE_BYTES + tile_byte(j & 31, (int)(k & 31))];
-                used++;
+        // eight codes per pass, requested without conditions so that they are in flight together (a slot past the
+        // count or with an index that does not exist reads row 0 and is skipped)
+        for (int t0 = 0; t0 < cnt; t0 += 8) {
+            int8_t q[8];
+            bool ok[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) {
+                const unsigned k = (unsigned)idx[t0 + u < cnt ? t0 + u : 0];
+                ok[u] = t0 + u < cnt && k < (unsigned)h;
+                const unsigned kk = ok[u] ? k : 0u;
+                q[u] = Wq[((size_t)(j >> 5) * KT + (kk >> 5)) * TILE_BYTES + tile_byte(j & 31, (int)(kk & 31))];
             }
+#pragma unroll
+            for (int u = 0; u < 8; u++)
+                if (ok[u]) {
+                    sum -= q[u];
+                    used++;
+                }
         }
         p = zp_range((unsigned)rec.x) * (1.0 / 254.0);
         q = (double)rec.y * p;
