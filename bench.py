@@ -35,8 +35,8 @@ COPY_PROBE_BYTES = 256 << 20   # size of the calibration copies of --copy-probe
 TRAFFIC_SOURCE = "profiles/bench_default_ffn13b_decode_hbm_traffic.txt"
 MEASURED_TRAFFIC = {
     # FETCH_SIZE / 0.5001 + WRITE_SIZE / 1.0 (KiB -> bytes; factors from the copy probe of the same runs)
-    "ffn13b": 633.80e6 + 167.84e6,   # gemm_prefill_kernel<4,2,4,false,false>: operand panels re-fetched per XCD and round + Out
-    "decode": 607.20e6 + 1.57e6,     # gemm_decode_kernel<1,1,8>
+    "ffn13b": 633.80e6 + 167.81e6,   # gemm_prefill_kernel<4,2,4,false,false>: operand panels re-fetched per XCD and round + Out
+    "decode": 607.39e6 + 1.57e6,     # gemm_decode_kernel<1,1,8>
 }
 
 
