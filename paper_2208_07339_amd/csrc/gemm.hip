@@ -476,24 +476,32 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
         int8_t* stg = lds + NB * STAGE + w * (BU * 4096);
 
         // rows O of the fp16 weights for column jcol, outlier slots t0 + 8*gl .. +7, straight from memory
+        // (both without conditions on the loads themselves, so that the eight indices, then the eight weights, are
+        // in flight together: a slot, column or token that does not exist reads one that does and is zeroed)
         auto load_w_mem = [&](int jcol, int t0) {
-            v8h wa;
+            unsigned k[8];
 #pragma unroll
             for (int e = 0; e < 8; e++) {
                 const int t = t0 + 8 * gl + e;
-                unsigned short v = 0;
-                if (t < cnt && jcol < o) {
-                    const unsigned k = g.rows_are_slots ? (unsigned)t : (unsigned)g.idx[t];
-                    if (k < (unsigned)g.wrows) v = g.Wf[(size_t)k * o + jcol];
-                }
-                wa[e] = __builtin_bit_cast(_Float16, v);
+                k[e] = g.rows_are_slots ? (unsigned)t : (unsigned)g.idx[t < cnt ? t : 0];
+            }
+            unsigned short v[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const bool ok = t0 + 8 * gl + e < cnt && k[e] < (unsigned)g.wrows;
+                v[e] = g.Wf[(size_t)(ok ? k[e] : 0u) * o + (jcol < o ? jcol : 0)];
+            }
+            v8h wa;
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const bool ok = t0 + 8 * gl + e < cnt && k[e] < (unsigned)g.wrows && jcol < o;
+                wa[e] = __builtin_bit_cast(_Float16, ok ? v[e] : (unsigned short)0);
             }
             return wa;
         };
         auto load_x_mem = [&](int i, int t0) {
-            v8h xb = (v8h)(0);
-            if (i < s) xb = *(const v8h*)(g.Xo + (size_t)i * opad + t0 + 8 * gl);
-            return xb;
+            const v8h xb = *(const v8h*)(g.Xo + (size_t)(i < s ? i : s - 1) * opad + t0 + 8 * gl);
+            return i < s ? xb : (v8h)(0);
         };
 
         // FAST: operands from the LDS image of the epilogue stages, no guards.  Its stores go
@@ -541,12 +549,14 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
                     if (cnt > 16) xb[b][1] = *(const v8h*)(EX + il * (2 * lpad) + (2 + gl) * 16);  // then lpad == 32
                 } else {
                     if constexpr (ZP) {
-                        const int4 rec = (i < s) ? g.zp.zcx[i] : make_int4(0, 0, 0, 0);
+                        int4 rec = g.zp.zcx[i < s ? i : s - 1];
+                        if (i >= s) rec = make_int4(0, 0, 0, 0);
                         zsa[b] = zp_range((unsigned)rec.x) * (1.0 / 254.0);
                         zza[b] = (double)rec.y;
                         zrs[b] = (double)rec.z;
                     } else {
-                        sx[b] = (i < s) ? f16_bits_to_float(g.cx[i]) * (1.0f / 16129.0f) : 0.0f;
+                        const float cxi = f16_bits_to_float(g.cx[i < s ? i : s - 1]) * (1.0f / 16129.0f);
+                        sx[b] = (i < s) ? cxi : 0.0f;
                     }
                     xb[b][0] = cnt > 0 ? load_x_mem(i, 0) : (v8h)(0);
                     xb[b][1] = cnt > 16 ? load_x_mem(i, 16) : (v8h)(0);
@@ -602,7 +612,8 @@ __global__ void __launch_bounds__(128 * WQ, 1) gemm_prefill_kernel(const GemmArg
 #pragma unroll
                             for (int r = 0; r < 16; r++) {
                                 const int j = cJ0w + jl + 8 * (r >> 2) + 4 * gl + (r & 3);
-                                cwv[aa][r] = (j < o) ? f16_bits_to_float(g.cw[j]) : 0.0f;
+                                const float cwj = f16_bits_to_float(g.cw[j < o ? j : 0]);
+                                cwv[aa][r] = (j < o) ? cwj : 0.0f;
                             }
                         }
                         wa[aa][0] = cnt > 0 ? load_w_mem(cJ0w + jl + ll, 0) : (v8h)(0);
