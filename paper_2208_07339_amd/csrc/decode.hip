@@ -279,17 +279,19 @@ bool decode_kernel_takes(int s, int h, int o, bool zeropoint)
     if (s <= 32) {
         // Two workgroups of this kernel fit a compute unit, so a W of 2 to 4 column tiles per compute unit is
         // taken in two rounds, the second one part empty, while the tiled kernel has one 128 x 128 tile for
-        // each of more than half of the compute units.  Per call at 8 / 16 / 32 tokens: 30.5 / 32.5 / 34.9 us
-        // tiled against 32.3 / 34.4 / 39.5 on 5 120 x 20 480, 40.6 / 42.0 / 44.6 against 44.1 / 45.7 / 51.6 on
-        // 8 192 x 22 016, 49.0 / 51.3 / 54.5 against 54.6 / 56.6 / 65.1 on 12 288 x 20 480.  One tile per compute
+        // each of more than half of the compute units.  Per call at 8 / 16 / 32 tokens: 33.6 / 34.0 / 36.3 us
+        // tiled against 36.2 / 38.2 / 43.3 on 6 656 x 17 920, 47.4 / 48.1 / 49.2 against 49.6 / 51.2 / 57.3 on
+        // 8 192 x 28 672, 49.3 / 50.5 / 52.8 against 52.0 / 53.9 / 61.5 on 12 288 x 20 480.  One tile per compute
         // unit streams its 128 columns at what one compute unit can pull, which costs more the longer K is:
-        // with the second round at least half full and K above 8 192 this kernel stays ahead (58.2 / 60.2 /
-        // 68.4 against 70.5 / 73.6 / 75.7 us on 12 288 x 24 576), as it does outside the range (25.7 against
-        // 29.6 us at 15 360 columns, 66.8 against 71.0 at 36 864).
+        // with the second round at least half full and K above 8 192 this kernel stays ahead (55.7 / 57.0 /
+        // 64.6 against 68.8 / 73.0 / 75.0 us on 12 288 x 24 576), as it does with a full second round (32.0 /
+        // 33.3 / 38.2 against 34.4 / 35.7 / 39.3 on 4 096 x 32 768) and outside the range (23.6 against 29.6 us
+        // at 15 360 columns, 62.5 against 70.2 at 36 864).
         const int second = JT - 2 * cus;  // workgroups of the second round
         // (the zeropoint forms of the two kernels compare the same way: 39.1 against 44.3 us at 32 tokens on
         // 5 120 x 20 480, 55.9 against 68.0 on 8 192 x 28 672, 79.7 against 73.3 on 12 288 x 24 576)
-        if (forced < 0 && second > 0 && (o + 127) / 128 <= cus && (second < cus || h <= 8192)) return false;
+        if (forced < 0 && second > 0 && second < 2 * cus && (o + 127) / 128 <= cus && (second < cus || h <= 8192))
+            return false;
         return true;
     }
     return (JT + 1) / 2 >= 2 * cus;
