@@ -457,12 +457,25 @@ int llmint8_zp_linear(const void* X_f16, int s, int h, float alpha, const int8_t
         r = hip_status(launch_prepass_small(X_f16, s, h, threshold_bits(alpha), L, idx, cap, count, status, nullptr,
                                             (unsigned short*)Xo_f16, Xq, 0, (hipStream_t)stream, (int4*)zc_x, &job));
     } else {
-        r = llmint8_find_outliers(X_f16, s, h, alpha, idx, cap, count, status, ws, ws_bytes, stream);
-        if (r == LLMINT8_OK) r = llmint8_zp_quantize_rows(X_f16, s, h, idx, count, cap, Xq, zc_x, Xo_f16, stream);
+        // the column scan as llmint8_find_outliers runs it, without its last kernel: the kernel that takes the
+        // rows' ranges reads the column lists itself, writes idx / count / status, and carries the per-column
+        // factors of the matmul as extra workgroups
+        hipStream_t st = (hipStream_t)stream;
+        char* base = (char*)ws_base(ws);
+        const OutlierLists L = carve_outlier_lists(base, h, cap);
+        unsigned short* part = (unsigned short*)(base + scratch_ws(h, cap));
+        const int nslab = colmax_slabs(s, h);
+        const ColumnJob job = {Wq, zc_w, base + scan_ws(s, h, o, cap) + rows_ws(o, cap), o, zp_col_pitch(o)};
+        hipError_t e = launch_colmax_partial(X_f16, s, h, part, nslab, st);
+        if (e == hipSuccess) e = launch_outlier_lists(part, nslab, h, threshold_bits(alpha), L, cap, st);
+        if (e == hipSuccess)
+            e = launch_zp_quantize_rows_lists(X_f16, s, h, L, idx, count, status, cap, Xq, (int4*)zc_x,
+                                              (unsigned short*)Xo_f16, &job, st);
+        r = hip_status(e);
     }
     if (r == LLMINT8_OK)
         r = zp_matmul_impl(Xq, zc_x, Xo_f16, idx, count, cap, Wq, zc_w, W_f16, s, h, o, Out_f16, nullptr, ws, ws_bytes,
-                           stream, s <= 32 && cap <= JOB_MAX_CAP);
+                           stream, cap <= JOB_MAX_CAP);
     return r;
 }
 

@@ -170,6 +170,48 @@ inline OutlierLists carve_outlier_lists(char* base, int h, int cap)
     return L;
 }
 
+// Positions of the lists in the overall order.  Call with all 256 threads of a workgroup; s_cnt and
+// s_base are LDS arrays of MAXLISTS ints.  Returns the total number of qualifying columns.
+__device__ inline int scan_lists(const int* __restrict__ count, int nl, int* s_cnt, int* s_base)
+{
+    __shared__ int s_wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    int c[4], sum = 0;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int l = 4 * tid + q;
+        c[q] = l < nl ? count[l] : 0;
+        sum += c[q];
+    }
+    int incl = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int t = __shfl_up(incl, d);
+        if (lane >= d) incl += t;
+    }
+    __syncthreads();  // s_wsum may still be read by a previous call
+    if (lane == 63) s_wsum[w] = incl;
+    __syncthreads();
+    int woff = 0, total = 0;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        if (q < w) woff += s_wsum[q];
+        total += s_wsum[q];
+    }
+    int run = woff + incl - sum;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int l = 4 * tid + q;
+        if (l < nl) {
+            s_cnt[l] = c[q];
+            s_base[l] = run;
+        }
+        run += c[q];
+    }
+    __syncthreads();
+    return total;
+}
+
 // partial column maxima of an fp16 matrix M[rows][cols]: part[slab][cols] (u16 magnitude bits)
 int colmax_slabs(int rows, int cols);
 hipError_t launch_colmax_partial(const void* M, int rows, int cols, unsigned short* part, int nslab,
@@ -226,6 +268,9 @@ hipError_t launch_zp_quantize_weight(const void* W, int h, int o, int8_t* Wq, in
                                      hipStream_t st);
 hipError_t launch_zp_quantize_rows(const void* X, int s, int h, const int32_t* idx, const int32_t* count, int cap,
                                    int8_t* Xq, int4* zc, unsigned short* Xo, hipStream_t st);
+hipError_t launch_zp_quantize_rows_lists(const void* X, int s, int h, OutlierLists L, int32_t* idx, int32_t* count,
+                                         int32_t* status, int cap, int8_t* Xq, int4* zc, unsigned short* Xo,
+                                         const ColumnJob* cj, hipStream_t st);
 // colc: three planes of zp_col_pitch(o) doubles (see zp_kcol_kernel).  The pitch covers every column a
 // tile grid can touch (tiles are at most 256 columns wide), so the epilogues read it unguarded.
 __host__ __device__ inline int zp_col_pitch(int o) { return ((o + 255) & ~255) + 256; }

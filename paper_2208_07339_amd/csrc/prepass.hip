@@ -262,47 +262,7 @@ hipError_t launch_outlier_lists(const unsigned short* part, int nslab, int h, un
     return hipGetLastError();
 }
 
-// Positions of the lists in the overall order.  Call with all 256 threads of a workgroup; s_cnt and
-// s_base are LDS arrays of MAXLISTS ints.  Returns the total number of qualifying columns.
-__device__ inline int scan_lists(const int* __restrict__ count, int nl, int* s_cnt, int* s_base)
-{
-    __shared__ int s_wsum[4];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    int c[4], sum = 0;
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-        const int l = 4 * tid + q;
-        c[q] = l < nl ? count[l] : 0;
-        sum += c[q];
-    }
-    int incl = sum;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int t = __shfl_up(incl, d);
-        if (lane >= d) incl += t;
-    }
-    __syncthreads();  // s_wsum may still be read by a previous call
-    if (lane == 63) s_wsum[w] = incl;
-    __syncthreads();
-    int woff = 0, total = 0;
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-        if (q < w) woff += s_wsum[q];
-        total += s_wsum[q];
-    }
-    int run = woff + incl - sum;
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-        const int l = 4 * tid + q;
-        if (l < nl) {
-            s_cnt[l] = c[q];
-            s_base[l] = run;
-        }
-        run += c[q];
-    }
-    __syncthreads();
-    return total;
-}
+// (scan_lists(), the positions of the lists in the overall order, lives in common.h: zeropoint.hip uses it too)
 
 // idx, count, status from the lists (the stand-alone outlier scan ends with this)
 __global__ void __launch_bounds__(256) merge_lists_kernel(OutlierLists L, int nl, int capc, int32_t* __restrict__ idx,

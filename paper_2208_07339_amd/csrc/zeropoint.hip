@@ -145,36 +145,122 @@ hipError_t launch_zp_quantize_weight(const void* W, int h, int o, int8_t* Wq, in
 }
 
 // ---------------------------------------------------------------------------
+// The per-column factors of Eq. 5 for column j, three planes of `pitch` doubles (see zp_kcol_kernel, which
+// documents them).  idx[0 .. cnt): the outlier set, in global memory or in LDS.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void zp_col_factors(const int8_t* __restrict__ Wq, const int4* __restrict__ zcw, int h, int o,
+                                               int KT, const int32_t* idx, int cnt, int pitch,
+                                               double* __restrict__ colc, int j)
+{
+    double p = 0.0, q = 0.0, r = 0.0;
+    if (j < o) {
+        const int4 rec = zcw[j];
+        long long sum = rec.z;
+        int used = 0;
+        // eight codes per pass, requested without conditions so that they are in flight together (a slot past the
+        // count or with an index that does not exist reads row 0 and is skipped)
+        for (int t0 = 0; t0 < cnt; t0 += 8) {
+            int8_t q[8];
+            bool ok[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) {
+                const unsigned k = (unsigned)idx[t0 + u < cnt ? t0 + u : 0];
+                ok[u] = t0 + u < cnt && k < (unsigned)h;
+                const unsigned kk = ok[u] ? k : 0u;
+                q[u] = Wq[((size_t)(j >> 5) * KT + (kk >> 5)) * TILE_BYTES + tile_byte(j & 31, (int)(kk & 31))];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; u++)
+                if (ok[u]) {
+                    sum -= q[u];
+                    used++;
+                }
+        }
+        p = zp_range((unsigned)rec.x) * (1.0 / 254.0);
+        q = (double)rec.y * p;
+        r = (double)(sum + (long long)(h - used) * rec.y) * p;
+    }
+    colc[j] = p;
+    colc[(size_t)pitch + j] = q;
+    colc[2 * (size_t)pitch + j] = r;
+}
+
+// ---------------------------------------------------------------------------
 // Hidden states.  One workgroup per row: range over the non-outlier columns,
 // constants, and the gathered outlier columns Xo (as row_absmax_kernel).
+// LISTS: the outlier set comes straight from the column lists of the scan
+// (workgroup 0 then writes idx, count and status), and the workgroups past
+// the s rows, cj.pitch / 256 of them, make the per-column factors of Eq. 5
+// that would otherwise take a kernel of their own (cap <= JOB_MAX_CAP).
 // ---------------------------------------------------------------------------
+template <bool LISTS>
 __global__ void __launch_bounds__(256) zp_row_range_kernel(const unsigned short* __restrict__ X, int s, int h,
-                                                           const int32_t* __restrict__ idx,
-                                                           const int32_t* __restrict__ count, int cap, int opad,
-                                                           int4* __restrict__ zc, unsigned short* __restrict__ Xo,
-                                                           int vec_ok)
+                                                           int32_t* __restrict__ idx, int32_t* __restrict__ count,
+                                                           int32_t* __restrict__ status, OutlierLists L, int capc,
+                                                           int cap, int opad, int4* __restrict__ zc,
+                                                           unsigned short* __restrict__ Xo, int vec_ok, ColumnJob cj)
 {
     extern __shared__ unsigned bitmap[];  // ceil(h / 32) words, then 8 words of reduction space
+    __shared__ int s_cnt[LISTS ? MAXLISTS : 1], s_base[LISTS ? MAXLISTS : 1];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int nw = (h + 31) / 32;
     unsigned* red = bitmap + nw;
+    if constexpr (LISTS) {
+        if ((int)blockIdx.x >= s) {  // a column job: the outlier set into LDS first, then one column per thread
+            __shared__ int s_idx[JOB_MAX_CAP];
+            const int nl = (h + 255) / 256;
+            const int total = scan_lists(L.count, nl, s_cnt, s_base);
+            const int cnt = total < cap ? total : cap;
+            for (int b = tid; b < nl; b += 256) {
+                const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+                for (int e = 0; e < n && s_base[b] + e < cap; e++) s_idx[s_base[b] + e] = L.cand[(size_t)b * capc + e];
+            }
+            __syncthreads();
+            const int j = ((int)blockIdx.x - s) * 256 + tid;
+            if (j < cj.pitch)
+                zp_col_factors(cj.Wq, (const int4*)cj.wconst, h, cj.o, k_tiles(h), s_idx, cnt, cj.pitch,
+                               (double*)cj.out, j);
+            return;
+        }
+    }
     const int i = blockIdx.x;
     const unsigned short* row = X + (size_t)i * h;
     for (int q = tid; q < nw; q += 256) bitmap[q] = 0;
-    int cnt = *count;
-    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
-    __syncthreads();
-    for (int t = tid; t < cnt; t += 256) {
-        const unsigned j = (unsigned)idx[t];
-        if (j < (unsigned)h) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
-    }
-    for (int t = tid; t < opad; t += 256) {
-        unsigned short v = 0;
-        if (t < cnt) {
-            const unsigned j = (unsigned)idx[t];
-            if (j < (unsigned)h) v = row[j];
+    if constexpr (LISTS) {
+        const int nl = (h + 255) / 256;
+        const int total = scan_lists(L.count, nl, s_cnt, s_base);  // its barriers also publish the cleared bitmap
+        const int cnt = total < cap ? total : cap;
+        for (int b = tid; b < nl; b += 256) {
+            const int n = s_cnt[b] < capc ? s_cnt[b] : capc;
+            const int base = s_base[b];
+            for (int e = 0; e < n && base + e < cap; e++) {
+                const int j = L.cand[(size_t)b * capc + e];
+                atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+                Xo[(size_t)i * opad + base + e] = row[j];
+                if (i == 0) idx[base + e] = j;
+            }
         }
-        Xo[(size_t)i * opad + t] = v;
+        for (int t = cnt + tid; t < opad; t += 256) Xo[(size_t)i * opad + t] = 0;
+        if (i == 0 && tid == 0) {
+            *count = cnt;
+            if (status) *status = total > cap ? 1 : 0;
+        }
+    } else {
+        int cnt = *count;
+        cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
+        __syncthreads();
+        for (int t = tid; t < cnt; t += 256) {
+            const unsigned j = (unsigned)idx[t];
+            if (j < (unsigned)h) atomicOr(&bitmap[j >> 5], 1u << (j & 31));
+        }
+        for (int t = tid; t < opad; t += 256) {
+            unsigned short v = 0;
+            if (t < cnt) {
+                const unsigned j = (unsigned)idx[t];
+                if (j < (unsigned)h) v = row[j];
+            }
+            Xo[(size_t)i * opad + t] = v;
+        }
     }
     __syncthreads();
     unsigned kmin = 0xffffu, kmax = 0u;
@@ -322,8 +408,30 @@ hipError_t launch_zp_quantize_rows(const void* X, int s, int h, const int32_t* i
     const int KT = k_tiles(h), RT = row_tiles(s);
     const size_t shm = ((size_t)(h + 31) / 32 + 8) * sizeof(unsigned);
     const int vec_ok = (h % 8 == 0) && (((uintptr_t)X & 15) == 0);
-    zp_row_range_kernel<<<s, 256, shm, st>>>((const unsigned short*)X, s, h, idx, count, cap, opad_of(cap), zc, Xo,
-                                             vec_ok);
+    const OutlierLists none = {nullptr, nullptr, nullptr};
+    const ColumnJob nojob = {nullptr, nullptr, nullptr, 0, 0};
+    zp_row_range_kernel<false><<<s, 256, shm, st>>>((const unsigned short*)X, s, h, (int32_t*)idx, (int32_t*)count,
+                                                    nullptr, none, 0, cap, opad_of(cap), zc, Xo, vec_ok, nojob);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    zp_quantize_rows_kernel<<<dim3(RT, (KT * 32 + 255) / 256), 256, 0, st>>>((const unsigned short*)X, s, h, idx, count,
+                                                                            cap, zc, Xq, KT, vec_ok);
+    return hipGetLastError();
+}
+
+// the same fed by the column lists of the scan: also writes idx, count, status, and (cj, cap <= JOB_MAX_CAP)
+// the per-column factors of launch_zp_kcol
+hipError_t launch_zp_quantize_rows_lists(const void* X, int s, int h, OutlierLists L, int32_t* idx, int32_t* count,
+                                         int32_t* status, int cap, int8_t* Xq, int4* zc, unsigned short* Xo,
+                                         const ColumnJob* cj, hipStream_t st)
+{
+    const int KT = k_tiles(h), RT = row_tiles(s);
+    const size_t shm = ((size_t)(h + 31) / 32 + 8) * sizeof(unsigned);
+    const int vec_ok = (h % 8 == 0) && (((uintptr_t)X & 15) == 0);
+    const ColumnJob job = (cj && cap <= JOB_MAX_CAP) ? *cj : ColumnJob{nullptr, nullptr, nullptr, 0, 0};
+    zp_row_range_kernel<true><<<s + job.pitch / 256, 256, shm, st>>>((const unsigned short*)X, s, h, idx, count, status,
+                                                                     L, list_capacity(cap), cap, opad_of(cap), zc, Xo,
+                                                                     vec_ok, job);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     zp_quantize_rows_kernel<<<dim3(RT, (KT * 32 + 255) / 256), 256, 0, st>>>((const unsigned short*)X, s, h, idx, count,
@@ -346,39 +454,9 @@ __global__ void __launch_bounds__(256) zp_kcol_kernel(const int8_t* __restrict__
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= pitch) return;
-    double p = 0.0, q = 0.0, r = 0.0;
-    if (j < o) {
-        int cnt = *count;
-        cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
-        const int4 rec = zcw[j];
-        long long sum = rec.z;
-        int used = 0;
-        // eight codes per pass, requested without conditions so that they are in flight together (a slot past the
-        // count or with an index that does not exist reads row 0 and is skipped)
-        for (int t0 = 0; t0 < cnt; t0 += 8) {
-            int8_t q[8];
-            bool ok[8];
-#pragma unroll
-            for (int u = 0; u < 8; u++) {
-                const unsigned k = (unsigned)idx[t0 + u < cnt ? t0 + u : 0];
-                ok[u] = t0 + u < cnt && k < (unsigned)h;
-                const unsigned kk = ok[u] ? k : 0u;
-                q[u] = Wq[((size_t)(j >> 5) * KT + (kk >> 5)) * TILE_BYTES + tile_byte(j & 31, (int)(kk & 31))];
-            }
-#pragma unroll
-            for (int u = 0; u < 8; u++)
-                if (ok[u]) {
-                    sum -= q[u];
-                    used++;
-                }
-        }
-        p = zp_range((unsigned)rec.x) * (1.0 / 254.0);
-        q = (double)rec.y * p;
-        r = (double)(sum + (long long)(h - used) * rec.y) * p;
-    }
-    colc[j] = p;
-    colc[(size_t)pitch + j] = q;
-    colc[2 * (size_t)pitch + j] = r;
+    int cnt = *count;
+    cnt = cnt < 0 ? 0 : (cnt > cap ? cap : cnt);
+    zp_col_factors(Wq, zcw, h, o, KT, idx, cnt, pitch, colc, j);
 }
 
 hipError_t launch_zp_kcol(const int8_t* Wq, const int4* zcw, int h, int o, const int32_t* idx, const int32_t* count,

@@ -234,10 +234,12 @@ def test_more_outlier_columns_than_cap():
     assert_out_close(out.cpu().numpy().reshape(-1), Os)
 
 
-def test_short_x_in_one_call_with_an_outlier_buffer_too_large_for_the_column_job():
-    """cap > 256: the per-column factors come from zp_kcol_kernel as in the staged calls, not from the second
-    pre-pass kernel.  Same outputs as the staged calls, Out against the oracle."""
-    d = wl.make_custom(12, 264, 72, 5, seed=91)
+@pytest.mark.parametrize("s", [12, 70])
+def test_one_call_with_an_outlier_buffer_too_large_for_the_column_job(s):
+    """cap > 256: the per-column factors come from zp_kcol_kernel as in the staged calls, not from extra
+    workgroups of a pre-pass kernel (the short-X one for 12 tokens, the one that takes the rows' ranges for 70).
+    Same outputs as the staged calls, Out against the oracle."""
+    d = wl.make_custom(s, 264, 72, 5, seed=91)
     zp_compare(one_sided(d), d["W"], 6.0, cap=300)
 
 
