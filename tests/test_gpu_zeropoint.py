@@ -203,6 +203,29 @@ def test_prefill_13b_ffn_up_full_size():
     assert_out_close(out.cpu().numpy()[ri, ci], Os, float(np.abs(Os.astype(np.float64)).max()))
 
 
+@pytest.mark.parametrize("s", [24, 200])
+def test_codes_at_exact_ties(s):
+    """Every third row has the range D = 254 / 2^k and entries that are odd multiples of 2^-(k+1): each quotient
+    254 x / D is an integer plus one half, so each code is decided by the round-half-even rule alone (a
+    quotient that is off by one unit in the last place lands on the wrong side).  Codes, sums and the
+    product bit-exact as everywhere else; the rows in between are ordinary ones."""
+    rng = np.random.default_rng(400 + s)
+    h, o = 1040, 72
+    d = wl.make_custom(s, h, o, 3, seed=17)
+    X = one_sided(d)
+    free = [c for c in range(h) if c not in set(d["planted"].tolist())]
+    for i in range(0, s, 3):
+        k = int(rng.integers(5, 8))                              # D / 2 < 4: no new outlier columns
+        D = 254.0 / 2.0 ** k
+        row = (rng.integers(-127, 127, h) + 0.5) / 2.0 ** k      # |row| < D / 2, exact in fp16
+        row[free[0]], row[free[1]] = -D / 2, D / 2               # the row's range, exactly
+        keep = X[i, d["planted"]].copy()
+        X[i] = row.astype(np.float16)
+        assert np.array_equal(X[i].astype(np.float64), row)
+        X[i, d["planted"]] = keep
+    zp_compare(np.ascontiguousarray(X), d["W"], 6.0)
+
+
 def test_more_outlier_columns_than_cap():
     """Only the first cap columns count as outliers; the rest are quantized like any other column (their
     large entries then widen the row ranges).  The oracle is given exactly that set."""
